@@ -1,0 +1,168 @@
+/*
+ * sc.h — C ABI of the budgeted KV cache for autoregressive decoding on MI355X (gfx950).
+ *
+ * The library implements the per-step hot path of Scissorhands (arxiv 2305.17118):
+ *   - Alg. 1 (inference with a budget KV cache): every step appends one key/value row per
+ *     (sequence, head) unit; when the cache reaches its trigger size it must be compressed.
+ *   - Sec. 4.1 estimator: attention of one query over the n resident rows only.
+ *   - Alg. 2 (compress): importance record I = number of steps inside the history window
+ *     at which a row's attention probability was below 1/t, kept online during generation
+ *     as Sec. 4.1 "Overhead Tradeoff" allows; the r most recent rows are protected; the m
+ *     rows with the largest record are dropped; survivors are compacted, n <- n - m.
+ *
+ * General conventions
+ *   Units.     A unit is one (sequence, head) pair; U = batch*heads.  All units advance in
+ *              lock step, so the counters t (tokens seen) and n (resident rows) are host
+ *              integers and no call ever reads device memory back.
+ *   Memory.    Every pointer marked "device" is device memory owned by the caller and must
+ *              stay valid until the work enqueued by the call has run.  The library never
+ *              allocates or frees device memory; the cache lives in a caller-provided
+ *              workspace (256-byte aligned, sc_workspace_bytes() long) that must outlive
+ *              the handle.  The handle owns host metadata only.
+ *   Streams.   `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *              Calls only enqueue kernels on it and never synchronise.
+ *   Errors.    Functions return sc_status; nothing throws, aborts or prints.  On any error
+ *              the cache (t, n, device contents) is unchanged and out-params untouched.
+ *   Threads.   A handle is not thread-safe; distinct handles are independent.
+ *   Element types.  SC_KV_F32: q/k/v/out are float.  SC_KV_F16 and SC_KV_I4G64: q/k/v/out
+ *              are IEEE binary16.  All dot products, the softmax and the weighted value sum
+ *              accumulate in fp32; `out` is rounded to nearest-even on store.
+ */
+#ifndef SC_H_
+#define SC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sc_cache sc_cache; /* opaque, host side */
+
+typedef enum {
+    SC_OK = 0,
+    SC_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, m > trigger size - r, ...    */
+    SC_ERR_WORKSPACE = 2,   /* workspace too small or not 256-byte aligned                    */
+    SC_ERR_FULL = 3,        /* sc_decode_step while a compression is due                      */
+    SC_ERR_STATE = 4,       /* sc_compress when none is due; sc_prefill on a non-empty cache  */
+    SC_ERR_UNSUPPORTED = 5, /* head_dim / kv_dtype / history-not-multiple-of-drop not built   */
+    SC_ERR_DEVICE = 6       /* a kernel launch failed (hipGetLastError)                       */
+} sc_status;
+
+/* Storage format of the cached K/V rows. */
+typedef enum {
+    SC_KV_F32 = 0,  /* fp32 rows                                                              */
+    SC_KV_F16 = 1,  /* fp16 rows                                                              */
+    SC_KV_I4G64 = 2 /* 4-bit codes, asymmetric, one (scale, zero) fp16 pair per 64 channels   */
+} sc_kv_dtype;
+
+/* When Alg. 1 compresses.  Alg. 1 says "if n > B ... such that n <= B" and Alg. 2 removes
+ * exactly m rows, so the literal reading leaves B+1-m rows; Sec. 4.2 states the cache holds
+ * exactly B rows for m = 1.  Both readings are offered. */
+typedef enum {
+    SC_TRIGGER_HARD_CAP = 0,  /* compress when n == B+1; afterwards n == B+1-m (<= B)         */
+    SC_TRIGGER_HIGH_WATER = 1 /* compress when n == B+m; afterwards n == B exactly            */
+} sc_trigger;
+
+/* Threshold below which a probability counts as "low" (Alg. 2 uses 1/t; Sec. 3.1 motivates
+ * it as the average score). */
+typedef enum {
+    SC_THRESH_INV_POS = 0, /* 1/t, t = tokens seen so far including the current one (paper)   */
+    SC_THRESH_INV_LEN = 1  /* 1/n, n = resident rows (the true average over a compacted cache)*/
+} sc_thresh;
+
+/* Problem statement of Def. 4.1 / inputs of Alg. 1 and Alg. 2. */
+typedef struct {
+    int32_t batch, heads; /* U = batch*heads independent units                               */
+    int32_t head_dim;     /* d in {64, 128}                                                  */
+    int32_t kv_dtype;     /* sc_kv_dtype                                                     */
+    int32_t budget;       /* B: token budget per unit (Alg. 1)                               */
+    int32_t recent;       /* r: most recent rows never evicted (Alg. 2), r >= 1              */
+    int32_t history;      /* w: history window in steps (Alg. 2); must be a multiple of drop */
+    int32_t drop;         /* m: rows dropped per compression (Alg. 2), 1 <= m <= n_trig - r  */
+    int32_t trigger;      /* sc_trigger                                                      */
+    int32_t thresh_mode;  /* sc_thresh                                                       */
+    float scale;          /* score scale; 0 selects 1/sqrt(head_dim)                         */
+} sc_config;
+
+/* Derived sizes of a configuration (host only, no GPU needed).
+ *   n_trig   : number of resident rows at which a compression becomes due
+ *   capacity : row stride of every per-unit array (n_trig rounded up to a multiple of 64);
+ *              also the leading dimension of probs_out
+ *   buckets  : E = w/m counter buckets kept per row
+ * Returns SC_ERR_INVALID_ARG / SC_ERR_UNSUPPORTED for a bad configuration. */
+sc_status sc_config_sizes(const sc_config *cfg, int32_t *n_trig, int32_t *capacity, int32_t *buckets);
+
+/* Bytes of device workspace a cache of this configuration needs; 0 if cfg is invalid. */
+size_t sc_workspace_bytes(const sc_config *cfg);
+
+/* Where step number t (1-based count of tokens seen) falls in the counter schedule (host
+ * only).  Compressions happen at t = n_trig + k*m; `epoch` is the k of the next compression
+ * at or after t (may be negative), `bucket` = epoch mod E the counter bucket that step t
+ * increments, `counted` = 0 for steps so early that they have left every history window
+ * before the first compression.  The union of the E buckets at a compression step is
+ * exactly the history window (t-w, t] of Alg. 2. */
+sc_status sc_schedule(const sc_config *cfg, int64_t t, int64_t *epoch, int32_t *bucket, int32_t *counted);
+
+/* Create an empty cache (n = 0, t = 0) inside dev_workspace (device, 256-byte aligned,
+ * `bytes` >= sc_workspace_bytes(cfg)).  Enqueues a clear of the counters on `stream`. */
+sc_status sc_cache_create(const sc_config *cfg, void *dev_workspace, size_t bytes, void *stream,
+                          sc_cache **out);
+
+/* Free the host metadata.  The workspace is the caller's. */
+void sc_cache_destroy(sc_cache *c);
+
+/* One decode step (Alg. 1 loop body + Sec. 4.1 estimator + one update of the Alg. 2 record):
+ * append k_new/v_new as row n of every unit, attend q over the n+1 resident rows, add one
+ * to the record of every row whose probability is below the threshold, n <- n+1, t <- t+1.
+ *   q, k_new, v_new : device, U rows of head_dim elements; consecutive units are `in_stride`
+ *                     elements apart (0 = densely packed [batch, heads, head_dim])
+ *   out             : device, dense [batch, heads, head_dim]
+ *   probs_out       : device fp32 [U][capacity] or NULL; receives, for slots < n, exactly the
+ *                     probabilities the threshold test was applied to (slots >= n untouched)
+ *   compress_due    : host int or NULL; set to 1 when n has reached n_trig, i.e. the caller
+ *                     must call sc_compress before the next step, else 0
+ * SC_ERR_FULL if a compression is due. */
+sc_status sc_decode_step(sc_cache *c, const void *q, const void *k_new, const void *v_new,
+                         int64_t in_stride, void *out, float *probs_out, int32_t *compress_due,
+                         void *stream);
+
+/* Alg. 2 on every unit: select the m candidates (slots < n - r) with the largest record,
+ * equal records lowest slot first; compact K, V, positions and counters in place keeping
+ * order; n <- n - m.
+ *   evicted_out : device int32 [U][m] or NULL; the dropped slots (numbering before
+ *                 compaction) of each unit in ascending order
+ * SC_ERR_STATE unless the previous step reported compress_due. */
+sc_status sc_compress(sc_cache *c, int32_t *evicted_out, void *stream);
+
+/* Stream a prompt through Alg. 1 (Def. 4.1 treats prompt and generated tokens as one
+ * stream): for each of the prompt_len positions in order, one decode step, then a
+ * compression whenever one is due.  The cache must be empty.
+ *   q, k, v : device, [U][>= prompt_len][head_dim]; consecutive units are `unit_stride`
+ *             elements apart (0 = prompt_len*head_dim)
+ *   out     : device dense [U][prompt_len][head_dim], or NULL to discard the outputs */
+sc_status sc_prefill(sc_cache *c, const void *q, const void *k, const void *v, int32_t prompt_len,
+                     int64_t unit_stride, void *out, void *stream);
+
+/* Resident rows n and tokens seen t (either pointer may be NULL). */
+sc_status sc_cache_len(const sc_cache *c, int32_t *n, int64_t *t);
+
+/* Device pointers into the workspace, for inspection (any pointer may be NULL):
+ *   K, V    : [U][capacity] rows; F32/F16: head_dim elements; I4G64: head_dim/2 bytes of
+ *             codes, channel 2i in the low nibble of byte i
+ *   K_meta, V_meta : I4G64 only (else NULL): [U][capacity][head_dim/64] pairs of fp16
+ *             (scale, zero); value = code*scale + zero
+ *   pos     : int32 [U][capacity], 0-based position in the stream of the row in each slot
+ *   cnt     : uint16 [U][buckets][capacity]; a row's record I is the sum over buckets */
+sc_status sc_cache_view(const sc_cache *c, const void **K, const void **V, const void **K_meta,
+                        const void **V_meta, const int32_t **pos, const uint16_t **cnt,
+                        int32_t *capacity, int32_t *buckets);
+
+/* Static description of a status code. */
+const char *sc_status_str(sc_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SC_H_ */

@@ -1,0 +1,247 @@
+"""ctypes binding of ``libsc.so`` (the C ABI of ``include/sc.h``), same names, marshalling only.
+
+Device memory and streams come from PyTorch-ROCm: tensors are passed as ``data_ptr()`` and
+the stream as ``torch.cuda.current_stream().cuda_stream``.  Nothing is computed here; if the
+library is missing this module raises at first use, there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libsc.so")
+
+SC_OK, SC_ERR_INVALID_ARG, SC_ERR_WORKSPACE, SC_ERR_FULL, SC_ERR_STATE, SC_ERR_UNSUPPORTED, \
+    SC_ERR_DEVICE = range(7)
+SC_KV_F32, SC_KV_F16, SC_KV_I4G64 = 0, 1, 2
+SC_TRIGGER_HARD_CAP, SC_TRIGGER_HIGH_WATER = 0, 1
+SC_THRESH_INV_POS, SC_THRESH_INV_LEN = 0, 1
+
+EXPORTS = (
+    "sc_config_sizes", "sc_workspace_bytes", "sc_schedule", "sc_cache_create", "sc_cache_destroy",
+    "sc_decode_step", "sc_compress", "sc_prefill", "sc_cache_len", "sc_cache_view", "sc_status_str",
+)
+
+
+class sc_config(C.Structure):
+    _fields_ = [(k, C.c_int32) for k in (
+        "batch", "heads", "head_dim", "kv_dtype", "budget", "recent", "history", "drop",
+        "trigger", "thresh_mode")] + [("scale", C.c_float)]
+
+
+class ScError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (sc_status %d)" % (where, sc_status_str(status), status))
+
+
+_lib = None
+
+
+def lib():
+    """Load ``libsc.so`` (built by ``__graft_entry__.build()`` / ``build.py``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "libsc.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(hipcc --offload-arch=gfx950); there is no fallback implementation")
+    l = C.CDLL(LIB_PATH)
+    vp, i32p, i64p = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+    cfgp = C.POINTER(sc_config)
+    l.sc_config_sizes.argtypes = [cfgp, i32p, i32p, i32p]
+    l.sc_workspace_bytes.argtypes = [cfgp]
+    l.sc_workspace_bytes.restype = C.c_size_t
+    l.sc_schedule.argtypes = [cfgp, C.c_int64, i64p, i32p, i32p]
+    l.sc_cache_create.argtypes = [cfgp, vp, C.c_size_t, vp, C.POINTER(vp)]
+    l.sc_cache_destroy.argtypes = [vp]
+    l.sc_cache_destroy.restype = None
+    l.sc_decode_step.argtypes = [vp, vp, vp, vp, C.c_int64, vp, vp, i32p, vp]
+    l.sc_compress.argtypes = [vp, vp, vp]
+    l.sc_prefill.argtypes = [vp, vp, vp, vp, C.c_int32, C.c_int64, vp, vp]
+    l.sc_cache_len.argtypes = [vp, i32p, i64p]
+    l.sc_cache_view.argtypes = [vp] + [C.POINTER(vp)] * 6 + [i32p, i32p]
+    l.sc_status_str.argtypes = [C.c_int]
+    l.sc_status_str.restype = C.c_char_p
+    for name in EXPORTS:
+        if name not in ("sc_workspace_bytes", "sc_cache_destroy", "sc_status_str"):
+            getattr(l, name).restype = C.c_int
+    _lib = l
+    return l
+
+
+def _check(status: int, where: str):
+    if status != SC_OK:
+        raise ScError(status, where)
+
+
+def make_config(batch, heads, head_dim, kv_dtype, budget, recent, history, drop,
+                trigger=SC_TRIGGER_HARD_CAP, thresh_mode=SC_THRESH_INV_POS, scale=0.0) -> sc_config:
+    return sc_config(batch, heads, head_dim, kv_dtype, budget, recent, history, drop, trigger,
+                     thresh_mode, scale)
+
+
+# ---- functions with the names of the C ABI -------------------------------------------------
+
+def sc_status_str(status: int) -> str:
+    return lib().sc_status_str(int(status)).decode()
+
+
+def sc_config_sizes(cfg: sc_config):
+    """-> (n_trig, capacity, buckets)"""
+    a, b, c = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(lib().sc_config_sizes(C.byref(cfg), C.byref(a), C.byref(b), C.byref(c)), "sc_config_sizes")
+    return a.value, b.value, c.value
+
+
+def sc_workspace_bytes(cfg: sc_config) -> int:
+    return int(lib().sc_workspace_bytes(C.byref(cfg)))
+
+
+def sc_schedule(cfg: sc_config, t: int):
+    """-> (epoch, bucket, counted)"""
+    e, b, c = C.c_int64(), C.c_int32(), C.c_int32()
+    _check(lib().sc_schedule(C.byref(cfg), int(t), C.byref(e), C.byref(b), C.byref(c)), "sc_schedule")
+    return e.value, b.value, bool(c.value)
+
+
+def sc_cache_create(cfg: sc_config, workspace_ptr: int, nbytes: int, stream: int = 0):
+    h = C.c_void_p()
+    _check(lib().sc_cache_create(C.byref(cfg), workspace_ptr, nbytes, stream, C.byref(h)),
+           "sc_cache_create")
+    return h
+
+
+def sc_cache_destroy(handle) -> None:
+    lib().sc_cache_destroy(handle)
+
+
+def sc_decode_step(handle, q_ptr, k_ptr, v_ptr, in_stride, out_ptr, probs_ptr=None, stream=0) -> bool:
+    """-> compress_due"""
+    due = C.c_int32(0)
+    _check(lib().sc_decode_step(handle, q_ptr, k_ptr, v_ptr, int(in_stride), out_ptr, probs_ptr,
+                                C.byref(due), stream), "sc_decode_step")
+    return bool(due.value)
+
+
+def sc_compress(handle, evicted_ptr=None, stream=0) -> None:
+    _check(lib().sc_compress(handle, evicted_ptr, stream), "sc_compress")
+
+
+def sc_prefill(handle, q_ptr, k_ptr, v_ptr, prompt_len, unit_stride, out_ptr=None, stream=0) -> None:
+    _check(lib().sc_prefill(handle, q_ptr, k_ptr, v_ptr, int(prompt_len), int(unit_stride), out_ptr,
+                            stream), "sc_prefill")
+
+
+def sc_cache_len(handle):
+    """-> (n, t)"""
+    n, t = C.c_int32(), C.c_int64()
+    _check(lib().sc_cache_len(handle, C.byref(n), C.byref(t)), "sc_cache_len")
+    return n.value, t.value
+
+
+def sc_cache_view(handle):
+    """-> dict of raw device addresses plus capacity and buckets"""
+    ptrs = [C.c_void_p() for _ in range(6)]
+    cap, bk = C.c_int32(), C.c_int32()
+    _check(lib().sc_cache_view(handle, *[C.byref(p) for p in ptrs], C.byref(cap), C.byref(bk)),
+           "sc_cache_view")
+    names = ("K", "V", "K_meta", "V_meta", "pos", "cnt")
+    d = {k: (p.value or 0) for k, p in zip(names, ptrs)}
+    d["capacity"], d["buckets"] = cap.value, bk.value
+    return d
+
+
+# ---- a small holder that keeps the torch workspace alive next to the handle ----------------
+
+class BudgetCache:
+    """Owns a torch uint8 workspace tensor and the ``sc_cache`` handle living in it.
+
+    Marshalling only: every method forwards to the C entry point of the same name with the
+    tensors' device addresses and the current torch stream."""
+
+    def __init__(self, cfg: sc_config, device="cuda:0"):
+        import torch
+
+        self._torch = torch
+        self.cfg = cfg
+        self.device = torch.device(device)
+        self.n_trig, self.capacity, self.buckets = sc_config_sizes(cfg)
+        self.units = cfg.batch * cfg.heads
+        nbytes = sc_workspace_bytes(cfg)
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        base = self.workspace.data_ptr()
+        self._ws_ptr = (base + 255) // 256 * 256
+        self.io_dtype = torch.float32 if cfg.kv_dtype == SC_KV_F32 else torch.float16
+        self.handle = sc_cache_create(cfg, self._ws_ptr, nbytes, self._stream())
+        self._view = sc_cache_view(self.handle)
+
+    def _stream(self) -> int:
+        return int(self._torch.cuda.current_stream(self.device).cuda_stream)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            sc_cache_destroy(self.handle)
+            self.handle = None
+
+    __del__ = close
+
+    @property
+    def n(self):
+        return sc_cache_len(self.handle)[0]
+
+    @property
+    def t(self):
+        return sc_cache_len(self.handle)[1]
+
+    def decode_step(self, q, k_new, v_new, out, probs_out=None, in_stride=0) -> bool:
+        return sc_decode_step(self.handle, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), in_stride,
+                              out.data_ptr(), None if probs_out is None else probs_out.data_ptr(),
+                              self._stream())
+
+    def compress(self, evicted_out=None) -> None:
+        sc_compress(self.handle, None if evicted_out is None else evicted_out.data_ptr(), self._stream())
+
+    def prefill(self, q, k, v, prompt_len, unit_stride=0, out=None) -> None:
+        sc_prefill(self.handle, q.data_ptr(), k.data_ptr(), v.data_ptr(), prompt_len, unit_stride,
+                   None if out is None else out.data_ptr(), self._stream())
+
+    def _typed(self, key, dtype, shape):
+        """A torch view (no copy) of one of the cache's arrays inside the workspace."""
+        torch = self._torch
+        off = self._view[key] - self.workspace.data_ptr()
+        nbytes = int(torch.tensor([], dtype=dtype).element_size())
+        count = 1
+        for s in shape:
+            count *= s
+        return self.workspace[off: off + count * nbytes].view(dtype).view(*shape)
+
+    def pos(self):
+        return self._typed("pos", self._torch.int32, (self.units, self.capacity))
+
+    def cnt(self):
+        return self._typed("cnt", self._torch.int16, (self.units, self.buckets, self.capacity))
+
+    def kv_rows(self):
+        """(K, V) as stored: F32/F16 -> [U, C, d] tensors; I4G64 -> uint8 codes [U, C, d/2]."""
+        torch = self._torch
+        d = self.cfg.head_dim
+        if self.cfg.kv_dtype == SC_KV_I4G64:
+            shape, dt = (self.units, self.capacity, d // 2), torch.uint8
+        else:
+            shape, dt = (self.units, self.capacity, d), self.io_dtype
+        return self._typed("K", dt, shape), self._typed("V", dt, shape)
+
+    def kv_meta(self):
+        """I4G64 only: (K_meta, V_meta) as fp16 [U, C, d/64, 2] = (scale, zero)."""
+        torch = self._torch
+        shape = (self.units, self.capacity, self.cfg.head_dim // 64, 2)
+        return self._typed("K_meta", torch.float16, shape), self._typed("V_meta", torch.float16, shape)
+
+
+def kv_cache_bytes(layers: int, d_model: int, batch: int, seq: int, bytes_per_elem: int = 2) -> int:
+    """Bytes of a full (uncompressed) KV cache: two tensors of [batch, seq, d_model] per layer
+    (the accounting behind the memory table of the paper's introduction)."""
+    return 2 * layers * d_model * bytes_per_elem * batch * seq

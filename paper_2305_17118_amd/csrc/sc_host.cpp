@@ -1,0 +1,283 @@
+// Host side of the C ABI declared in include/sc.h: configuration checks, workspace carving,
+// and the lock-step state machine of Alg. 1 (t tokens seen, n resident rows, when a
+// compression is due, which counter bucket a step increments).  All device work is enqueued
+// through sc_kernels.hpp; nothing here reads device memory or synchronises.
+#include "../../include/sc.h"
+
+#include <cmath>
+#include <new>
+
+#include "sc_kernels.hpp"
+
+struct sc_cache {
+    sc_config cfg;
+    sc::Layout L;
+    int32_t n_trig;
+    int32_t n;
+    int64_t t;
+    float qk_log2;
+};
+
+namespace {
+
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Sizes {
+    int32_t n_trig, C, E;
+    size_t row_bytes, meta_bytes;  // per K (or V) row
+    size_t off_K, off_V, off_Km, off_Vm, off_pos, off_cnt, off_map, off_first, total;
+};
+
+sc_status derive(const sc_config* cfg, Sizes* s) {
+    if (!cfg) return SC_ERR_INVALID_ARG;
+    if (cfg->batch < 1 || cfg->heads < 1 || cfg->budget < 1 || cfg->recent < 1 || cfg->history < 1 ||
+        cfg->drop < 1)
+        return SC_ERR_INVALID_ARG;
+    if (cfg->trigger != SC_TRIGGER_HARD_CAP && cfg->trigger != SC_TRIGGER_HIGH_WATER)
+        return SC_ERR_INVALID_ARG;
+    if (cfg->thresh_mode != SC_THRESH_INV_POS && cfg->thresh_mode != SC_THRESH_INV_LEN)
+        return SC_ERR_INVALID_ARG;
+    if (!(cfg->scale >= 0.0f) || std::isinf(cfg->scale)) return SC_ERR_INVALID_ARG;
+    if ((int64_t)cfg->batch * cfg->heads > (1 << 24)) return SC_ERR_INVALID_ARG;
+    if (cfg->budget > (1 << 20) || cfg->drop > (1 << 20)) return SC_ERR_INVALID_ARG;
+    if (cfg->head_dim != 64 && cfg->head_dim != 128) return SC_ERR_UNSUPPORTED;
+    if (cfg->kv_dtype < SC_KV_F32 || cfg->kv_dtype > SC_KV_I4G64) return SC_ERR_UNSUPPORTED;
+    if (cfg->history % cfg->drop != 0) return SC_ERR_UNSUPPORTED;
+    if (cfg->history > 65535) return SC_ERR_UNSUPPORTED;  // records are 16-bit
+    const int64_t n_trig =
+        cfg->trigger == SC_TRIGGER_HIGH_WATER ? (int64_t)cfg->budget + cfg->drop : (int64_t)cfg->budget + 1;
+    if (cfg->drop > n_trig - cfg->recent) return SC_ERR_INVALID_ARG;
+    if (n_trig > 12288) return SC_ERR_UNSUPPORTED;  // one unit's scores must fit in LDS
+    s->n_trig = (int32_t)n_trig;
+    s->C = (int32_t)((n_trig + 63) / 64 * 64);
+    s->E = cfg->history / cfg->drop;
+    const size_t d = (size_t)cfg->head_dim;
+    s->row_bytes = cfg->kv_dtype == SC_KV_F32 ? d * 4 : cfg->kv_dtype == SC_KV_F16 ? d * 2 : d / 2;
+    s->meta_bytes = cfg->kv_dtype == SC_KV_I4G64 ? d / 64 * 4 : 0;
+    const size_t rows = (size_t)cfg->batch * cfg->heads * (size_t)s->C;
+    size_t off = 0;
+    s->off_K = off;     off = align_up(off + rows * s->row_bytes);
+    s->off_V = off;     off = align_up(off + rows * s->row_bytes);
+    s->off_Km = off;    off = align_up(off + rows * s->meta_bytes);
+    s->off_Vm = off;    off = align_up(off + rows * s->meta_bytes);
+    s->off_pos = off;   off = align_up(off + rows * 4);
+    s->off_cnt = off;   off = align_up(off + rows * (size_t)s->E * 2);
+    s->off_map = off;   off = align_up(off + rows * 4);
+    s->off_first = off; off = align_up(off + (size_t)cfg->batch * cfg->heads * 4);
+    s->total = off;
+    return SC_OK;
+}
+
+// ceil((t - n_trig) / m) for any sign.
+int64_t epoch_of(int64_t t, int64_t n_trig, int64_t m) {
+    const int64_t a = t - n_trig;
+    return a >= 0 ? (a + m - 1) / m : -((-a) / m);
+}
+
+int32_t bucket_of(int64_t epoch, int32_t E) { return (int32_t)(((epoch % E) + E) % E); }
+
+size_t elem_bytes(const sc_config& c) { return c.kv_dtype == SC_KV_F32 ? 4 : 2; }
+
+sc_status step_impl(sc_cache* c, const void* q, const void* k_new, const void* v_new, int64_t in_stride,
+                    void* out, int64_t out_stride, float* probs_out, hipStream_t stream) {
+    const int64_t t1 = c->t + 1;
+    const int32_t n1 = c->n + 1;
+    sc::StepArgs a;
+    a.q = q;
+    a.k_new = k_new;
+    a.v_new = v_new;
+    a.in_stride = (long)in_stride;
+    a.out = out;
+    a.out_stride = (long)out_stride;
+    a.probs = probs_out;
+    a.n = n1;
+    a.pos_value = (int)(t1 - 1);
+    const int64_t ep = epoch_of(t1, c->n_trig, c->cfg.drop);
+    a.bucket = bucket_of(ep, c->L.E);
+    a.counted = ep > -(int64_t)c->L.E;
+    a.qk_log2 = c->qk_log2;
+    a.tau = c->cfg.thresh_mode == SC_THRESH_INV_LEN ? 1.0f / (float)n1 : 1.0f / (float)t1;
+    if (sc::launch_decode_step(c->L, a, stream) != hipSuccess) return SC_ERR_DEVICE;
+    c->t = t1;
+    c->n = n1;
+    return SC_OK;
+}
+
+sc_status compress_impl(sc_cache* c, int32_t* evicted_out, hipStream_t stream) {
+    sc::CompressArgs a;
+    a.n = c->n;
+    a.r = c->cfg.recent;
+    a.m = c->cfg.drop;
+    // The step that made the cache full closed epoch k; the following steps count into k+1.
+    const int64_t ep = epoch_of(c->t, c->n_trig, c->cfg.drop);
+    a.zero_bucket = bucket_of(ep + 1, c->L.E);
+    a.evicted = evicted_out;
+    if (sc::launch_compress(c->L, a, stream) != hipSuccess) return SC_ERR_DEVICE;
+    c->n -= c->cfg.drop;
+    return SC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+sc_status sc_config_sizes(const sc_config* cfg, int32_t* n_trig, int32_t* capacity, int32_t* buckets) {
+    Sizes s;
+    const sc_status st = derive(cfg, &s);
+    if (st != SC_OK) return st;
+    if (n_trig) *n_trig = s.n_trig;
+    if (capacity) *capacity = s.C;
+    if (buckets) *buckets = s.E;
+    return SC_OK;
+}
+
+size_t sc_workspace_bytes(const sc_config* cfg) {
+    Sizes s;
+    return derive(cfg, &s) == SC_OK ? s.total : 0;
+}
+
+sc_status sc_schedule(const sc_config* cfg, int64_t t, int64_t* epoch, int32_t* bucket, int32_t* counted) {
+    Sizes s;
+    const sc_status st = derive(cfg, &s);
+    if (st != SC_OK) return st;
+    if (t < 1) return SC_ERR_INVALID_ARG;
+    const int64_t ep = epoch_of(t, s.n_trig, cfg->drop);
+    if (epoch) *epoch = ep;
+    if (bucket) *bucket = bucket_of(ep, s.E);
+    if (counted) *counted = ep > -(int64_t)s.E;
+    return SC_OK;
+}
+
+sc_status sc_cache_create(const sc_config* cfg, void* dev_workspace, size_t bytes, void* stream,
+                          sc_cache** out) {
+    if (!out) return SC_ERR_INVALID_ARG;
+    Sizes s;
+    const sc_status st = derive(cfg, &s);
+    if (st != SC_OK) return st;
+    if (!dev_workspace) return SC_ERR_INVALID_ARG;
+    if (bytes < s.total || (reinterpret_cast<uintptr_t>(dev_workspace) % kAlign) != 0)
+        return SC_ERR_WORKSPACE;
+    sc_cache* c = new (std::nothrow) sc_cache;
+    if (!c) return SC_ERR_INVALID_ARG;
+    c->cfg = *cfg;
+    char* base = static_cast<char*>(dev_workspace);
+    sc::Layout& L = c->L;
+    L.U = cfg->batch * cfg->heads;
+    L.d = cfg->head_dim;
+    L.kv_dtype = cfg->kv_dtype;
+    L.C = s.C;
+    L.E = s.E;
+    L.K = base + s.off_K;
+    L.V = base + s.off_V;
+    L.K_meta = s.meta_bytes ? base + s.off_Km : nullptr;
+    L.V_meta = s.meta_bytes ? base + s.off_Vm : nullptr;
+    L.pos = reinterpret_cast<int32_t*>(base + s.off_pos);
+    L.cnt = reinterpret_cast<uint16_t*>(base + s.off_cnt);
+    L.srcmap = reinterpret_cast<int32_t*>(base + s.off_map);
+    L.first = reinterpret_cast<int32_t*>(base + s.off_first);
+    c->n_trig = s.n_trig;
+    c->n = 0;
+    c->t = 0;
+    const float scale = cfg->scale > 0.0f ? cfg->scale : 1.0f / std::sqrt((float)cfg->head_dim);
+    c->qk_log2 = scale * 1.4426950408889634f;
+    if (sc::launch_clear_counters(L, static_cast<hipStream_t>(stream)) != hipSuccess) {
+        delete c;
+        return SC_ERR_DEVICE;
+    }
+    *out = c;
+    return SC_OK;
+}
+
+void sc_cache_destroy(sc_cache* c) { delete c; }
+
+sc_status sc_decode_step(sc_cache* c, const void* q, const void* k_new, const void* v_new,
+                         int64_t in_stride, void* out, float* probs_out, int32_t* compress_due,
+                         void* stream) {
+    if (!c || !q || !k_new || !v_new || !out) return SC_ERR_INVALID_ARG;
+    if (in_stride < 0 || (in_stride != 0 && in_stride < c->cfg.head_dim)) return SC_ERR_INVALID_ARG;
+    const size_t eb = elem_bytes(c->cfg);
+    if (in_stride != 0 && (in_stride * eb) % 16 != 0) return SC_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_new) |
+         reinterpret_cast<uintptr_t>(v_new) | reinterpret_cast<uintptr_t>(out)) % 16 != 0)
+        return SC_ERR_INVALID_ARG;
+    if (c->n >= c->n_trig) return SC_ERR_FULL;
+    const int64_t stride = in_stride ? in_stride : c->cfg.head_dim;
+    const sc_status st = step_impl(c, q, k_new, v_new, stride, out, c->cfg.head_dim, probs_out,
+                                   static_cast<hipStream_t>(stream));
+    if (st != SC_OK) return st;
+    if (compress_due) *compress_due = (c->n == c->n_trig);
+    return SC_OK;
+}
+
+sc_status sc_compress(sc_cache* c, int32_t* evicted_out, void* stream) {
+    if (!c) return SC_ERR_INVALID_ARG;
+    if (c->n != c->n_trig) return SC_ERR_STATE;
+    return compress_impl(c, evicted_out, static_cast<hipStream_t>(stream));
+}
+
+sc_status sc_prefill(sc_cache* c, const void* q, const void* k, const void* v, int32_t prompt_len,
+                     int64_t unit_stride, void* out, void* stream) {
+    if (!c || !q || !k || !v || prompt_len < 1) return SC_ERR_INVALID_ARG;
+    if (c->n != 0 || c->t != 0) return SC_ERR_STATE;
+    const int64_t d = c->cfg.head_dim;
+    const int64_t stride = unit_stride ? unit_stride : (int64_t)prompt_len * d;
+    if (stride < (int64_t)prompt_len * d) return SC_ERR_INVALID_ARG;
+    const size_t eb = elem_bytes(c->cfg);
+    if ((stride * eb) % 16 != 0) return SC_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k) | reinterpret_cast<uintptr_t>(v) |
+         reinterpret_cast<uintptr_t>(out)) % 16 != 0)
+        return SC_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int32_t i = 0; i < prompt_len; ++i) {
+        const size_t off = (size_t)i * d * eb;
+        void* o = out ? static_cast<char*>(out) + off : nullptr;
+        sc_status st = step_impl(c, static_cast<const char*>(q) + off, static_cast<const char*>(k) + off,
+                                 static_cast<const char*>(v) + off, stride, o, (int64_t)prompt_len * d,
+                                 nullptr, s);
+        if (st != SC_OK) return st;
+        if (c->n == c->n_trig) {
+            st = compress_impl(c, nullptr, s);
+            if (st != SC_OK) return st;
+        }
+    }
+    return SC_OK;
+}
+
+sc_status sc_cache_len(const sc_cache* c, int32_t* n, int64_t* t) {
+    if (!c) return SC_ERR_INVALID_ARG;
+    if (n) *n = c->n;
+    if (t) *t = c->t;
+    return SC_OK;
+}
+
+sc_status sc_cache_view(const sc_cache* c, const void** K, const void** V, const void** K_meta,
+                        const void** V_meta, const int32_t** pos, const uint16_t** cnt, int32_t* capacity,
+                        int32_t* buckets) {
+    if (!c) return SC_ERR_INVALID_ARG;
+    if (K) *K = c->L.K;
+    if (V) *V = c->L.V;
+    if (K_meta) *K_meta = c->L.K_meta;
+    if (V_meta) *V_meta = c->L.V_meta;
+    if (pos) *pos = c->L.pos;
+    if (cnt) *cnt = c->L.cnt;
+    if (capacity) *capacity = c->L.C;
+    if (buckets) *buckets = c->L.E;
+    return SC_OK;
+}
+
+const char* sc_status_str(sc_status s) {
+    switch (s) {
+        case SC_OK: return "ok";
+        case SC_ERR_INVALID_ARG: return "invalid argument";
+        case SC_ERR_WORKSPACE: return "workspace too small or misaligned";
+        case SC_ERR_FULL: return "cache full: a compression is due";
+        case SC_ERR_STATE: return "call not legal in the current cache state";
+        case SC_ERR_UNSUPPORTED: return "configuration not supported by this build";
+        case SC_ERR_DEVICE: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,59 @@
+// Internal interface between the host state machine (sc_host.cpp) and the gfx950 kernels.
+// Not part of the public ABI (that is include/sc.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sc {
+
+enum : int { KV_F32 = 0, KV_F16 = 1, KV_I4G64 = 2 };
+
+// Device addresses of one cache inside the caller's workspace.  Every per-unit array has a
+// row stride of `C` slots.
+struct Layout {
+    int U, d, kv_dtype;
+    int C;          // slots per unit (multiple of 64)
+    int E;          // counter buckets per slot
+    void* K;        // F32/F16: [U][C][d] elements; I4: [U][C][d/2] bytes of codes
+    void* V;
+    void* K_meta;   // I4 only: [U][C][d/64] x {fp16 scale, fp16 zero}
+    void* V_meta;
+    int32_t* pos;   // [U][C]
+    uint16_t* cnt;  // [U][E][C]
+    int32_t* srcmap;  // [U][C] scratch written by select, read by compact
+    int32_t* first;   // [U] scratch: first slot whose row moves
+};
+
+struct StepArgs {
+    const void* q;
+    const void* k_new;
+    const void* v_new;
+    long in_stride;   // elements between units in q/k_new/v_new
+    void* out;        // [U][d]
+    long out_stride;  // elements between units in out
+    float* probs;     // [U][C] or null
+    int n;            // resident rows including the one appended by this step
+    int pos_value;    // stream position of the appended row (t-1)
+    int bucket;       // counter bucket this step increments
+    int counted;      // 0: this step falls outside every history window, do not count
+    float qk_log2;    // score scale * log2(e)
+    float tau;        // low-score threshold
+};
+
+// Append the new row then attend (two launches on `stream`).
+hipError_t launch_decode_step(const Layout& L, const StepArgs& a, hipStream_t stream);
+
+struct CompressArgs {
+    int n;          // resident rows before compression (== trigger size)
+    int r, m;       // recent window, rows to drop
+    int zero_bucket;  // bucket the following epoch will count into (cleared here)
+    int32_t* evicted; // [U][m] or null
+};
+
+hipError_t launch_compress(const Layout& L, const CompressArgs& a, hipStream_t stream);
+
+// Zero all counters (cache creation).
+hipError_t launch_clear_counters(const Layout& L, hipStream_t stream);
+
+}  // namespace sc

@@ -1,0 +1,146 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle.
+
+Small shapes first (every storage type and head size, both trigger policies, both threshold
+modes, ragged row counts that do not fill a load tile, one to four counter buckets), then
+API-level behaviour (prefill == stepping, error codes leave the state untouched).
+The five full-size workloads are in test_gpu_workloads.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2305_17118_amd import binding as B
+from paper_2305_17118_amd.workloads import KV_F16, KV_F32, KV_I4G64, Workload, streams
+
+from .parity_util import ParityRun
+
+pytestmark = pytest.mark.gpu
+
+
+def _wl(name, batch, heads, d, kv, prompt, decode, budget, r, w, m, heavy=0.0, cid=90):
+    return Workload(name, cid, batch, heads, d, kv, prompt, decode, budget, r, w, m, heavy)
+
+
+SMALL = [
+    # name, batch, heads, d, kv, prompt, decode, B, r, w, m, heavy
+    _wl("f32-d64", 1, 3, 64, KV_F32, 100, 60, 40, 5, 16, 8),
+    _wl("f32-d128", 1, 2, 128, KV_F32, 90, 30, 37, 3, 12, 6),
+    _wl("f16-d128-ragged", 1, 5, 128, KV_F16, 150, 100, 100, 7, 32, 16, 0.05),
+    _wl("f16-d64", 2, 2, 64, KV_F16, 120, 40, 50, 4, 20, 10),
+    _wl("i4-d128", 1, 4, 128, KV_I4G64, 130, 60, 70, 6, 24, 12, 0.05),
+    _wl("i4-d64", 1, 3, 64, KV_I4G64, 100, 40, 45, 4, 16, 8),
+    _wl("drop-one", 1, 2, 128, KV_F16, 60, 40, 30, 1, 4, 1),
+    _wl("one-bucket", 1, 2, 64, KV_F32, 80, 40, 33, 2, 9, 9),
+    _wl("four-buckets", 1, 3, 128, KV_F16, 120, 80, 64, 8, 32, 8, 0.1),
+    _wl("long-window", 1, 2, 128, KV_F16, 90, 60, 20, 2, 64, 8),  # w > trigger size
+]
+
+
+@pytest.mark.parametrize("wl", SMALL, ids=lambda w: w.name)
+@pytest.mark.parametrize("trigger", [B.SC_TRIGGER_HARD_CAP, B.SC_TRIGGER_HIGH_WATER], ids=["cap", "hw"])
+def test_small_shapes_match_oracle(wl, trigger):
+    run = ParityRun(wl, trigger=trigger)
+    st = run.run()
+    assert st["steps"] == wl.total and st["compressions"] >= 3
+    n_after = wl.budget + 1 - wl.drop if trigger == B.SC_TRIGGER_HARD_CAP else wl.budget
+    assert run.cache.n_trig - wl.drop == n_after
+
+
+@pytest.mark.parametrize("kv,d", [(KV_F32, 64), (KV_F16, 128), (KV_I4G64, 128)])
+def test_threshold_on_resident_count_and_explicit_scale(kv, d):
+    wl = _wl("inv-len", 1, 3, d, kv, 80, 50, 36, 4, 16, 8, 0.05)
+    st = ParityRun(wl, thresh=B.SC_THRESH_INV_LEN, scale=0.11).run()
+    assert st["compressions"] >= 5
+
+
+@pytest.mark.parametrize("units,kv", [(1100, KV_F16), (2100, KV_F16), (1030, KV_I4G64), (2050, KV_F32)])
+def test_many_units_select_other_workgroup_shapes(units, kv):
+    """Unit counts on both sides of the points where the launcher changes the workgroup size."""
+    d = 64 if kv == KV_F32 else 128
+    wl = _wl("units-%d" % units, units // 10, 10, d, kv, 70, 30, 48, 5, 16, 16, 0.05)
+    sel = [0, 1, 63, 64, wl.units // 2, wl.units - 2, wl.units - 1]
+    st = ParityRun(wl, sel=sel).run()
+    assert st["compressions"] >= 3
+
+
+def test_budget_not_reached_is_full_attention():
+    wl = _wl("no-evict", 1, 4, 128, KV_F16, 40, 30, 128, 8, 32, 16)
+    run = ParityRun(wl)
+    st = run.run()
+    assert st["compressions"] == 0 and run.cache.n == 70
+    # textbook attention over everything seen so far, straight from the inputs
+    q, k, v = (a.astype(np.float64) for a in streams(wl))
+    lg = np.einsum("ud,utd->ut", q[:, -1], k) / np.sqrt(128)
+    p = np.exp(lg - lg.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    ref = np.einsum("ut,utd->ud", p, v)
+    got = run.out.float().cpu().numpy()
+    assert np.all(np.linalg.norm(got - ref, axis=1) <= 2e-3 * np.linalg.norm(ref, axis=1))
+
+
+def test_prefill_equals_stepping():
+    """sc_prefill is the prompt streamed through decode steps with a compression whenever one
+    is due: cache contents, counters, positions and outputs must be identical, bit for bit."""
+    wl = _wl("prefill", 2, 3, 128, KV_F16, 200, 0, 64, 8, 32, 16, 0.05)
+    q, k, v = (torch.from_numpy(a).cuda() for a in streams(wl))
+    cfg = B.make_config(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.budget, wl.recent, wl.history,
+                        wl.drop)
+    a, b = B.BudgetCache(cfg), B.BudgetCache(cfg)
+    T, d, U = wl.total, wl.head_dim, wl.units
+    out_a = torch.empty(U, T, d, dtype=torch.float16, device="cuda")
+    out_b = torch.zeros(U, T, d, dtype=torch.float16, device="cuda")
+    a.prefill(q, k, v, T, 0, out_a)
+    step_out = torch.empty(U, d, dtype=torch.float16, device="cuda")
+    for s in range(T):
+        due = b.decode_step(q[:, s], k[:, s], v[:, s], step_out, in_stride=T * d)
+        out_b[:, s] = step_out
+        if due:
+            b.compress()
+    assert (a.n, a.t) == (b.n, b.t)
+    n = a.n
+    assert torch.equal(out_a, out_b)
+    assert torch.equal(a.pos()[:, :n], b.pos()[:, :n])
+    assert torch.equal(a.cnt(), b.cnt())
+    Ka, Va = a.kv_rows()
+    Kb, Vb = b.kv_rows()
+    assert torch.equal(Ka[:, :n], Kb[:, :n]) and torch.equal(Va[:, :n], Vb[:, :n])
+    # a strided prompt (longer allocation than the prompt) gives the same cache
+    c = B.BudgetCache(cfg)
+    pad = torch.zeros(U, 8, d, dtype=torch.float16, device="cuda")
+    qq, kk, vv = (torch.cat([x, pad], dim=1).contiguous() for x in (q, k, v))
+    c.prefill(qq, kk, vv, T, (T + 8) * d, None)
+    assert torch.equal(a.pos()[:, :n], c.pos()[:, :n]) and torch.equal(a.cnt(), c.cnt())
+
+
+def test_error_codes_leave_state_untouched():
+    wl = _wl("errors", 1, 2, 64, KV_F32, 0, 0, 8, 2, 4, 4)
+    cfg = B.make_config(1, 2, 64, KV_F32, 8, 2, 4, 4)
+    c = B.BudgetCache(cfg)
+    x = torch.randn(2, 64, device="cuda")
+    out = torch.empty(2, 64, device="cuda")
+    with pytest.raises(B.ScError) as e:
+        c.compress()
+    assert e.value.status == B.SC_ERR_STATE
+    for i in range(9):
+        due = c.decode_step(x, x, x, out)
+        assert due == (i == 8)
+    assert (c.n, c.t) == (9, 9)
+    with pytest.raises(B.ScError) as e:
+        c.decode_step(x, x, x, out)
+    assert e.value.status == B.SC_ERR_FULL and (c.n, c.t) == (9, 9)
+    with pytest.raises(B.ScError) as e:
+        c.prefill(x, x, x, 1)
+    assert e.value.status == B.SC_ERR_STATE
+    with pytest.raises(B.ScError) as e:
+        B.sc_decode_step(c.handle, x.data_ptr() + 4, x.data_ptr(), x.data_ptr(), 0, out.data_ptr())
+    assert e.value.status == B.SC_ERR_INVALID_ARG
+    c.compress()
+    assert (c.n, c.t) == (5, 9)
+    with pytest.raises(B.ScError) as e:
+        B.sc_decode_step(c.handle, None, x.data_ptr(), x.data_ptr(), 0, out.data_ptr())
+    assert e.value.status == B.SC_ERR_INVALID_ARG and (c.n, c.t) == (5, 9)
+    fresh = B.BudgetCache(cfg)
+    with pytest.raises(B.ScError) as e:
+        fresh.prefill(x, x, x, 0)
+    assert e.value.status == B.SC_ERR_INVALID_ARG
+    torch.cuda.synchronize()

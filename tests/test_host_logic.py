@@ -1,0 +1,139 @@
+"""Host-side logic of the C-ABI library (no GPU needed): exported symbols, configuration
+checks, derived sizes, and the counter-bucket schedule that must reproduce the history window
+of Alg. 2 at every compression step."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2305_17118_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _cfg(**kw):
+    base = dict(batch=2, heads=4, head_dim=128, kv_dtype=B.SC_KV_F16, budget=64, recent=8,
+                history=32, drop=16)
+    base.update(kw)
+    return B.make_config(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "sc.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(sc_[a-z_0-9]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS), (declared ^ set(B.EXPORTS))
+    raw = ctypes.CDLL(B.LIB_PATH)
+    for name in sorted(declared):
+        assert getattr(raw, name) is not None
+
+
+def test_status_strings():
+    seen = {B.sc_status_str(s) for s in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+    assert B.sc_status_str(99) == "unknown status"
+
+
+@pytest.mark.parametrize("trigger,expect", [(B.SC_TRIGGER_HARD_CAP, 65), (B.SC_TRIGGER_HIGH_WATER, 80)])
+def test_sizes(trigger, expect):
+    n_trig, cap, E = B.sc_config_sizes(_cfg(trigger=trigger))
+    assert n_trig == expect and cap == 128 and E == 2
+    assert cap % 64 == 0 and cap >= n_trig
+
+
+def test_workspace_accounts_for_every_array():
+    for kv, row in ((B.SC_KV_F32, 512), (B.SC_KV_F16, 256), (B.SC_KV_I4G64, 64 + 8)):
+        cfg = _cfg(kv_dtype=kv)
+        _, cap, E = B.sc_config_sizes(cfg)
+        U = 8
+        need = U * cap * (2 * row + 4 + 2 * E + 4) + U * 4
+        got = B.sc_workspace_bytes(cfg)
+        assert need <= got <= need + 10 * 256
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(head_dim=96), B.SC_ERR_UNSUPPORTED),
+    (dict(kv_dtype=7), B.SC_ERR_UNSUPPORTED),
+    (dict(history=40), B.SC_ERR_UNSUPPORTED),      # w not a multiple of m
+    (dict(budget=16, recent=16, drop=16, history=16), B.SC_ERR_INVALID_ARG),  # m > n_trig - r
+    (dict(batch=0), B.SC_ERR_INVALID_ARG),
+    (dict(recent=0), B.SC_ERR_INVALID_ARG),
+    (dict(drop=0), B.SC_ERR_INVALID_ARG),
+    (dict(trigger=3), B.SC_ERR_INVALID_ARG),
+    (dict(thresh_mode=-1), B.SC_ERR_INVALID_ARG),
+    (dict(scale=-1.0), B.SC_ERR_INVALID_ARG),
+])
+def test_bad_configs(kw, status):
+    cfg = _cfg(**kw)
+    with pytest.raises(B.ScError) as e:
+        B.sc_config_sizes(cfg)
+    assert e.value.status == status
+    assert B.sc_workspace_bytes(cfg) == 0
+
+
+def test_create_rejects_bad_workspace_without_touching_the_gpu():
+    cfg = _cfg()
+    need = B.sc_workspace_bytes(cfg)
+    with pytest.raises(B.ScError) as e:
+        B.sc_cache_create(cfg, 0, need)
+    assert e.value.status == B.SC_ERR_INVALID_ARG
+    with pytest.raises(B.ScError) as e:
+        B.sc_cache_create(cfg, 4096, need - 1)
+    assert e.value.status == B.SC_ERR_WORKSPACE
+    with pytest.raises(B.ScError) as e:
+        B.sc_cache_create(cfg, 4096 + 16, need)
+    assert e.value.status == B.SC_ERR_WORKSPACE
+
+
+@pytest.mark.parametrize("B_,r,w,m,trigger", [
+    (256, 32, 64, 64, 0), (1024, 64, 256, 128, 0), (410, 64, 256, 128, 0), (683, 128, 512, 256, 1),
+    (20, 2, 12, 3, 0), (20, 2, 12, 3, 1), (9, 1, 5, 1, 0), (30, 4, 40, 8, 0),
+])
+def test_bucket_schedule_reproduces_the_history_window(B_, r, w, m, trigger):
+    """Simulate which steps each bucket holds.  At every compression step T_k the union of the
+    buckets must be exactly the last w steps (T_k - w, T_k] (those that exist), and the bucket
+    cleared after the compression must be the one holding the oldest epoch."""
+    cfg = _cfg(budget=B_, recent=r, history=w, drop=m, trigger=trigger)
+    n_trig, _, E = B.sc_config_sizes(cfg)
+    assert E == w // m
+    buckets = [set() for _ in range(E)]
+    n = 0
+    compressions = 0
+    for t in range(1, n_trig + 6 * m + 3):
+        epoch, b, counted = B.sc_schedule(cfg, t)
+        if counted:
+            buckets[b].add(t)
+        n += 1
+        if n == n_trig:
+            assert t == n_trig + compressions * m and epoch == compressions
+            held = set().union(*buckets)
+            assert held == set(range(max(1, t - w + 1), t + 1))
+            nxt_epoch, nxt_bucket, _ = B.sc_schedule(cfg, t + 1)
+            assert nxt_epoch == epoch + 1
+            # everything in the bucket that will be reused has left the next window
+            assert all(s <= t + m - w for s in buckets[nxt_bucket])
+            buckets[nxt_bucket].clear()
+            n -= m
+            compressions += 1
+    assert compressions >= 6
+
+
+def test_kv_cache_accounting_matches_the_papers_table():
+    rows = []
+    for line in open(os.path.join(ROOT, "tests", "golden", "kv_cache_table1.txt")):
+        if line.strip() and not line.startswith("#"):
+            name, layers, d_model, gb = line.split()
+            rows.append((name, int(layers), int(d_model), int(gb)))
+    got = {name: B.kv_cache_bytes(L, d, batch=128, seq=2048) / 2 ** 30 for name, L, d, _ in rows}
+    printed = {name: gb for name, _, _, gb in rows}
+    assert got["OPT-175B"] == printed["OPT-175B"] == 1152
+    assert got["LLaMA-65B"] == printed["LLaMA-65B"] == 640
+    assert got["BLOOM"] == 980  # the paper prints 950 for this row
+
+
+def test_compression_ratio_of_the_workloads():
+    """Budget / full length gives the compression labels of the five workloads."""
+    from paper_2305_17118_amd.workloads import CONFIGS
+    ratios = [round(2048 / c.budget) for c in CONFIGS]
+    assert ratios[1:] == [2, 5, 3, 3]
