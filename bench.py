@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Decode throughput of the budgeted KV cache on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch: sc_decode_step (append + budgeted
+attention + importance-record update, one kernel) followed by sc_compress whenever the cache
+has reached its trigger size.  The workload is the OPT-6.7B-shaped single layer (batch 16,
+32 heads, head_dim 128, fp16, 1024-token prompt streamed through the cache, then decoding
+under budget 1024).  Because one layer's cache (269 MB) is about the size of the chip's
+last-level cache and is re-read every step, R independent cache instances are stepped
+round-robin (as the layers of a model would be), so every step finds its cache cold in HBM.
+tokens/s = batch * steps / wall time, a step being one layer-instance step.
+
+Prints ONE JSON line (see the design doc for the field definitions).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(wl, n: int) -> int:
+    """Bytes one decode-attention launch must move when n rows are resident after the append:
+    per unit, n rows of K and of V (plus their 4-bit scale/zero words), a 2-byte counter read
+    and written per row, and the q / k_new / v_new / out vectors."""
+    from paper_2305_17118_amd.workloads import KV_F32, KV_F16
+    d = wl.head_dim
+    if wl.kv_dtype == KV_F32:
+        row, e_io = d * 4, 4
+    elif wl.kv_dtype == KV_F16:
+        row, e_io = d * 2, 2
+    else:
+        row, e_io = d // 2 + (d // 64) * 4, 2
+    return wl.units * (n * (2 * row + 4) + 4 * d * e_io)
+
+
+def cpu_baseline(wl, sample_units: int, sample_steps: int) -> dict:
+    """Time the CPU oracle, as it stands, on a bounded sample of the same workload: the first
+    `sample_units` units, full streamed prompt (untimed), then `sample_steps` decode steps with
+    their compressions (timed).  Scaled linearly to the full unit count (units are independent
+    and identically distributed)."""
+    from oracle.sco import Oracle, OracleConfig
+    from paper_2305_17118_amd.workloads import streams
+
+    units = list(range(min(sample_units, wl.units)))
+    cores = os.cpu_count() or 1
+    q, k, v = streams(wl, units, steps=wl.prompt + sample_steps, threads=min(cores, 16))
+    o = Oracle(OracleConfig(1, len(units), wl.head_dim, wl.kv_dtype, wl.budget, wl.recent, wl.history,
+                            wl.drop), nthreads=cores)
+    for s in range(wl.prompt):
+        _, _, due = o.step(q[:, s], k[:, s], v[:, s], want_probs=False)
+        if due:
+            o.compress()
+    t0 = time.perf_counter()
+    for s in range(wl.prompt, wl.prompt + sample_steps):
+        _, _, due = o.step(q[:, s], k[:, s], v[:, s], want_probs=False)
+        if due:
+            o.compress()
+    dt = time.perf_counter() - t0
+    frac = len(units) / wl.units
+    return {
+        "value": wl.batch * sample_steps / (dt / frac),
+        "unit": "tokens/s",
+        "cores": min(cores, len(units)),
+        "kind": "oracle",
+        "sample": "%d of %d units, %d decode steps after the full %d-token streamed prompt, "
+                  "%.1f s of CPU time measured, scaled by unit count" % (
+                      len(units), wl.units, sample_steps, wl.prompt, dt),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1500)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = headline)")
+    ap.add_argument("--rotate", type=int, default=0, help="cache instances stepped round-robin "
+                    "(0 = enough to cover three times the 256 MB last-level cache)")
+    ap.add_argument("--no-events", action="store_true", help="skip the per-launch HIP events")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-units", type=int, default=64)
+    ap.add_argument("--cpu-steps", type=int, default=384)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (units are independent, so sharding over "
+              "GPUs needs no collective and is not part of this build); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2305_17118_amd import binding as B
+    from paper_2305_17118_amd.workloads import CONFIGS, KV_F32, KV_F16, streams
+
+    wl = CONFIGS[args.config - 1]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = B.make_config(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.budget, wl.recent, wl.history,
+                        wl.drop)
+    ws_bytes = B.sc_workspace_bytes(cfg)
+    R = args.rotate or max(1, -(-3 * 256 * 2 ** 20 // ws_bytes))
+    T, d, U = wl.total, wl.head_dim, wl.units
+    steps_avail = R * wl.decode
+    K, W = args.steps, args.warmup
+    if W + K > steps_avail:
+        K = steps_avail - W
+        print("bench.py: only %d decode steps exist for %d instances; timing %d" % (steps_avail, R, K),
+              file=sys.stderr)
+
+    q, k, v = (torch.from_numpy(a).to(dev) for a in streams(wl, threads=16))
+    caches = [B.BudgetCache(cfg, dev) for _ in range(R)]
+    outs = [torch.empty(U, d, dtype=caches[0].io_dtype, device=dev) for _ in range(R)]
+    for c in caches:
+        c.prefill(q, k, v, wl.prompt, T * d, None)
+    torch.cuda.synchronize()
+
+    cursor = [wl.prompt] * R
+    n_log = []
+
+    def one_step(i, ev=None):
+        r = i % R
+        s = cursor[r]
+        cursor[r] = s + 1
+        c = caches[r]
+        if ev is not None:
+            ev[0].record()
+        due = c.decode_step(q[:, s], k[:, s], v[:, s], outs[r], None, in_stride=T * d)
+        if ev is not None:
+            ev[1].record()
+        n_log.append(c.n)
+        if due:
+            c.compress()
+        return due
+
+    for i in range(W):
+        one_step(i)
+    n_log.clear()
+    use_events = not args.no_events
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(K)] if use_events else None
+    compress_events = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        compress_events += one_step(W + i, events[i] if use_events else None)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    alg = sum(algorithmic_bytes(wl, n) for n in n_log) / len(n_log)
+    if use_events:
+        kern_ms = sum(a.elapsed_time(b) for a, b in events) / K
+        achieved = alg / (kern_ms * 1e-3) / 1e9
+    else:
+        kern_ms, achieved = None, None
+    kernel_name = "attn_i4_kernel" if wl.kv_dtype not in (KV_F32, KV_F16) else "attn_rows_kernel"
+    res = {
+        "metric": "decode tokens/s with budgeted KV cache",
+        "value": wl.batch * K / wall,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": wall / K * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": {0: "f32", 1: "f16", 2: "i4+f16"}[wl.kv_dtype],
+        "data": "synthetic",
+        "config": {
+            "workload": wl.name, "batch": wl.batch, "heads": wl.heads, "head_dim": wl.head_dim,
+            "prompt": wl.prompt, "decode": wl.decode, "budget": wl.budget, "recent": wl.recent,
+            "history": wl.history, "drop": wl.drop, "trigger": "hard_cap",
+            "cache_instances_round_robin": R, "compressions_in_timed_region": compress_events,
+            "resident_rows_avg": sum(n_log) / len(n_log),
+        },
+        "roofline": {
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": None if achieved is None else achieved / HBM_PEAK_GBS, "traffic": None,
+            "kernel": kernel_name, "kernel_ms_avg": kern_ms, "algorithmic_bytes_per_launch": alg,
+        },
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(wl, args.cpu_units, args.cpu_steps)
+    print(json.dumps(res))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -308,14 +308,15 @@ static void step_unit(void *vctx, int u) {
     memset(low + (size_t)slot * w, 0, (size_t)w);
 
     /* Sec. 4.1 estimator: scores over resident rows, softmax, weighted value sum. */
-    double *s = (double *)malloc(sizeof(double) * (size_t)n);
+    double *s = (double *)malloc(sizeof(double) * (size_t)(n + d));
+    double *qd = s + n; /* this unit's query, widened once */
+    for (int ch = 0; ch < d; ++ch)
+        qd[ch] = (double)load_elem(c->q, h->cfg.kv_dtype == SCO_F32 ? SCO_F32 : SCO_F16,
+                                   (size_t)u * d + (size_t)ch);
     double mx = -INFINITY;
     for (int j = 0; j < n; ++j) {
         double acc = 0.0;
-        for (int ch = 0; ch < d; ++ch)
-            acc += (double)load_elem(c->q, h->cfg.kv_dtype == SCO_F32 ? SCO_F32 : SCO_F16,
-                                     (size_t)u * d + (size_t)ch) *
-                   (double)K[(size_t)j * d + ch];
+        for (int ch = 0; ch < d; ++ch) acc += qd[ch] * (double)K[(size_t)j * d + ch];
         s[j] = h->scale * acc;
         if (s[j] > mx) mx = s[j];
     }

@@ -2,7 +2,10 @@
 // attention estimator of Sec. 4.1 with the Alg. 2 importance record updated in the softmax
 // epilogue (the online variant of Sec. 4.1 "Overhead Tradeoff").
 //
-// One workgroup owns one (sequence, head) unit.  K and V rows are streamed exactly once,
+// One workgroup owns one (sequence, head) unit and does the whole step for it in a single
+// launch: the new row is taken from k_new/v_new (quantised first for 4-bit storage), written
+// to its slot and attended to from registers / LDS, so nothing is read back from a slot
+// written in the same launch.  K and V rows already resident are streamed exactly once,
 // together, with 16-byte loads per lane; a row of 16*LPR bytes is spread over LPR adjacent
 // lanes, so one wave instruction fetches 64/LPR whole rows (1 KiB, fully coalesced).  Each
 // lane group keeps a running softmax (max, sum, weighted value partial) that is rescaled only
@@ -35,17 +38,21 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 struct AttnArgs {
     const void* q;
-    long q_stride;
+    const void* k_new;
+    const void* v_new;
+    long in_stride;  // elements between units in q, k_new and v_new
     const void* K;
     const void* V;
     const void* K_meta;
     const void* V_meta;
+    int32_t* pos;
+    int pos_value;
     void* out;
     long out_stride;
     float* probs;
     uint16_t* cnt;  // current bucket of unit 0
     long cnt_unit_stride;
-    int n, C;
+    int n, C;  // n counts the row appended by this launch
     float qk_log2, tau;
     int counted;
 };
@@ -56,18 +63,49 @@ union Frag {
     T e[N];
 };
 
-// Merge the running softmax of lane groups / waves: (m, l, acc) <- combine with (mo, lo, acco).
-__device__ __forceinline__ void merge_scales(float m, float mo, float& mn, float& a, float& b) {
-    mn = fmaxf(m, mo);
-    a = (m == mn) ? 1.0f : fast_exp2(m - mn);
-    b = (mo == mn) ? 1.0f : fast_exp2(mo - mn);
-}
+// Running softmax of one lane group: m = max score so far (log2 domain), l = sum of
+// exp2(score - m), acc = sum of exp2(score - m) * value fragment.
+template <int N>
+struct Running {
+    float m, l, acc[N];
+    __device__ __forceinline__ void init() {
+        m = -INFINITY;
+        l = 0.f;
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] = 0.f;
+    }
+    // Account for one row with score s; returns its weight exp2(s - m) (0 when !valid).
+    __device__ __forceinline__ float admit(float s, bool valid) {
+        if (valid && s > m) {
+            const float al = fast_exp2(m - s);
+            l *= al;
+#pragma unroll
+            for (int i = 0; i < N; ++i) acc[i] *= al;
+            m = s;
+        }
+        const float e = valid ? fast_exp2(s - m) : 0.f;
+        l += e;
+        return e;
+    }
+    // Merge with the lane `off` away (both lanes end with the merged state).
+    __device__ __forceinline__ void merge_xor(int off) {
+        const float mo = __shfl_xor(m, off), lo = __shfl_xor(l, off);
+        const float mn = fmaxf(m, mo);
+        const float sa = (m == mn) ? 1.0f : fast_exp2(m - mn);
+        const float sb = (mo == mn) ? 1.0f : fast_exp2(mo - mn);
+        l = l * sa + lo * sb;
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] = acc[i] * sa + __shfl_xor(acc[i], off) * sb;
+        m = mn;
+    }
+};
 
 // Shared tail of both attention kernels: combine the per-wave partials, write `out`, then the
 // probability epilogue with the counter update.
 template <typename TOut, int D, int NW>
-__device__ __forceinline__ void finish_unit(const AttnArgs& a, int u, float* s_lds, float* part_m,
-                                            float* part_l, float* part_acc) {
+__device__ __forceinline__ void finish_unit(const AttnArgs& a, int u, const float* s_lds,
+                                            const float* part_m, const float* part_l,
+                                            const float* part_acc) {
     const int tid = threadIdx.x;
     float M = part_m[0];
 #pragma unroll
@@ -109,69 +147,69 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
     const int u = blockIdx.x;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int g = lane / LPR, c = lane % LPR;
-    const int n = a.n;
-    const T* Ku = (const T*)a.K + (size_t)u * a.C * D + c * EPL;
-    const T* Vu = (const T*)a.V + (size_t)u * a.C * D + c * EPL;
+    const int nc = a.n - 1;  // rows resident before this step; the new row goes to slot nc
+    T* Ku = (T*)a.K + (size_t)u * a.C * D + c * EPL;
+    T* Vu = (T*)a.V + (size_t)u * a.C * D + c * EPL;
+    const size_t in_off = (size_t)u * a.in_stride + c * EPL;
 
     float qf[EPL];
     {
         Frag<T, EPL> qr;
-        qr.raw = *reinterpret_cast<const uint4*>((const T*)a.q + (size_t)u * a.q_stride + c * EPL);
+        qr.raw = *reinterpret_cast<const uint4*>((const T*)a.q + in_off);
 #pragma unroll
         for (int i = 0; i < EPL; ++i) qf[i] = (float)qr.e[i] * a.qk_log2;
     }
-    float m = -INFINITY, l = 0.f, acc[EPL];
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
+    // Alg. 1 model update: the first lane group of wave 0 owns the new row.
+    const bool owner = (wv == 0) && (g == 0);
+    Frag<T, EPL> k_own, v_own;
+    k_own.raw = make_uint4(0, 0, 0, 0);
+    v_own.raw = make_uint4(0, 0, 0, 0);
+    if (owner) {
+        k_own.raw = *reinterpret_cast<const uint4*>((const T*)a.k_new + in_off);
+        v_own.raw = *reinterpret_cast<const uint4*>((const T*)a.v_new + in_off);
+        *reinterpret_cast<uint4*>(Ku + (size_t)nc * D) = k_own.raw;
+        *reinterpret_cast<uint4*>(Vu + (size_t)nc * D) = v_own.raw;
+        if (c == 0) a.pos[(size_t)u * a.C + nc] = a.pos_value;
+    }
 
-    for (int base = wv * CHUNK; base < n; base += NW * CHUNK) {
+    Running<EPL> run;
+    run.init();
+    auto take_row = [&](const Frag<T, EPL>& kr, const Frag<T, EPL>& vr, int j, bool valid) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) s = fmaf((float)kr.e[i], qf[i], s);
+        s = group_sum<LPR>(s);
+        if (valid && c == 0) s_lds[j] = s;
+        const float e = run.admit(s, valid);
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) run.acc[i] = fmaf(e, (float)vr.e[i], run.acc[i]);
+    };
+
+    for (int base = wv * CHUNK; base < nc; base += NW * CHUNK) {
         Frag<T, EPL> kr[UNR], vr[UNR];
 #pragma unroll
         for (int x = 0; x < UNR; ++x) {
             const int j = base + x * RPW + g;
-            const int jj = j < n ? j : n - 1;
+            const int jj = j < nc ? j : 0;
             kr[x].raw = *reinterpret_cast<const uint4*>(Ku + (size_t)jj * D);
             vr[x].raw = *reinterpret_cast<const uint4*>(Vu + (size_t)jj * D);
         }
 #pragma unroll
         for (int x = 0; x < UNR; ++x) {
             const int j = base + x * RPW + g;
-            const bool valid = j < n;
-            float s = 0.f;
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) s = fmaf((float)kr[x].e[i], qf[i], s);
-            s = group_sum<LPR>(s);
-            if (valid && c == 0) s_lds[j] = s;
-            if (valid && s > m) {
-                const float al = fast_exp2(m - s);
-                l *= al;
-#pragma unroll
-                for (int i = 0; i < EPL; ++i) acc[i] *= al;
-                m = s;
-            }
-            const float e = valid ? fast_exp2(s - m) : 0.f;
-            l += e;
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) acc[i] = fmaf(e, (float)vr[x].e[i], acc[i]);
+            take_row(kr[x], vr[x], j, j < nc);
         }
     }
-    // lane groups of one wave
+    if (wv == 0) take_row(k_own, v_own, nc, owner);
+
 #pragma unroll
-    for (int off = LPR; off < 64; off <<= 1) {
-        const float mo = __shfl_xor(m, off), lo = __shfl_xor(l, off);
-        float mn, sa, sb;
-        merge_scales(m, mo, mn, sa, sb);
-        l = l * sa + lo * sb;
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) acc[i] = acc[i] * sa + __shfl_xor(acc[i], off) * sb;
-        m = mn;
-    }
+    for (int off = LPR; off < 64; off <<= 1) run.merge_xor(off);
     if (g == 0) {
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) part_acc[wv * D + c * EPL + i] = acc[i];
+        for (int i = 0; i < EPL; ++i) part_acc[wv * D + c * EPL + i] = run.acc[i];
         if (c == 0) {
-            part_m[wv] = m;
-            part_l[wv] = l;
+            part_m[wv] = run.m;
+            part_l[wv] = run.l;
         }
     }
     __syncthreads();
@@ -184,164 +222,19 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
 //   <q, k>   = sum_groups scale_g * sum_c q_c*code_c + zero_g * sum_c q_c
 //   sum_j p_j v_j[c] = sum_j (p_j*scale_jg) * code_jc + sum_j p_j*zero_jg
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ float2 unpack_meta(uint32_t w) {
-    union {
-        uint32_t u;
-        _Float16 h[2];
-    } cv;
-    cv.u = w;
-    return make_float2((float)cv.h[0], (float)cv.h[1]);
-}
+union MetaWord {
+    uint32_t u32;
+    _Float16 h[2];  // scale, zero
+};
 
-template <int D, int NW, int UNR>
-__global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
-    constexpr int LPR = D / 32;
-    constexpr int RPW = 64 / LPR;
-    constexpr int GPR = D / 64;  // groups per row
-    constexpr int CHUNK = RPW * UNR;
-    constexpr int ROWB = D / 2;  // bytes of codes per row
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    float* s_lds = reinterpret_cast<float*>(smem_raw);
-    float* part_m = s_lds + a.C;
-    float* part_l = part_m + NW;
-    float* part_acc = part_l + NW;
-
-    const int u = blockIdx.x;
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int g = lane / LPR, c = lane % LPR;
-    const int gi = c / 2;  // 64-channel group this lane's 32 channels fall in
-    const int n = a.n;
-    const unsigned char* Ku = (const unsigned char*)a.K + (size_t)u * a.C * ROWB + c * 16;
-    const unsigned char* Vu = (const unsigned char*)a.V + (size_t)u * a.C * ROWB + c * 16;
-    const uint32_t* Km = (const uint32_t*)a.K_meta + (size_t)u * a.C * GPR + gi;
-    const uint32_t* Vm = (const uint32_t*)a.V_meta + (size_t)u * a.C * GPR + gi;
-
-    float qf[32];
-    float qsum = 0.f;
-    {
-        const _Float16* qu = (const _Float16*)a.q + (size_t)u * a.q_stride + c * 32;
-#pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) {
-            Frag<_Float16, 8> qr;
-            qr.raw = *reinterpret_cast<const uint4*>(qu + v4 * 8);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                qf[v4 * 8 + i] = (float)qr.e[i] * a.qk_log2;
-                qsum += qf[v4 * 8 + i];
-            }
-        }
-    }
-    float m = -INFINITY, l = 0.f, zacc = 0.f, acc[32];
-#pragma unroll
-    for (int i = 0; i < 32; ++i) acc[i] = 0.f;
-
-    for (int base = wv * CHUNK; base < n; base += NW * CHUNK) {
-        uint4 kr[UNR], vr[UNR];
-        uint32_t km[UNR], vm[UNR];
-#pragma unroll
-        for (int x = 0; x < UNR; ++x) {
-            const int j = base + x * RPW + g;
-            const int jj = j < n ? j : n - 1;
-            kr[x] = *reinterpret_cast<const uint4*>(Ku + (size_t)jj * ROWB);
-            vr[x] = *reinterpret_cast<const uint4*>(Vu + (size_t)jj * ROWB);
-            km[x] = Km[(size_t)jj * GPR];
-            vm[x] = Vm[(size_t)jj * GPR];
-        }
-#pragma unroll
-        for (int x = 0; x < UNR; ++x) {
-            const int j = base + x * RPW + g;
-            const bool valid = j < n;
-            const uint32_t kw[4] = {kr[x].x, kr[x].y, kr[x].z, kr[x].w};
-            float dotc = 0.f;
-#pragma unroll
-            for (int w = 0; w < 4; ++w)
-#pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    dotc = fmaf((float)((kw[w] >> (4 * k)) & 15u), qf[w * 8 + k], dotc);
-            const float2 kmeta = unpack_meta(km[x]);
-            float s = group_sum<LPR>(fmaf(kmeta.x, dotc, kmeta.y * qsum));
-            if (valid && c == 0) s_lds[j] = s;
-            if (valid && s > m) {
-                const float al = fast_exp2(m - s);
-                l *= al;
-                zacc *= al;
-#pragma unroll
-                for (int i = 0; i < 32; ++i) acc[i] *= al;
-                m = s;
-            }
-            const float e = valid ? fast_exp2(s - m) : 0.f;
-            l += e;
-            const float2 vmeta = unpack_meta(vm[x]);
-            const float es = e * vmeta.x;
-            zacc = fmaf(e, vmeta.y, zacc);
-            const uint32_t vw[4] = {vr[x].x, vr[x].y, vr[x].z, vr[x].w};
-#pragma unroll
-            for (int w = 0; w < 4; ++w)
-#pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    acc[w * 8 + k] = fmaf(es, (float)((vw[w] >> (4 * k)) & 15u), acc[w * 8 + k]);
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < 32; ++i) acc[i] += zacc;
-#pragma unroll
-    for (int off = LPR; off < 64; off <<= 1) {
-        const float mo = __shfl_xor(m, off), lo = __shfl_xor(l, off);
-        float mn, sa, sb;
-        merge_scales(m, mo, mn, sa, sb);
-        l = l * sa + lo * sb;
-#pragma unroll
-        for (int i = 0; i < 32; ++i) acc[i] = acc[i] * sa + __shfl_xor(acc[i], off) * sb;
-        m = mn;
-    }
-    if (g == 0) {
-#pragma unroll
-        for (int i = 0; i < 32; ++i) part_acc[wv * D + c * 32 + i] = acc[i];
-        if (c == 0) {
-            part_m[wv] = m;
-            part_l[wv] = l;
-        }
-    }
-    __syncthreads();
-    finish_unit<_Float16, D, NW>(a, u, s_lds, part_m, part_l, part_acc);
-}
-
-// ---------------------------------------------------------------------------------------
-// Append: copy (or quantise) this step's k/v row into slot n-1 and record its position.
-// ---------------------------------------------------------------------------------------
-template <typename T, int D>
-__global__ void __launch_bounds__(64) append_rows_kernel(const T* k_new, const T* v_new, long in_stride,
-                                                         T* K, T* V, int32_t* pos, int C, int slot,
-                                                         int pos_value) {
-    constexpr int EPL = 16 / (int)sizeof(T);
-    constexpr int LPR = D / EPL;
-    const int u = blockIdx.x, lane = threadIdx.x;
-    if (lane < LPR) {
-        *reinterpret_cast<uint4*>(K + ((size_t)u * C + slot) * D + lane * EPL) =
-            *reinterpret_cast<const uint4*>(k_new + (size_t)u * in_stride + lane * EPL);
-    } else if (lane < 2 * LPR) {
-        const int c = lane - LPR;
-        *reinterpret_cast<uint4*>(V + ((size_t)u * C + slot) * D + c * EPL) =
-            *reinterpret_cast<const uint4*>(v_new + (size_t)u * in_stride + c * EPL);
-    }
-    if (lane == 63) pos[(size_t)u * C + slot] = pos_value;
-}
-
-// 4-bit append.  Wave 0 quantises the key row, wave 1 the value row; lane i owns channels
-// 2i and 2i+1 (one byte of codes).  Every operation is a single IEEE fp32 operation so the
-// codes are reproducible: zero = min, scale = fp16((max-min)/15) (1 when that is 0),
+// Quantise one row of D fp16 channels held two per lane (lane i: channels 2i, 2i+1; lanes
+// >= D/2 idle) and store codes and meta to `codes` / `meta` (global) and to their LDS copies.
+// Every operation is a single IEEE fp32 operation so the codes are reproducible anywhere:
+// zero = min, scale = fp16((max-min)/15) (1 when that is 0),
 // code = clamp(rint((x-zero)/scale), 0, 15).
 template <int D>
-__global__ void __launch_bounds__(128) append_i4_kernel(const _Float16* k_new, const _Float16* v_new,
-                                                        long in_stride, unsigned char* K,
-                                                        unsigned char* V, uint32_t* K_meta,
-                                                        uint32_t* V_meta, int32_t* pos, int C, int slot,
-                                                        int pos_value) {
-    constexpr int GPR = D / 64;
-    const int u = blockIdx.x, lane = threadIdx.x & 63, which = threadIdx.x >> 6;
-    const _Float16* src = (which ? v_new : k_new) + (size_t)u * in_stride;
-    unsigned char* dst = (which ? V : K) + ((size_t)u * C + slot) * (D / 2);
-    uint32_t* meta = (which ? V_meta : K_meta) + ((size_t)u * C + slot) * GPR;
+__device__ __forceinline__ void quantise_row(const _Float16* src, unsigned char* codes, uint32_t* meta,
+                                             unsigned char* lds_codes, uint32_t* lds_meta, int lane) {
     if (lane < D / 2) {
         const float x0 = (float)src[2 * lane], x1 = (float)src[2 * lane + 1];
         float mn = fminf(x0, x1), mx = fmaxf(x0, x1);
@@ -363,18 +256,139 @@ __global__ void __launch_bounds__(128) append_i4_kernel(const _Float16* k_new, c
         float c1 = rintf(__fdiv_rn(__fsub_rn(x1, z), s));
         c0 = fminf(fmaxf(c0, 0.f), 15.f);
         c1 = fminf(fmaxf(c1, 0.f), 15.f);
-        dst[lane] = (unsigned char)((uint32_t)c0 | ((uint32_t)c1 << 4));
+        const unsigned char byte = (unsigned char)((uint32_t)c0 | ((uint32_t)c1 << 4));
+        codes[lane] = byte;
+        lds_codes[lane] = byte;
         if ((lane & 31) == 0) {
-            union {
-                uint32_t u32;
-                _Float16 h[2];
-            } cv;
-            cv.h[0] = sh;
-            cv.h[1] = zh;
-            meta[lane >> 5] = cv.u32;
+            MetaWord mw;
+            mw.h[0] = sh;
+            mw.h[1] = zh;
+            meta[lane >> 5] = mw.u32;
+            lds_meta[lane >> 5] = mw.u32;
         }
     }
-    if (threadIdx.x == 127) pos[(size_t)u * C + slot] = pos_value;
+}
+
+template <int D, int NW, int UNR>
+__global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
+    constexpr int LPR = D / 32;
+    constexpr int RPW = 64 / LPR;
+    constexpr int GPR = D / 64;  // groups per row
+    constexpr int CHUNK = RPW * UNR;
+    constexpr int ROWB = D / 2;  // bytes of codes per row
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    float* s_lds = reinterpret_cast<float*>(smem_raw);
+    float* part_m = s_lds + a.C;
+    float* part_l = part_m + NW;
+    float* part_acc = part_l + NW;
+    __shared__ __align__(16) unsigned char new_codes[2][ROWB];  // [0] key row, [1] value row
+    __shared__ uint32_t new_meta[2][GPR];
+
+    const int u = blockIdx.x;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int g = lane / LPR, c = lane % LPR;
+    const int gi = c / 2;  // 64-channel group this lane's 32 channels fall in
+    const int nc = a.n - 1;
+    unsigned char* Kb = (unsigned char*)a.K + (size_t)u * a.C * ROWB;
+    unsigned char* Vb = (unsigned char*)a.V + (size_t)u * a.C * ROWB;
+    uint32_t* Kmb = (uint32_t*)a.K_meta + (size_t)u * a.C * GPR;
+    uint32_t* Vmb = (uint32_t*)a.V_meta + (size_t)u * a.C * GPR;
+
+    // Alg. 1 model update: wave 0 quantises the key row, wave 1 the value row.
+    if (wv < 2) {
+        const _Float16* src = (const _Float16*)(wv ? a.v_new : a.k_new) + (size_t)u * a.in_stride;
+        quantise_row<D>(src, (wv ? Vb : Kb) + (size_t)nc * ROWB, (wv ? Vmb : Kmb) + (size_t)nc * GPR,
+                        new_codes[wv], new_meta[wv], lane);
+        if (wv == 0 && lane == 0) a.pos[(size_t)u * a.C + nc] = a.pos_value;
+    }
+
+    const unsigned char* Ku = Kb + c * 16;
+    const unsigned char* Vu = Vb + c * 16;
+    const uint32_t* Km = Kmb + gi;
+    const uint32_t* Vm = Vmb + gi;
+
+    float qf[32];
+    float qsum = 0.f;
+    {
+        const _Float16* qu = (const _Float16*)a.q + (size_t)u * a.in_stride + c * 32;
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+            Frag<_Float16, 8> qr;
+            qr.raw = *reinterpret_cast<const uint4*>(qu + v4 * 8);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                qf[v4 * 8 + i] = (float)qr.e[i] * a.qk_log2;
+                qsum += qf[v4 * 8 + i];
+            }
+        }
+    }
+    Running<32> run;
+    run.init();
+    float zacc = 0.f;  // sum of weight * zero of this lane's group (rescaled with run.acc)
+    auto take_row = [&](const uint4& kr, const uint4& vr, uint32_t kmw, uint32_t vmw, int j, bool valid) {
+        const uint32_t kw[4] = {kr.x, kr.y, kr.z, kr.w};
+        float dotc = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                dotc = fmaf((float)((kw[w] >> (4 * k)) & 15u), qf[w * 8 + k], dotc);
+        MetaWord km, vm;
+        km.u32 = kmw;
+        vm.u32 = vmw;
+        const float s = group_sum<LPR>(fmaf((float)km.h[0], dotc, (float)km.h[1] * qsum));
+        if (valid && c == 0) s_lds[j] = s;
+        const float m_before = run.m;
+        const float e = run.admit(s, valid);
+        if (run.m != m_before) zacc *= fast_exp2(m_before - run.m);
+        const float es = e * (float)vm.h[0];
+        zacc = fmaf(e, (float)vm.h[1], zacc);
+        const uint32_t vw[4] = {vr.x, vr.y, vr.z, vr.w};
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                run.acc[w * 8 + k] = fmaf(es, (float)((vw[w] >> (4 * k)) & 15u), run.acc[w * 8 + k]);
+    };
+
+    for (int base = wv * CHUNK; base < nc; base += NW * CHUNK) {
+        uint4 kr[UNR], vr[UNR];
+        uint32_t km[UNR], vm[UNR];
+#pragma unroll
+        for (int x = 0; x < UNR; ++x) {
+            const int j = base + x * RPW + g;
+            const int jj = j < nc ? j : 0;
+            kr[x] = *reinterpret_cast<const uint4*>(Ku + (size_t)jj * ROWB);
+            vr[x] = *reinterpret_cast<const uint4*>(Vu + (size_t)jj * ROWB);
+            km[x] = Km[(size_t)jj * GPR];
+            vm[x] = Vm[(size_t)jj * GPR];
+        }
+#pragma unroll
+        for (int x = 0; x < UNR; ++x) {
+            const int j = base + x * RPW + g;
+            take_row(kr[x], vr[x], km[x], vm[x], j, j < nc);
+        }
+    }
+    __syncthreads();  // the quantised new row is in LDS
+    if (wv == 0) {
+        const uint4 kr = *reinterpret_cast<const uint4*>(&new_codes[0][c * 16]);
+        const uint4 vr = *reinterpret_cast<const uint4*>(&new_codes[1][c * 16]);
+        take_row(kr, vr, new_meta[0][gi], new_meta[1][gi], nc, g == 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 32; ++i) run.acc[i] += zacc;
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) run.merge_xor(off);
+    if (g == 0) {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) part_acc[wv * D + c * 32 + i] = run.acc[i];
+        if (c == 0) {
+            part_m[wv] = run.m;
+            part_l[wv] = run.l;
+        }
+    }
+    __syncthreads();
+    finish_unit<_Float16, D, NW>(a, u, s_lds, part_m, part_l, part_acc);
 }
 
 __global__ void clear_u32_kernel(uint32_t* p, size_t n) {
@@ -416,48 +430,17 @@ int pick_waves(int U) {
 }  // namespace
 
 hipError_t launch_decode_step(const Layout& L, const StepArgs& s, hipStream_t stream) {
-    const int slot = s.n - 1;
-    hipError_t err;
-    if (L.kv_dtype == KV_F32) {
-        if (L.d == 64)
-            append_rows_kernel<float, 64><<<L.U, 64, 0, stream>>>(
-                (const float*)s.k_new, (const float*)s.v_new, s.in_stride, (float*)L.K, (float*)L.V,
-                L.pos, L.C, slot, s.pos_value);
-        else
-            append_rows_kernel<float, 128><<<L.U, 64, 0, stream>>>(
-                (const float*)s.k_new, (const float*)s.v_new, s.in_stride, (float*)L.K, (float*)L.V,
-                L.pos, L.C, slot, s.pos_value);
-    } else if (L.kv_dtype == KV_F16) {
-        if (L.d == 64)
-            append_rows_kernel<_Float16, 64><<<L.U, 64, 0, stream>>>(
-                (const _Float16*)s.k_new, (const _Float16*)s.v_new, s.in_stride, (_Float16*)L.K,
-                (_Float16*)L.V, L.pos, L.C, slot, s.pos_value);
-        else
-            append_rows_kernel<_Float16, 128><<<L.U, 64, 0, stream>>>(
-                (const _Float16*)s.k_new, (const _Float16*)s.v_new, s.in_stride, (_Float16*)L.K,
-                (_Float16*)L.V, L.pos, L.C, slot, s.pos_value);
-    } else {
-        if (L.d == 64)
-            append_i4_kernel<64><<<L.U, 128, 0, stream>>>(
-                (const _Float16*)s.k_new, (const _Float16*)s.v_new, s.in_stride, (unsigned char*)L.K,
-                (unsigned char*)L.V, (uint32_t*)L.K_meta, (uint32_t*)L.V_meta, L.pos, L.C, slot,
-                s.pos_value);
-        else
-            append_i4_kernel<128><<<L.U, 128, 0, stream>>>(
-                (const _Float16*)s.k_new, (const _Float16*)s.v_new, s.in_stride, (unsigned char*)L.K,
-                (unsigned char*)L.V, (uint32_t*)L.K_meta, (uint32_t*)L.V_meta, L.pos, L.C, slot,
-                s.pos_value);
-    }
-    err = hipGetLastError();
-    if (err != hipSuccess) return err;
-
     AttnArgs a;
     a.q = s.q;
-    a.q_stride = s.in_stride;
+    a.k_new = s.k_new;
+    a.v_new = s.v_new;
+    a.in_stride = s.in_stride;
     a.K = L.K;
     a.V = L.V;
     a.K_meta = L.K_meta;
     a.V_meta = L.V_meta;
+    a.pos = L.pos;
+    a.pos_value = s.pos_value;
     a.out = s.out;
     a.out_stride = s.out_stride;
     a.probs = s.probs;

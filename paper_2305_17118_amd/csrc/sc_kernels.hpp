@@ -41,7 +41,7 @@ struct StepArgs {
     float tau;        // low-score threshold
 };
 
-// Append the new row then attend (two launches on `stream`).
+// One launch on `stream`: append the new row and attend.
 hipError_t launch_decode_step(const Layout& L, const StepArgs& a, hipStream_t stream);
 
 struct CompressArgs {
