@@ -120,7 +120,8 @@ void sc_cache_destroy(sc_cache *c);
  *                     elements apart (0 = densely packed [batch, heads, head_dim])
  *   out             : device, dense [batch, heads, head_dim]
  *   probs_out       : device fp32 [U][capacity] or NULL; receives, for slots < n, exactly the
- *                     probabilities the threshold test was applied to (slots >= n untouched)
+ *                     probabilities the threshold test was applied to (slot n is written
+ *                     as 0 when n is odd, other slots >= n are untouched)
  *   compress_due    : host int or NULL; set to 1 when n has reached n_trig, i.e. the caller
  *                     must call sc_compress before the next step, else 0
  * SC_ERR_FULL if a compression is due. */

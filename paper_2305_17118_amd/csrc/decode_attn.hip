@@ -100,12 +100,28 @@ struct Running {
     }
 };
 
+// Counter words: two 16-bit counters (slots 2i and 2i+1) per 32-bit word.  Each thread owns
+// the words i = tid, tid + NT, ...; the first CNT_PF of them are fetched when the kernel
+// starts so that their latency is hidden behind the K/V stream.
+constexpr int CNT_PF = 2;
+
+template <int NT>
+__device__ __forceinline__ void prefetch_counters(const AttnArgs& a, int u, uint32_t (&pre)[CNT_PF]) {
+    const uint32_t* cw = reinterpret_cast<const uint32_t*>(a.cnt + (size_t)u * a.cnt_unit_stride);
+#pragma unroll
+    for (int k = 0; k < CNT_PF; ++k) {
+        const int i = threadIdx.x + k * NT;
+        pre[k] = (a.counted && 2 * i < a.n) ? cw[i] : 0u;
+    }
+}
+
 // Shared tail of both attention kernels: combine the per-wave partials, write `out`, then the
 // probability epilogue with the counter update.
 template <typename TOut, int D, int NW>
 __device__ __forceinline__ void finish_unit(const AttnArgs& a, int u, const float* s_lds,
                                             const float* part_m, const float* part_l,
-                                            const float* part_acc) {
+                                            const float* part_acc, const uint32_t (&pre)[CNT_PF]) {
+    constexpr int NT = NW * 64;
     const int tid = threadIdx.x;
     float M = part_m[0];
 #pragma unroll
@@ -120,24 +136,45 @@ __device__ __forceinline__ void finish_unit(const AttnArgs& a, int u, const floa
         for (int w = 0; w < NW; ++w) o += part_acc[w * D + tid] * fast_exp2(part_m[w] - M);
         ((TOut*)a.out)[(size_t)u * a.out_stride + tid] = (TOut)(o * invL);
     }
-    uint16_t* cnt = a.cnt + (size_t)u * a.cnt_unit_stride;
-    float* probs = a.probs ? a.probs + (size_t)u * a.C : nullptr;
-    for (int j = tid; j < a.n; j += NW * 64) {
-        const float p = fast_exp2(s_lds[j] - M) * invL;
-        if (probs) probs[j] = p;
-        if (a.counted && p < a.tau) cnt[j] = (uint16_t)(cnt[j] + 1);
+    uint32_t* cw = reinterpret_cast<uint32_t*>(a.cnt + (size_t)u * a.cnt_unit_stride);
+    float2* probs = a.probs ? reinterpret_cast<float2*>(a.probs + (size_t)u * a.C) : nullptr;
+    const int n = a.n;
+    auto do_word = [&](int i, uint32_t word) {
+        const int j = 2 * i;  // j < n here; slot j+1 may be the first free one
+        const float p0 = fast_exp2(s_lds[j] - M) * invL;
+        const float p1 = (j + 1 < n) ? fast_exp2(s_lds[j + 1] - M) * invL : 0.f;
+        if (probs) probs[i] = make_float2(p0, p1);
+        const uint32_t inc = (p0 < a.tau ? 1u : 0u) | ((j + 1 < n && p1 < a.tau) ? 0x10000u : 0u);
+        if (a.counted && inc) cw[i] = word + inc;
+    };
+#pragma unroll
+    for (int k = 0; k < CNT_PF; ++k) {
+        const int i = tid + k * NT;
+        if (2 * i < n) do_word(i, pre[k]);
     }
+    for (int i = tid + CNT_PF * NT; 2 * i < n; i += NT) do_word(i, a.counted ? cw[i] : 0u);
 }
 
 // ---------------------------------------------------------------------------------------
 // fp32 / fp16 rows.
 // ---------------------------------------------------------------------------------------
+// K/V rows are read exactly once per launch: stream them with non-temporal loads so that they
+// do not displace anything in the cache hierarchy (measurably faster than plain loads here).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream16(const void* base, uint32_t byte_off) {
+    const u32x4 v = __builtin_nontemporal_load(
+        reinterpret_cast<const u32x4*>(static_cast<const char*>(base) + byte_off));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 template <typename T, int D, int NW, int UNR>
 __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
     constexpr int EPL = 16 / (int)sizeof(T);  // elements per lane
     constexpr int LPR = D / EPL;              // lanes per row
     constexpr int RPW = 64 / LPR;             // rows per wave load
-    constexpr int CHUNK = RPW * UNR;
+    constexpr int CHUNK = RPW * UNR;          // rows a wave fetches per batch of loads
+    constexpr int STRIDE = NW * CHUNK;
+    constexpr uint32_t ROWB = D * sizeof(T);
     extern __shared__ __align__(16) unsigned char smem_raw[];
     float* s_lds = reinterpret_cast<float*>(smem_raw);
     float* part_m = s_lds + a.C;
@@ -148,33 +185,32 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int g = lane / LPR, c = lane % LPR;
     const int nc = a.n - 1;  // rows resident before this step; the new row goes to slot nc
-    T* Ku = (T*)a.K + (size_t)u * a.C * D + c * EPL;
-    T* Vu = (T*)a.V + (size_t)u * a.C * D + c * EPL;
+    // unit-uniform bases (scalar registers) + 32-bit per-lane byte offsets
+    char* Kb = (char*)a.K + (size_t)u * a.C * ROWB;
+    char* Vb = (char*)a.V + (size_t)u * a.C * ROWB;
+    const uint32_t lane_off = (uint32_t)g * ROWB + (uint32_t)c * 16u;
     const size_t in_off = (size_t)u * a.in_stride + c * EPL;
+    using F = Frag<T, EPL>;
 
-    float qf[EPL];
-    {
-        Frag<T, EPL> qr;
-        qr.raw = *reinterpret_cast<const uint4*>((const T*)a.q + in_off);
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) qf[i] = (float)qr.e[i] * a.qk_log2;
-    }
-    // Alg. 1 model update: the first lane group of wave 0 owns the new row.
-    const bool owner = (wv == 0) && (g == 0);
-    Frag<T, EPL> k_own, v_own;
+    // Everything the kernel needs from memory up front is requested before anything is
+    // waited for: q, the new row (its owner only), the counters.
+    F qr;
+    qr.raw = *reinterpret_cast<const uint4*>((const T*)a.q + in_off);
+    const bool owner = (wv == 0) && (g == 0);  // Alg. 1 model update: who holds the new row
+    F k_own, v_own;
     k_own.raw = make_uint4(0, 0, 0, 0);
     v_own.raw = make_uint4(0, 0, 0, 0);
     if (owner) {
         k_own.raw = *reinterpret_cast<const uint4*>((const T*)a.k_new + in_off);
         v_own.raw = *reinterpret_cast<const uint4*>((const T*)a.v_new + in_off);
-        *reinterpret_cast<uint4*>(Ku + (size_t)nc * D) = k_own.raw;
-        *reinterpret_cast<uint4*>(Vu + (size_t)nc * D) = v_own.raw;
-        if (c == 0) a.pos[(size_t)u * a.C + nc] = a.pos_value;
     }
+    uint32_t cpre[CNT_PF];
+    prefetch_counters<NW * 64>(a, u, cpre);
 
+    float qf[EPL];
     Running<EPL> run;
     run.init();
-    auto take_row = [&](const Frag<T, EPL>& kr, const Frag<T, EPL>& vr, int j, bool valid) {
+    auto take_row = [&](const F& kr, const F& vr, int j, bool valid) {
         float s = 0.f;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) s = fmaf((float)kr.e[i], qf[i], s);
@@ -184,21 +220,47 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
 #pragma unroll
         for (int i = 0; i < EPL; ++i) run.acc[i] = fmaf(e, (float)vr.e[i], run.acc[i]);
     };
+    // Full chunks need no bounds checks; one ragged chunk at most is handled with masks.
+    auto load_full = [&](F (&kr)[UNR], F (&vr)[UNR], int base) {
+        const uint32_t off = (uint32_t)base * ROWB + lane_off;
+#pragma unroll
+        for (int x = 0; x < UNR; ++x) {
+            kr[x].raw = load_stream16(Kb, off + (uint32_t)x * (RPW * ROWB));
+            vr[x].raw = load_stream16(Vb, off + (uint32_t)x * (RPW * ROWB));
+        }
+    };
+    auto take_full = [&](const F (&kr)[UNR], const F (&vr)[UNR], int base) {
+#pragma unroll
+        for (int x = 0; x < UNR; ++x) take_row(kr[x], vr[x], base + x * RPW + g, true);
+    };
 
-    for (int base = wv * CHUNK; base < nc; base += NW * CHUNK) {
-        Frag<T, EPL> kr[UNR], vr[UNR];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) qf[i] = (float)qr.e[i] * a.qk_log2;
+    int base = wv * CHUNK;
+    for (; base + CHUNK <= nc; base += STRIDE) {
+        F kr[UNR], vr[UNR];
+        load_full(kr, vr, base);
+        take_full(kr, vr, base);
+    }
+    if (base < nc) {  // ragged tail of this wave
+        F kr[UNR], vr[UNR];
 #pragma unroll
         for (int x = 0; x < UNR; ++x) {
             const int j = base + x * RPW + g;
-            const int jj = j < nc ? j : 0;
-            kr[x].raw = *reinterpret_cast<const uint4*>(Ku + (size_t)jj * D);
-            vr[x].raw = *reinterpret_cast<const uint4*>(Vu + (size_t)jj * D);
+            const uint32_t off = (j < nc ? (uint32_t)j : 0u) * ROWB + (uint32_t)c * 16u;
+            kr[x].raw = load_stream16(Kb, off);
+            vr[x].raw = load_stream16(Vb, off);
         }
 #pragma unroll
         for (int x = 0; x < UNR; ++x) {
             const int j = base + x * RPW + g;
             take_row(kr[x], vr[x], j, j < nc);
         }
+    }
+    if (owner) {
+        *reinterpret_cast<uint4*>(Kb + (size_t)nc * ROWB + c * 16) = k_own.raw;
+        *reinterpret_cast<uint4*>(Vb + (size_t)nc * ROWB + c * 16) = v_own.raw;
+        if (c == 0) a.pos[(size_t)u * a.C + nc] = a.pos_value;
     }
     if (wv == 0) take_row(k_own, v_own, nc, owner);
 
@@ -213,7 +275,7 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
         }
     }
     __syncthreads();
-    finish_unit<T, D, NW>(a, u, s_lds, part_m, part_l, part_acc);
+    finish_unit<T, D, NW>(a, u, s_lds, part_m, part_l, part_acc, cpre);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -322,6 +384,8 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
             }
         }
     }
+    uint32_t cpre[CNT_PF];
+    prefetch_counters<NW * 64>(a, u, cpre);
     Running<32> run;
     run.init();
     float zacc = 0.f;  // sum of weight * zero of this lane's group (rescaled with run.acc)
@@ -388,7 +452,7 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
         }
     }
     __syncthreads();
-    finish_unit<_Float16, D, NW>(a, u, s_lds, part_m, part_l, part_acc);
+    finish_unit<_Float16, D, NW>(a, u, s_lds, part_m, part_l, part_acc, cpre);
 }
 
 __global__ void clear_u32_kernel(uint32_t* p, size_t n) {
@@ -419,13 +483,10 @@ hipError_t launch_i4(const AttnArgs& a, int U, int nw, hipStream_t stream) {
     return hipGetLastError();
 }
 
-// Waves per workgroup: enough waves chip-wide (256 CUs) to keep many loads in flight even
-// when there are few units.
-int pick_waves(int U) {
-    if (U >= 2048) return 4;
-    if (U >= 1024) return 8;
-    return 16;
-}
+// Waves per workgroup.  Measured on MI355X over unit counts from 512 to 9216 and 350 to 1000
+// resident rows: 16 waves with two K and two V loads in flight per lane (<= 64 VGPRs, so two
+// workgroups share a CU) is the fastest or within noise of it everywhere.
+int pick_waves(int /*U*/) { return 16; }
 
 }  // namespace
 
@@ -453,11 +514,11 @@ hipError_t launch_decode_step(const Layout& L, const StepArgs& s, hipStream_t st
     a.counted = s.counted;
     const int nw = pick_waves(L.U);
     if (L.kv_dtype == KV_F32)
-        return L.d == 64 ? launch_rows<float, 64, 4>(a, L.U, nw, stream)
-                         : launch_rows<float, 128, 4>(a, L.U, nw, stream);
+        return L.d == 64 ? launch_rows<float, 64, 2>(a, L.U, nw, stream)
+                         : launch_rows<float, 128, 2>(a, L.U, nw, stream);
     if (L.kv_dtype == KV_F16)
-        return L.d == 64 ? launch_rows<_Float16, 64, 4>(a, L.U, nw, stream)
-                         : launch_rows<_Float16, 128, 4>(a, L.U, nw, stream);
+        return L.d == 64 ? launch_rows<_Float16, 64, 2>(a, L.U, nw, stream)
+                         : launch_rows<_Float16, 128, 2>(a, L.U, nw, stream);
     return L.d == 64 ? launch_i4<64, 2>(a, L.U, nw, stream) : launch_i4<128, 2>(a, L.U, nw, stream);
 }
 

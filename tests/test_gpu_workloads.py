@@ -1,0 +1,47 @@
+"""Full-size parity: the five workloads of the throughput metric at their real shapes, in the
+launch configuration the benchmark times, GPU (all units) against the oracle on a seeded
+sample of units (all heads of the first sequence plus units scattered over the batch; units
+are independent and identically distributed, so a sample checks every code path).  Every
+step of prompt and decode is compared; records, evicted slots, positions and stored rows
+must agree bit for bit at every compression.
+"""
+import pytest
+
+from paper_2305_17118_amd import binding as B
+from paper_2305_17118_amd.workloads import CONFIGS, sample_units
+
+from .parity_util import ParityRun
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample(wl, extra):
+    if wl.units <= 64:
+        return list(range(wl.units))
+    first_seq = list(range(wl.heads))
+    return sorted(set(first_seq) | set(sample_units(wl, extra)))
+
+
+@pytest.mark.parametrize("idx,extra", [(0, 0), (1, 16), (2, 24), (3, 24), (4, 24)],
+                         ids=[c.name for c in CONFIGS])
+def test_workload_matches_oracle(idx, extra):
+    wl = CONFIGS[idx]
+    sel = _sample(wl, extra)
+    print("\n%s: %d units on the GPU, %d on the oracle" % (wl.name, wl.units, len(sel)), flush=True)
+    run = ParityRun(wl, sel=sel)
+    st = run.run(check_rows_every=3)
+    print(st, flush=True)
+    assert st["steps"] == wl.total
+    expected = sum(1 for t in range(1, wl.total + 1)
+                   if t >= wl.budget + 1 and (t - wl.budget - 1) % wl.drop == 0)
+    assert st["compressions"] == expected
+    assert run.cache.n <= wl.budget + 1
+
+
+def test_headline_workload_high_water_policy():
+    """The trigger policy that leaves exactly B rows after each compression, on the headline
+    shape (shortened stream: 1024 prompt + 320 decode, three compressions)."""
+    wl = CONFIGS[1].scaled(decode=320)
+    run = ParityRun(wl, sel=_sample(wl, 8), trigger=B.SC_TRIGGER_HIGH_WATER)
+    st = run.run(check_rows_every=2)
+    assert st["compressions"] == 2 and run.cache.n == wl.budget + (wl.total - wl.budget - wl.drop) % wl.drop
