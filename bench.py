@@ -108,7 +108,7 @@ def main() -> int:
     cfg = B.make_config(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.budget, wl.recent, wl.history,
                         wl.drop)
     ws_bytes = B.sc_workspace_bytes(cfg)
-    R = args.rotate or max(1, -(-3 * 256 * 2 ** 20 // ws_bytes))
+    R = args.rotate or min(8, max(1, -(-3 * 256 * 2 ** 20 // ws_bytes)))
     T, d, U = wl.total, wl.head_dim, wl.units
     steps_avail = R * wl.decode
     K, W = args.steps, args.warmup
@@ -167,7 +167,7 @@ def main() -> int:
     wall = time.perf_counter() - t0
 
     if use_events:
-        clean = [gr for gr in groups if gr[3]]
+        clean = [gr for gr in groups if gr[3]] or groups
         launches = sum(gr[2] for gr in clean)
         kern_ms = sum(gr[0].elapsed_time(gr[1]) for gr in clean) / launches
         alg = sum(algorithmic_bytes(wl, n) for gr in clean for n in gr[4]) / launches

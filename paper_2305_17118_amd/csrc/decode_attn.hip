@@ -117,24 +117,26 @@ __device__ __forceinline__ void prefetch_counters(const AttnArgs& a, int u, uint
 
 // Shared tail of both attention kernels: combine the per-wave partials, write `out`, then the
 // probability epilogue with the counter update.
-template <typename TOut, int D, int NW>
+// NT = threads of the workgroup, NP = number of partial (m, l, acc[D]) triples published in LDS.
+template <typename TOut, int D, int NT, int NP>
 __device__ __forceinline__ void finish_unit(const AttnArgs& a, int u, const float* s_lds,
                                             const float* part_m, const float* part_l,
                                             const float* part_acc, const uint32_t (&pre)[CNT_PF]) {
-    constexpr int NT = NW * 64;
     const int tid = threadIdx.x;
     float M = part_m[0];
 #pragma unroll
-    for (int w = 1; w < NW; ++w) M = fmaxf(M, part_m[w]);
+    for (int w = 1; w < NP; ++w) M = fmaxf(M, part_m[w]);
     float Lsum = 0.f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) Lsum += part_l[w] * fast_exp2(part_m[w] - M);
+    for (int w = 0; w < NP; ++w) Lsum += part_l[w] * fast_exp2(part_m[w] - M);
     const float invL = 1.0f / Lsum;
-    if (a.out && tid < D) {
-        float o = 0.f;
+    if (a.out) {
+        for (int ch = tid; ch < D; ch += NT) {
+            float o = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) o += part_acc[w * D + tid] * fast_exp2(part_m[w] - M);
-        ((TOut*)a.out)[(size_t)u * a.out_stride + tid] = (TOut)(o * invL);
+            for (int w = 0; w < NP; ++w) o += part_acc[w * D + ch] * fast_exp2(part_m[w] - M);
+            ((TOut*)a.out)[(size_t)u * a.out_stride + ch] = (TOut)(o * invL);
+        }
     }
     uint32_t* cw = reinterpret_cast<uint32_t*>(a.cnt + (size_t)u * a.cnt_unit_stride);
     float2* probs = a.probs ? reinterpret_cast<float2*>(a.probs + (size_t)u * a.C) : nullptr;
@@ -275,7 +277,7 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
         }
     }
     __syncthreads();
-    finish_unit<T, D, NW>(a, u, s_lds, part_m, part_l, part_acc, cpre);
+    finish_unit<T, D, NW * 64, NW>(a, u, s_lds, part_m, part_l, part_acc, cpre);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -331,18 +333,69 @@ __device__ __forceinline__ void quantise_row(const _Float16* src, unsigned char*
     }
 }
 
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+// Two 4-bit codes of a 32-bit word, bits [lo, lo+4) of each 16-bit half, as a pair of fp16
+// numbers without any int->float conversion: OR-ing the bits into the mantissa of 1024.0
+// (0x6400, whose ulp is 1) gives 1024 + code for lo = 0 and 1024 + 16*code for lo = 4.
+__device__ __forceinline__ half2_t nibble_pair(uint32_t w, uint32_t mask) {
+    uint32_t r;
+    // one VALU instruction; the mask sits in a vector register and the constant in a scalar
+    // one because this encoding takes no literals and a single scalar operand
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(w), "v"(mask), "s"(0x64006400u));
+    return __builtin_bit_cast(half2_t, r);
+}
+
+// The eight codes of word w as four such pairs: {n0,n4}, {n1,n5}x16, {n2,n6}, {n3,n7}x16.
+__device__ __forceinline__ void unpack8(uint32_t w, half2_t (&h)[4]) {
+    const uint32_t t = w >> 8;
+    h[0] = nibble_pair(w, 0x000F000Fu);
+    h[1] = nibble_pair(w, 0x00F000F0u);
+    h[2] = nibble_pair(t, 0x000F000Fu);
+    h[3] = nibble_pair(t, 0x00F000F0u);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_max(float v) { return fmaxf(v, dpp_f32<CTRL>(v)); }
+
+// DPP row_ror:n (rotate right by n lanes inside each row of 16 lanes).
+#define SC_ROW_ROR(n) (0x120 + (n))
+
+// Sum / max over the lane groups that share a row of 16 lanes (groups are LPR lanes wide, so
+// lanes LPR, 2*LPR, ... apart hold the same channels of different cache rows).
+template <int LPR>
+__device__ __forceinline__ float row_groups_sum(float v) {
+    if constexpr (LPR <= 2) v += dpp_f32<SC_ROW_ROR(2)>(v);
+    if constexpr (LPR <= 4) v += dpp_f32<SC_ROW_ROR(4)>(v);
+    if constexpr (LPR <= 8) v += dpp_f32<SC_ROW_ROR(8)>(v);
+    return v;
+}
+template <int LPR>
+__device__ __forceinline__ float row_groups_max(float v) {
+    if constexpr (LPR <= 2) v = dpp_max<SC_ROW_ROR(2)>(v);
+    if constexpr (LPR <= 4) v = dpp_max<SC_ROW_ROR(4)>(v);
+    if constexpr (LPR <= 8) v = dpp_max<SC_ROW_ROR(8)>(v);
+    return v;
+}
+
+// The kernel is bound by plain ALU work as much as by HBM (256 codes per 144 bytes), so the
+// inner loop avoids per-code conversions: codes become fp16 pairs with one AND-OR each, the
+// key side uses the packed fp16 dot product with fp32 accumulation, the value side the mixed
+// fp16 x fp32 fused multiply-add; the +1024 offsets of the pairs and the zero points are
+// folded out of the loop.  All lane groups of a 16-lane row share one running maximum, so
+// their partial sums merge with plain DPP adds.
 template <int D, int NW, int UNR>
 __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
-    constexpr int LPR = D / 32;
-    constexpr int RPW = 64 / LPR;
-    constexpr int GPR = D / 64;  // groups per row
-    constexpr int CHUNK = RPW * UNR;
-    constexpr int ROWB = D / 2;  // bytes of codes per row
+    constexpr int LPR = D / 32;   // lanes per cache row (16 bytes = 32 codes per lane)
+    constexpr int RPW = 64 / LPR; // cache rows per wave load
+    constexpr int GPR = D / 64;   // quantisation groups per cache row
+    constexpr uint32_t ROWB = D / 2;  // bytes of codes per cache row
+    constexpr int NP = NW * 4;        // one partial per 16-lane row
     extern __shared__ __align__(16) unsigned char smem_raw[];
     float* s_lds = reinterpret_cast<float*>(smem_raw);
     float* part_m = s_lds + a.C;
-    float* part_l = part_m + NW;
-    float* part_acc = part_l + NW;
+    float* part_l = part_m + NP;
+    float* part_acc = part_l + NP;
     __shared__ __align__(16) unsigned char new_codes[2][ROWB];  // [0] key row, [1] value row
     __shared__ uint32_t new_meta[2][GPR];
 
@@ -356,81 +409,122 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
     uint32_t* Kmb = (uint32_t*)a.K_meta + (size_t)u * a.C * GPR;
     uint32_t* Vmb = (uint32_t*)a.V_meta + (size_t)u * a.C * GPR;
 
-    // Alg. 1 model update: wave 0 quantises the key row, wave 1 the value row.
-    if (wv < 2) {
-        const _Float16* src = (const _Float16*)(wv ? a.v_new : a.k_new) + (size_t)u * a.in_stride;
-        quantise_row<D>(src, (wv ? Vb : Kb) + (size_t)nc * ROWB, (wv ? Vmb : Kmb) + (size_t)nc * GPR,
-                        new_codes[wv], new_meta[wv], lane);
-        if (wv == 0 && lane == 0) a.pos[(size_t)u * a.C + nc] = a.pos_value;
-    }
-
-    const unsigned char* Ku = Kb + c * 16;
-    const unsigned char* Vu = Vb + c * 16;
-    const uint32_t* Km = Kmb + gi;
-    const uint32_t* Vm = Vmb + gi;
-
-    float qf[32];
-    float qsum = 0.f;
-    {
-        const _Float16* qu = (const _Float16*)a.q + (size_t)u * a.in_stride + c * 32;
-#pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) {
-            Frag<_Float16, 8> qr;
-            qr.raw = *reinterpret_cast<const uint4*>(qu + v4 * 8);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                qf[v4 * 8 + i] = (float)qr.e[i] * a.qk_log2;
-                qsum += qf[v4 * 8 + i];
-            }
-        }
+    // Alg. 1 model update: wave 0 quantises the key row, wave 1 (wave 0 again when the
+    // workgroup is a single wave) the value row.
+    for (int which = wv; which < 2; which += NW) {
+        const _Float16* src = (const _Float16*)(which ? a.v_new : a.k_new) + (size_t)u * a.in_stride;
+        quantise_row<D>(src, (which ? Vb : Kb) + (size_t)nc * ROWB,
+                        (which ? Vmb : Kmb) + (size_t)nc * GPR, new_codes[which], new_meta[which], lane);
+        if (which == 0 && lane == 0) a.pos[(size_t)u * a.C + nc] = a.pos_value;
     }
     uint32_t cpre[CNT_PF];
     prefetch_counters<NW * 64>(a, u, cpre);
-    Running<32> run;
-    run.init();
-    float zacc = 0.f;  // sum of weight * zero of this lane's group (rescaled with run.acc)
+
+    // q of this lane's 32 channels as fp16 pairs matching unpack8, and the constants that
+    // cancel the +1024 of every pair: qa0/qb0 = -1024 * (sum of q over the channels that go
+    // through the plain / the x16 pairs); qsum for the zero point.
+    half2_t qh[16];
+    float qa0, qb0, qsum;
+    {
+        const _Float16* qu = (const _Float16*)a.q + (size_t)u * a.in_stride + c * 32;
+        float sa = 0.f, sb = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            Frag<_Float16, 8> qr;
+            qr.raw = *reinterpret_cast<const uint4*>(qu + w * 8);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                qh[w * 4 + k] = half2_t{qr.e[k], qr.e[k + 4]};
+                const float pair = (float)qr.e[k] + (float)qr.e[k + 4];
+                if (k & 1) sb += pair; else sa += pair;
+            }
+        }
+        qa0 = -1024.f * sa;
+        qb0 = -1024.f * sb;
+        qsum = sa + sb;
+    }
+    // Running softmax shared by the 16 lanes of a row: m, and per lane l (its own cache rows),
+    // acc (32 channels, still carrying the pair offsets), wsum (sum of weight*scale, to remove
+    // those offsets) and zacc (sum of weight*zero).
+    float m = -INFINITY, l = 0.f, wsum = 0.f, zacc = 0.f, acc[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) acc[i] = 0.f;
+
     auto take_row = [&](const uint4& kr, const uint4& vr, uint32_t kmw, uint32_t vmw, int j, bool valid) {
         const uint32_t kw[4] = {kr.x, kr.y, kr.z, kr.w};
-        float dotc = 0.f;
+        float da = qa0, db = qb0;
 #pragma unroll
-        for (int w = 0; w < 4; ++w)
-#pragma unroll
-            for (int k = 0; k < 8; ++k)
-                dotc = fmaf((float)((kw[w] >> (4 * k)) & 15u), qf[w * 8 + k], dotc);
+        for (int w = 0; w < 4; ++w) {
+            half2_t h[4];
+            unpack8(kw[w], h);
+            da = __builtin_amdgcn_fdot2(h[0], qh[w * 4 + 0], da, false);
+            db = __builtin_amdgcn_fdot2(h[1], qh[w * 4 + 1], db, false);
+            da = __builtin_amdgcn_fdot2(h[2], qh[w * 4 + 2], da, false);
+            db = __builtin_amdgcn_fdot2(h[3], qh[w * 4 + 3], db, false);
+        }
         MetaWord km, vm;
         km.u32 = kmw;
         vm.u32 = vmw;
-        const float s = group_sum<LPR>(fmaf((float)km.h[0], dotc, (float)km.h[1] * qsum));
+        const float dotc = fmaf(db, 0.0625f, da);  // sum of q*code over this lane's channels
+        float s = group_sum<LPR>(fmaf((float)km.h[0], dotc, (float)km.h[1] * qsum)) * a.qk_log2;
         if (valid && c == 0) s_lds[j] = s;
-        const float m_before = run.m;
-        const float e = run.admit(s, valid);
-        if (run.m != m_before) zacc *= fast_exp2(m_before - run.m);
+        s = valid ? s : -INFINITY;
+        const float smax = row_groups_max<LPR>(s);
+        if (smax > m) {  // same decision in all 16 lanes of the row
+            const float al = fast_exp2(m - smax);
+            l *= al;
+            wsum *= al;
+            zacc *= al;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) acc[i] *= al;
+            m = smax;
+        }
+        const float e = valid ? fast_exp2(s - m) : 0.f;
+        l += e;
         const float es = e * (float)vm.h[0];
+        const float es16 = es * 0.0625f;
+        wsum += es;
         zacc = fmaf(e, (float)vm.h[1], zacc);
         const uint32_t vw[4] = {vr.x, vr.y, vr.z, vr.w};
 #pragma unroll
-        for (int w = 0; w < 4; ++w)
+        for (int w = 0; w < 4; ++w) {
+            half2_t h[4];
+            unpack8(vw[w], h);
 #pragma unroll
-            for (int k = 0; k < 8; ++k)
-                run.acc[w * 8 + k] = fmaf(es, (float)((vw[w] >> (4 * k)) & 15u), run.acc[w * 8 + k]);
+            for (int k = 0; k < 4; ++k) {
+                const float wk = (k & 1) ? es16 : es;
+                acc[w * 8 + k] = fmaf((float)h[k][0], wk, acc[w * 8 + k]);
+                acc[w * 8 + k + 4] = fmaf((float)h[k][1], wk, acc[w * 8 + k + 4]);
+            }
+        }
     };
 
-    for (int base = wv * CHUNK; base < nc; base += NW * CHUNK) {
-        uint4 kr[UNR], vr[UNR];
-        uint32_t km[UNR], vm[UNR];
+    // A ring of UNR tiles (RPW cache rows each) per wave: as soon as a tile has been consumed
+    // its registers are refilled with the tile UNR positions ahead, so UNR-1 tiles of loads
+    // stay in flight behind the arithmetic.  Wave w owns tiles w, w+NW, w+2NW, ...
+    const int ntiles = (nc + RPW - 1) / RPW;
+    uint4 kr[UNR], vr[UNR];
+    uint32_t km[UNR], vm[UNR];
+    auto issue = [&](int x, int tile) {
+        const int j = tile * RPW + g;
+        const uint32_t jj = j < nc ? (uint32_t)j : 0u;
+        kr[x] = load_stream16(Kb, jj * ROWB + (uint32_t)c * 16u);
+        vr[x] = load_stream16(Vb, jj * ROWB + (uint32_t)c * 16u);
+        km[x] = __builtin_nontemporal_load(Kmb + jj * GPR + gi);
+        vm[x] = __builtin_nontemporal_load(Vmb + jj * GPR + gi);
+    };
+#pragma unroll
+    for (int x = 0; x < UNR; ++x)
+        if (wv + x * NW < ntiles) issue(x, wv + x * NW);
+    for (int t = wv; t < ntiles; t += UNR * NW) {
 #pragma unroll
         for (int x = 0; x < UNR; ++x) {
-            const int j = base + x * RPW + g;
-            const int jj = j < nc ? j : 0;
-            kr[x] = *reinterpret_cast<const uint4*>(Ku + (size_t)jj * ROWB);
-            vr[x] = *reinterpret_cast<const uint4*>(Vu + (size_t)jj * ROWB);
-            km[x] = Km[(size_t)jj * GPR];
-            vm[x] = Vm[(size_t)jj * GPR];
-        }
-#pragma unroll
-        for (int x = 0; x < UNR; ++x) {
-            const int j = base + x * RPW + g;
-            take_row(kr[x], vr[x], km[x], vm[x], j, j < nc);
+            const int tc = t + x * NW;
+            if (tc < ntiles) {
+                const int j = tc * RPW + g;
+                take_row(kr[x], vr[x], km[x], vm[x], j, j < nc);
+                if (tc + UNR * NW < ntiles) issue(x, tc + UNR * NW);
+            }
         }
     }
     __syncthreads();  // the quantised new row is in LDS
@@ -439,20 +533,31 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
         const uint4 vr = *reinterpret_cast<const uint4*>(&new_codes[1][c * 16]);
         take_row(kr, vr, new_meta[0][gi], new_meta[1][gi], nc, g == 0);
     }
+    // Remove the pair offsets (1024*weight, resp. 1024*weight/16), add the zero points, then
+    // add up the lane groups of each 16-lane row (they share m, so plain sums).
+    {
+        const float off_a = 1024.f * wsum, off_b = 64.f * wsum;
 #pragma unroll
-    for (int i = 0; i < 32; ++i) run.acc[i] += zacc;
+        for (int w = 0; w < 4; ++w)
 #pragma unroll
-    for (int off = LPR; off < 64; off <<= 1) run.merge_xor(off);
-    if (g == 0) {
+            for (int k = 0; k < 4; ++k) {
+                const float o = (k & 1) ? off_b : off_a;
+                acc[w * 8 + k] = row_groups_sum<LPR>(acc[w * 8 + k] - o + zacc);
+                acc[w * 8 + k + 4] = row_groups_sum<LPR>(acc[w * 8 + k + 4] - o + zacc);
+            }
+        l = row_groups_sum<LPR>(l);
+    }
+    if ((lane & 15) < LPR) {
+        const int p = wv * 4 + (lane >> 4);
 #pragma unroll
-        for (int i = 0; i < 32; ++i) part_acc[wv * D + c * 32 + i] = run.acc[i];
+        for (int i = 0; i < 32; ++i) part_acc[p * D + c * 32 + i] = acc[i];
         if (c == 0) {
-            part_m[wv] = run.m;
-            part_l[wv] = run.l;
+            part_m[p] = m;
+            part_l[p] = l;
         }
     }
     __syncthreads();
-    finish_unit<_Float16, D, NW>(a, u, s_lds, part_m, part_l, part_acc, cpre);
+    finish_unit<_Float16, D, NW * 64, NP>(a, u, s_lds, part_m, part_l, part_acc, cpre);
 }
 
 __global__ void clear_u32_kernel(uint32_t* p, size_t n) {
@@ -474,11 +579,12 @@ hipError_t launch_rows(const AttnArgs& a, int U, int nw, hipStream_t stream) {
 
 template <int D, int UNR>
 hipError_t launch_i4(const AttnArgs& a, int U, int nw, hipStream_t stream) {
-    const size_t lds = ((size_t)a.C + 2 * nw + (size_t)nw * D) * sizeof(float);
+    const size_t lds = ((size_t)a.C + 8 * nw + (size_t)4 * nw * D) * sizeof(float);
     switch (nw) {
+        case 1: attn_i4_kernel<D, 1, UNR><<<U, 64, lds, stream>>>(a); break;
+        case 2: attn_i4_kernel<D, 2, UNR><<<U, 128, lds, stream>>>(a); break;
         case 4: attn_i4_kernel<D, 4, UNR><<<U, 256, lds, stream>>>(a); break;
-        case 8: attn_i4_kernel<D, 8, UNR><<<U, 512, lds, stream>>>(a); break;
-        default: attn_i4_kernel<D, 16, UNR><<<U, 1024, lds, stream>>>(a); break;
+        default: attn_i4_kernel<D, 8, UNR><<<U, 512, lds, stream>>>(a); break;
     }
     return hipGetLastError();
 }
@@ -487,6 +593,16 @@ hipError_t launch_i4(const AttnArgs& a, int U, int nw, hipStream_t stream) {
 // resident rows: 16 waves with two K and two V loads in flight per lane (<= 64 VGPRs, so two
 // workgroups share a CU) is the fastest or within noise of it everywhere.
 int pick_waves(int /*U*/) { return 16; }
+
+// The 4-bit kernel is bound by ALU work, and the per-wave fixed work (query set-up, merging 32
+// accumulators, the epilogue) is paid once per wave: use as few waves per workgroup as still
+// give the chip about 3000 waves (measured: 1 wave per unit is fastest at 3072 units).
+int pick_waves_i4(int U) {
+    if (U >= 2048) return 1;
+    if (U >= 1024) return 2;
+    if (U >= 512) return 4;
+    return 8;
+}
 
 }  // namespace
 
@@ -519,7 +635,8 @@ hipError_t launch_decode_step(const Layout& L, const StepArgs& s, hipStream_t st
     if (L.kv_dtype == KV_F16)
         return L.d == 64 ? launch_rows<_Float16, 64, 2>(a, L.U, nw, stream)
                          : launch_rows<_Float16, 128, 2>(a, L.U, nw, stream);
-    return L.d == 64 ? launch_i4<64, 2>(a, L.U, nw, stream) : launch_i4<128, 2>(a, L.U, nw, stream);
+    const int nw4 = pick_waves_i4(L.U);
+    return L.d == 64 ? launch_i4<64, 4>(a, L.U, nw4, stream) : launch_i4<128, 4>(a, L.U, nw4, stream);
 }
 
 hipError_t launch_clear_counters(const Layout& L, hipStream_t stream) {

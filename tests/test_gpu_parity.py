@@ -53,7 +53,8 @@ def test_threshold_on_resident_count_and_explicit_scale(kv, d):
     assert st["compressions"] >= 5
 
 
-@pytest.mark.parametrize("units,kv", [(1100, KV_F16), (2100, KV_F16), (1030, KV_I4G64), (2050, KV_F32)])
+@pytest.mark.parametrize("units,kv", [(1100, KV_F16), (2100, KV_F16), (520, KV_I4G64), (1030, KV_I4G64),
+                                      (2060, KV_I4G64), (2050, KV_F32)])
 def test_many_units_select_other_workgroup_shapes(units, kv):
     """Unit counts on both sides of the points where the launcher changes the workgroup size."""
     d = 64 if kv == KV_F32 else 128
