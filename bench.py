@@ -26,6 +26,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
+# HBM bytes per decode-attention launch measured with rocprofv3 counters (FETCH_SIZE x 2.000 +
+# WRITE_SIZE x 1.000, factors from a copy of known size) for the headline workload in this
+# launch configuration; see profiles/attn_rows_fp16_cfg2_hbm_traffic.md.  Other workloads: null.
+MEASURED_TRAFFIC_BYTES = {"cfg2-opt6.7b-fp16": 253.56e6}
+
 
 def algorithmic_bytes(wl, n: int) -> int:
     """Bytes one decode-attention launch must move when n rows are resident after the append:
@@ -198,7 +203,8 @@ def main() -> int:
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": None if achieved is None else achieved / HBM_PEAK_GBS, "traffic": None,
+            "frac": None if achieved is None else achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if R == 3 else None,
             "kernel": kernel_name, "kernel_ms_avg": kern_ms, "algorithmic_bytes_per_launch": alg,
         },
     }
