@@ -14,6 +14,8 @@
 // threshold, bump the counters and (optionally) dump the probabilities.
 #include "sc_kernels.hpp"
 
+#include <type_traits>
+
 namespace sc {
 namespace {
 
@@ -450,7 +452,11 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < 32; ++i) acc[i] = 0.f;
 
-    auto take_row = [&](const uint4& kr, const uint4& vr, uint32_t kmw, uint32_t vmw, int j, bool valid) {
+    // One cache row per lane group.  `masked` (a compile-time tag) is only true for the one
+    // ragged tile at the end of the cache and for the new row, where some groups hold no row.
+    auto take_row = [&](auto masked, const uint4& kr, const uint4& vr, uint32_t kmw, uint32_t vmw, int j,
+                        bool valid) {
+        constexpr bool MASKED = decltype(masked)::value;
         const uint32_t kw[4] = {kr.x, kr.y, kr.z, kr.w};
         float da = qa0, db = qb0;
 #pragma unroll
@@ -467,19 +473,28 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
         vm.u32 = vmw;
         const float dotc = fmaf(db, 0.0625f, da);  // sum of q*code over this lane's channels
         float s = group_sum<LPR>(fmaf((float)km.h[0], dotc, (float)km.h[1] * qsum)) * a.qk_log2;
-        if (valid && c == 0) s_lds[j] = s;
-        s = valid ? s : -INFINITY;
-        const float smax = row_groups_max<LPR>(s);
-        if (smax > m) {  // same decision in all 16 lanes of the row
-            const float al = fast_exp2(m - smax);
-            l *= al;
-            wsum *= al;
-            zacc *= al;
-#pragma unroll
-            for (int i = 0; i < 32; ++i) acc[i] *= al;
-            m = smax;
+        if constexpr (MASKED) {
+            if (valid && c == 0) s_lds[j] = s;
+            s = valid ? s : -INFINITY;
+        } else {
+            s_lds[j] = s;  // the LPR lanes of a group store the same value to the same address
         }
-        const float e = valid ? fast_exp2(s - m) : 0.f;
+        // The running maximum moves rarely: only when some lane of the wave sees a score above
+        // its row's maximum is the row maximum formed (same decision in all 16 lanes of a row).
+        if (__builtin_amdgcn_ballot_w64(s > m) != 0ull) {
+            const float smax = row_groups_max<LPR>(s);
+            if (smax > m) {
+                const float al = fast_exp2(m - smax);
+                l *= al;
+                wsum *= al;
+                zacc *= al;
+#pragma unroll
+                for (int i = 0; i < 32; ++i) acc[i] *= al;
+                m = smax;
+            }
+        }
+        float e = fast_exp2(s - m);
+        if constexpr (MASKED) e = valid ? e : 0.f;
         l += e;
         const float es = e * (float)vm.h[0];
         const float es16 = es * 0.0625f;
@@ -498,20 +513,37 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
             }
         }
     };
+    using Full = std::integral_constant<bool, false>;
+    using Ragged = std::integral_constant<bool, true>;
 
     // A ring of UNR tiles (RPW cache rows each) per wave: as soon as a tile has been consumed
     // its registers are refilled with the tile UNR positions ahead, so UNR-1 tiles of loads
-    // stay in flight behind the arithmetic.  Wave w owns tiles w, w+NW, w+2NW, ...
+    // stay in flight behind the arithmetic.  Wave w owns tiles w, w+NW, w+2NW, ...; tiles are
+    // requested in increasing order, so one running byte offset (codes) and one running word
+    // offset (meta) serve every refill.  Tiles below `nfull` are complete; at most one ragged
+    // tile follows them.
+    const int nfull = nc / RPW;
     const int ntiles = (nc + RPW - 1) / RPW;
     uint4 kr[UNR], vr[UNR];
     uint32_t km[UNR], vm[UNR];
+    uint32_t code_off = ((uint32_t)(wv * RPW + g)) * ROWB + (uint32_t)c * 16u;
+    uint32_t meta_off = ((uint32_t)(wv * RPW + g)) * GPR + (uint32_t)gi;
     auto issue = [&](int x, int tile) {
-        const int j = tile * RPW + g;
-        const uint32_t jj = j < nc ? (uint32_t)j : 0u;
-        kr[x] = load_stream16(Kb, jj * ROWB + (uint32_t)c * 16u);
-        vr[x] = load_stream16(Vb, jj * ROWB + (uint32_t)c * 16u);
-        km[x] = __builtin_nontemporal_load(Kmb + jj * GPR + gi);
-        vm[x] = __builtin_nontemporal_load(Vmb + jj * GPR + gi);
+        if (tile < nfull) {
+            kr[x] = load_stream16(Kb, code_off);
+            vr[x] = load_stream16(Vb, code_off);
+            km[x] = __builtin_nontemporal_load(Kmb + meta_off);
+            vm[x] = __builtin_nontemporal_load(Vmb + meta_off);
+        } else {
+            const int j = tile * RPW + g;
+            const uint32_t jj = j < nc ? (uint32_t)j : 0u;
+            kr[x] = load_stream16(Kb, jj * ROWB + (uint32_t)c * 16u);
+            vr[x] = load_stream16(Vb, jj * ROWB + (uint32_t)c * 16u);
+            km[x] = Kmb[jj * GPR + gi];
+            vm[x] = Vmb[jj * GPR + gi];
+        }
+        code_off += NW * RPW * ROWB;
+        meta_off += NW * RPW * GPR;
     };
 #pragma unroll
     for (int x = 0; x < UNR; ++x)
@@ -522,7 +554,10 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
             const int tc = t + x * NW;
             if (tc < ntiles) {
                 const int j = tc * RPW + g;
-                take_row(kr[x], vr[x], km[x], vm[x], j, j < nc);
+                if (tc < nfull)
+                    take_row(Full{}, kr[x], vr[x], km[x], vm[x], j, true);
+                else
+                    take_row(Ragged{}, kr[x], vr[x], km[x], vm[x], j, j < nc);
                 if (tc + UNR * NW < ntiles) issue(x, tc + UNR * NW);
             }
         }
@@ -531,7 +566,7 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
     if (wv == 0) {
         const uint4 kr = *reinterpret_cast<const uint4*>(&new_codes[0][c * 16]);
         const uint4 vr = *reinterpret_cast<const uint4*>(&new_codes[1][c * 16]);
-        take_row(kr, vr, new_meta[0][gi], new_meta[1][gi], nc, g == 0);
+        take_row(Ragged{}, kr, vr, new_meta[0][gi], new_meta[1][gi], nc, g == 0);
     }
     // Remove the pair offsets (1024*weight, resp. 1024*weight/16), add the zero points, then
     // add up the lane groups of each 16-lane row (they share m, so plain sums).
