@@ -103,12 +103,15 @@ struct Running {
 };
 
 // Counter words: two 16-bit counters (slots 2i and 2i+1) per 32-bit word.  Each thread owns
-// the words i = tid, tid + NT, ...; the first CNT_PF of them are fetched when the kernel
-// starts so that their latency is hidden behind the K/V stream.
-constexpr int CNT_PF = 2;
+// the words i = tid, tid + NT, ...; the first cnt_pf(NT) of them (enough for 768 resident
+// rows, more with many threads) are fetched when the kernel starts so that their latency is
+// hidden behind the K/V stream: a dependent load per word in the epilogue costs a full
+// memory round trip each.
+constexpr int cnt_pf(int nt) { return nt >= 384 ? 1 : 384 / nt; }
 
 template <int NT>
-__device__ __forceinline__ void prefetch_counters(const AttnArgs& a, int u, uint32_t (&pre)[CNT_PF]) {
+__device__ __forceinline__ void prefetch_counters(const AttnArgs& a, int u, uint32_t (&pre)[cnt_pf(NT)]) {
+    constexpr int CNT_PF = cnt_pf(NT);
     const uint32_t* cw = reinterpret_cast<const uint32_t*>(a.cnt + (size_t)u * a.cnt_unit_stride);
 #pragma unroll
     for (int k = 0; k < CNT_PF; ++k) {
@@ -123,7 +126,8 @@ __device__ __forceinline__ void prefetch_counters(const AttnArgs& a, int u, uint
 template <typename TOut, int D, int NT, int NP>
 __device__ __forceinline__ void finish_unit(const AttnArgs& a, int u, const float* s_lds,
                                             const float* part_m, const float* part_l,
-                                            const float* part_acc, const uint32_t (&pre)[CNT_PF]) {
+                                            const float* part_acc, const uint32_t (&pre)[cnt_pf(NT)]) {
+    constexpr int CNT_PF = cnt_pf(NT);
     const int tid = threadIdx.x;
     float M = part_m[0];
 #pragma unroll
@@ -208,7 +212,7 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
         k_own.raw = *reinterpret_cast<const uint4*>((const T*)a.k_new + in_off);
         v_own.raw = *reinterpret_cast<const uint4*>((const T*)a.v_new + in_off);
     }
-    uint32_t cpre[CNT_PF];
+    uint32_t cpre[cnt_pf(NW * 64)];
     prefetch_counters<NW * 64>(a, u, cpre);
 
     float qf[EPL];
@@ -293,16 +297,16 @@ union MetaWord {
     _Float16 h[2];  // scale, zero
 };
 
-// Quantise one row of D fp16 channels held two per lane (lane i: channels 2i, 2i+1; lanes
-// >= D/2 idle) and store codes and meta to `codes` / `meta` (global) and to their LDS copies.
+// Quantise one row of D fp16 channels held two per lane (lane i holds x0 = channel 2i and
+// x1 = channel 2i+1; lanes >= D/2 idle) and store codes and meta to `codes` / `meta` (global)
+// and to their LDS copies.
 // Every operation is a single IEEE fp32 operation so the codes are reproducible anywhere:
 // zero = min, scale = fp16((max-min)/15) (1 when that is 0),
 // code = clamp(rint((x-zero)/scale), 0, 15).
 template <int D>
-__device__ __forceinline__ void quantise_row(const _Float16* src, unsigned char* codes, uint32_t* meta,
+__device__ __forceinline__ void quantise_row(float x0, float x1, unsigned char* codes, uint32_t* meta,
                                              unsigned char* lds_codes, uint32_t* lds_meta, int lane) {
     if (lane < D / 2) {
-        const float x0 = (float)src[2 * lane], x1 = (float)src[2 * lane + 1];
         float mn = fminf(x0, x1), mx = fmaxf(x0, x1);
 #pragma unroll
         for (int off = 1; off < 32; off <<= 1) {
@@ -415,11 +419,13 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
     // workgroup is a single wave) the value row.
     for (int which = wv; which < 2; which += NW) {
         const _Float16* src = (const _Float16*)(which ? a.v_new : a.k_new) + (size_t)u * a.in_stride;
-        quantise_row<D>(src, (which ? Vb : Kb) + (size_t)nc * ROWB,
+        const float x0 = lane < D / 2 ? (float)src[2 * lane] : 0.f;
+        const float x1 = lane < D / 2 ? (float)src[2 * lane + 1] : 0.f;
+        quantise_row<D>(x0, x1, (which ? Vb : Kb) + (size_t)nc * ROWB,
                         (which ? Vmb : Kmb) + (size_t)nc * GPR, new_codes[which], new_meta[which], lane);
         if (which == 0 && lane == 0) a.pos[(size_t)u * a.C + nc] = a.pos_value;
     }
-    uint32_t cpre[CNT_PF];
+    uint32_t cpre[cnt_pf(NW * 64)];
     prefetch_counters<NW * 64>(a, u, cpre);
 
     // q of this lane's 32 channels as fp16 pairs matching unpack8, and the constants that
@@ -595,6 +601,281 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
     finish_unit<_Float16, D, NW * 64, NP>(a, u, s_lds, part_m, part_l, part_acc, cpre);
 }
 
+// ---------------------------------------------------------------------------------------
+// 4-bit rows, head_dim 128, key side on the matrix cores.
+//
+// The 4-bit kernel above is limited by vector-ALU issue, not by HBM.  Here the q.k products
+// move to MFMA (v_mfma_f32_16x16x32_f16), which runs beside the vector ALU: a tile of 16 cache
+// rows is the B operand (lane l = row l%16, 16 bytes = channels 32*(l/16) .. +31; one 32-bit
+// word of codes becomes the 8 fp16 values a lane owes one MFMA with four AND-ORs), q is the A
+// operand, laid out once per launch.  The M dimension, useless for a single query, separates
+// the two quantisation groups of a row (output row 0: channels 0-63, row 1: channels 64-127)
+// and repeats them for every 16-lane row, so each lane finds both sums for its own cache row
+// in its accumulator registers and no shuffle is needed.  The value side stays on the vector
+// ALU (its contraction runs over cache rows, which no lane holds contiguously).
+// ---------------------------------------------------------------------------------------
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+union CodeOctet {  // the 8 codes of one 32-bit word as fp16: {n0, n4, 16*n1, 16*n5, n2, n6, 16*n3, 16*n7} + 1024
+    half2_t h2[4];
+    half8_t h8;
+};
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) { return v + dpp_f32<CTRL>(v); }
+
+// Sum / max over the 16 lanes of a DPP row (every lane ends with the result).
+__device__ __forceinline__ float row16_sum(float v) {
+    v = dpp_add<0xB1>(v);
+    v = dpp_add<0x4E>(v);
+    v = dpp_add<0x141>(v);
+    return dpp_add<0x140>(v);
+}
+__device__ __forceinline__ float row16_max(float v) {
+    v = dpp_max<0xB1>(v);
+    v = dpp_max<0x4E>(v);
+    v = dpp_max<0x141>(v);
+    return dpp_max<0x140>(v);
+}
+
+template <int NW, int UNR>
+__global__ void __launch_bounds__(NW * 64) attn_i4_mfma_kernel(AttnArgs a) {
+    constexpr int D = 128;
+    constexpr int RPW = 16;           // cache rows per tile (one wave load)
+    constexpr int GPR = 2;            // quantisation groups per cache row
+    constexpr uint32_t ROWB = D / 2;  // bytes of codes per cache row
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    float* s_lds = reinterpret_cast<float*>(smem_raw);
+    float* part_m = s_lds + a.C;
+    float* part_l = part_m + NW;
+    float* part_acc = part_l + NW;
+    __shared__ __align__(16) unsigned char new_codes[2][ROWB];  // [0] key row, [1] value row
+    __shared__ __align__(8) uint32_t new_meta[2][GPR];
+
+    const int u = blockIdx.x;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int r = lane & 15;   // cache row inside a tile
+    const int kb = lane >> 4;  // which 32 channels of the row this lane holds
+    const int gi = kb >> 1;    // their quantisation group
+    const int nc = a.n - 1;
+    unsigned char* Kb = (unsigned char*)a.K + (size_t)u * a.C * ROWB;
+    unsigned char* Vb = (unsigned char*)a.V + (size_t)u * a.C * ROWB;
+    uint32_t* Kmb = (uint32_t*)a.K_meta + (size_t)u * a.C * GPR;
+    uint32_t* Vmb = (uint32_t*)a.V_meta + (size_t)u * a.C * GPR;
+
+    // Everything small the kernel needs is requested first (the raw new row, q, the counter
+    // words), then the first tiles of the K/V stream; the set-up below only waits for the
+    // former while the latter are already in flight.
+    constexpr int NQ = NW == 1 ? 2 : 1;  // new rows this wave may have to quantise
+    _Float16 nx[NQ][2];
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+        const int which = wv + i * NW;
+        nx[i][0] = nx[i][1] = (_Float16)0.f;
+        if (which < 2) {
+            const _Float16* src = (const _Float16*)(which ? a.v_new : a.k_new) + (size_t)u * a.in_stride;
+            const half2_t pair = *reinterpret_cast<const half2_t*>(src + 2 * lane);
+            nx[i][0] = pair[0];
+            nx[i][1] = pair[1];
+        }
+    }
+    Frag<_Float16, 8> qraw[4];
+    {
+        const _Float16* qu = (const _Float16*)a.q + (size_t)u * a.in_stride + kb * 32;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) qraw[t].raw = *reinterpret_cast<const uint4*>(qu + t * 8);
+    }
+    uint32_t cpre[cnt_pf(NW * 64)];
+    prefetch_counters<NW * 64>(a, u, cpre);
+
+    // Ring of UNR tiles per wave, refilled as soon as consumed (see attn_i4_kernel).
+    const int nfull = nc / RPW;
+    const int ntiles = (nc + RPW - 1) / RPW;
+    uint4 kr[UNR], vr[UNR];
+    uint2 km[UNR];
+    uint32_t vm[UNR];
+    uint32_t code_off = ((uint32_t)(wv * RPW + r)) * ROWB + (uint32_t)kb * 16u;
+    uint32_t meta_off = ((uint32_t)(wv * RPW + r)) * GPR;
+    auto issue = [&](int x, int tile) {
+        if (tile < nfull) {
+            kr[x] = load_stream16(Kb, code_off);
+            vr[x] = load_stream16(Vb, code_off);
+            km[x] = *reinterpret_cast<const uint2*>(Kmb + meta_off);
+            vm[x] = Vmb[meta_off + gi];
+        } else {
+            const int j = tile * RPW + r;
+            const uint32_t jj = j < nc ? (uint32_t)j : 0u;
+            kr[x] = load_stream16(Kb, jj * ROWB + (uint32_t)kb * 16u);
+            vr[x] = load_stream16(Vb, jj * ROWB + (uint32_t)kb * 16u);
+            km[x] = *reinterpret_cast<const uint2*>(Kmb + jj * GPR);
+            vm[x] = Vmb[jj * GPR + gi];
+        }
+        code_off += NW * RPW * ROWB;
+        meta_off += NW * RPW * GPR;
+    };
+#pragma unroll
+    for (int x = 0; x < UNR; ++x)
+        if (wv + x * NW < ntiles) issue(x, wv + x * NW);
+
+    // Alg. 1 model update: wave 0 quantises the key row, wave 1 (wave 0 again when the
+    // workgroup is a single wave) the value row.
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+        const int which = wv + i * NW;
+        if (which < 2) {
+            quantise_row<D>((float)nx[i][0], (float)nx[i][1], (which ? Vb : Kb) + (size_t)nc * ROWB,
+                            (which ? Vmb : Kmb) + (size_t)nc * GPR, new_codes[which], new_meta[which], lane);
+            if (which == 0 && lane == 0) a.pos[(size_t)u * a.C + nc] = a.pos_value;
+        }
+    }
+
+    // A operands: qa[t] feeds the MFMA that consumes word t of every lane's 16 bytes.  Lane l
+    // holds A[i = l%16][k = 8*(l/16) .. +7]; k-block kb, element e stands for channel
+    // 32*kb + 8*t + {0,4,1,5,2,6,3,7}[e], divided by 16 where the code arrives multiplied by
+    // 16.  Output rows i%4 == 0 take the channels of group 0 (k-blocks 0,1), rows i%4 == 1
+    // those of group 1 (k-blocks 2,3), other rows are zero.  c0[g] = -(what the +1024 of every
+    // code adds up to for group g), qs[g] = sum of q over group g (for the zero points).
+    half8_t qa[4];
+    float c0[2], qs[2];
+    {
+        const bool mine = ((r & 3) == 0 && gi == 0) || ((r & 3) == 1 && gi == 1);
+        float sa = 0.f, sb = 0.f;  // sums over the plain / the x16 positions of this lane's 32 channels
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const Frag<_Float16, 8>& qr = qraw[t];
+            const _Float16 sixteenth = (_Float16)0.0625f;
+            half8_t v = {qr.e[0], qr.e[4], qr.e[1] * sixteenth, qr.e[5] * sixteenth,
+                         qr.e[2], qr.e[6], qr.e[3] * sixteenth, qr.e[7] * sixteenth};
+            sa += (float)qr.e[0] + (float)qr.e[4] + (float)qr.e[2] + (float)qr.e[6];
+            sb += (float)qr.e[1] + (float)qr.e[5] + (float)qr.e[3] + (float)qr.e[7];
+            const half8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
+            qa[t] = mine ? v : zero;
+        }
+        // the other half of this lane's group sits 16 lanes away, the other group 32 lanes away
+        const float off = 1024.f * sa + 64.f * sb, sum = sa + sb;
+        const float off_g = off + __shfl_xor(off, 16), sum_g = sum + __shfl_xor(sum, 16);
+        const float off_o = __shfl_xor(off_g, 32), sum_o = __shfl_xor(sum_g, 32);
+        c0[0] = -(gi == 0 ? off_g : off_o);
+        c0[1] = -(gi == 0 ? off_o : off_g);
+        qs[0] = gi == 0 ? sum_g : sum_o;
+        qs[1] = gi == 0 ? sum_o : sum_g;
+    }
+
+    // Running softmax, one maximum per wave: m; per lane l (sum of weights of its cache rows),
+    // acc (32 channels, still carrying the pair offsets), wsum (sum of weight*scale, to remove
+    // those offsets) and zacc (sum of weight*zero).
+    float m = -INFINITY, l = 0.f, wsum = 0.f, zacc = 0.f, acc[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) acc[i] = 0.f;
+
+    auto take_tile = [&](auto masked, const uint4& kr, const uint4& vr, uint2 kmw, uint32_t vmw, int j,
+                         bool valid) {
+        constexpr bool MASKED = decltype(masked)::value;
+        const uint32_t kw[4] = {kr.x, kr.y, kr.z, kr.w};
+        float4_t d = {c0[0], c0[1], 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            CodeOctet b;
+            unpack8(kw[t], b.h2);
+            d = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[t], b.h8, d, 0, 0, 0);
+        }
+        MetaWord k0, k1, vm;
+        k0.u32 = kmw.x;
+        k1.u32 = kmw.y;
+        vm.u32 = vmw;
+        float s = fmaf((float)k0.h[0], d[0], (float)k0.h[1] * qs[0]);
+        s = fmaf((float)k1.h[0], d[1], s);
+        s = fmaf((float)k1.h[1], qs[1], s) * a.qk_log2;
+        if constexpr (MASKED) {
+            if (valid && kb == 0) s_lds[j] = s;
+            s = valid ? s : -INFINITY;
+        } else {
+            s_lds[j] = s;  // the four lanes that hold row j store the same value
+        }
+        if (__builtin_amdgcn_ballot_w64(s > m) != 0ull) {  // rare once the maximum has settled
+            float smax = row16_max(s);  // over the 16 rows of the tile ...
+            smax = fmaxf(smax, __shfl_xor(smax, 16));  // ... and made identical in all four
+            smax = fmaxf(smax, __shfl_xor(smax, 32));  // 16-lane rows, whatever their rounding
+            const float al = fast_exp2(m - smax);
+            l *= al;
+            wsum *= al;
+            zacc *= al;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) acc[i] *= al;
+            m = smax;
+        }
+        float e = fast_exp2(s - m);
+        if constexpr (MASKED) e = valid ? e : 0.f;
+        l += e;
+        const float es = e * (float)vm.h[0];
+        const float es16 = es * 0.0625f;
+        wsum += es;
+        zacc = fmaf(e, (float)vm.h[1], zacc);
+        const uint32_t vw[4] = {vr.x, vr.y, vr.z, vr.w};
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            half2_t h[4];
+            unpack8(vw[w], h);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float wk = (k & 1) ? es16 : es;
+                acc[w * 8 + k] = fmaf((float)h[k][0], wk, acc[w * 8 + k]);
+                acc[w * 8 + k + 4] = fmaf((float)h[k][1], wk, acc[w * 8 + k + 4]);
+            }
+        }
+    };
+    using Full = std::integral_constant<bool, false>;
+    using Ragged = std::integral_constant<bool, true>;
+
+    for (int t = wv; t < ntiles; t += UNR * NW) {
+#pragma unroll
+        for (int x = 0; x < UNR; ++x) {
+            const int tc = t + x * NW;
+            if (tc < ntiles) {
+                const int j = tc * RPW + r;
+                if (tc < nfull)
+                    take_tile(Full{}, kr[x], vr[x], km[x], vm[x], j, true);
+                else
+                    take_tile(Ragged{}, kr[x], vr[x], km[x], vm[x], j, j < nc);
+                if (tc + UNR * NW < ntiles) issue(x, tc + UNR * NW);
+            }
+        }
+    }
+    __syncthreads();  // the quantised new row is in LDS
+    if (wv == 0) {
+        const uint4 nk = *reinterpret_cast<const uint4*>(&new_codes[0][kb * 16]);
+        const uint4 nv = *reinterpret_cast<const uint4*>(&new_codes[1][kb * 16]);
+        take_tile(Ragged{}, nk, nv, make_uint2(new_meta[0][0], new_meta[0][1]), new_meta[1][gi], nc, r == 0);
+    }
+    // Add up the 16 cache rows of every DPP row, then remove the pair offsets (1024*weight,
+    // resp. 1024*weight/16) and add the zero points.
+    {
+        wsum = row16_sum(wsum);
+        zacc = row16_sum(zacc);
+        l = row16_sum(l);
+        const float off_a = 1024.f * wsum, off_b = 64.f * wsum;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float o = zacc - ((k & 1) ? off_b : off_a);
+                acc[w * 8 + k] = row16_sum(acc[w * 8 + k]) + o;
+                acc[w * 8 + k + 4] = row16_sum(acc[w * 8 + k + 4]) + o;
+            }
+    }
+    if (r == 0) {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) part_acc[wv * D + kb * 32 + i] = acc[i];
+        if (kb == 0) {
+            part_m[wv] = m;
+            part_l[wv] = l;
+        }
+    }
+    __syncthreads();
+    finish_unit<_Float16, D, NW * 64, NW>(a, u, s_lds, part_m, part_l, part_acc, cpre);
+}
+
 __global__ void clear_u32_kernel(uint32_t* p, size_t n) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -620,6 +901,18 @@ hipError_t launch_i4(const AttnArgs& a, int U, int nw, hipStream_t stream) {
         case 2: attn_i4_kernel<D, 2, UNR><<<U, 128, lds, stream>>>(a); break;
         case 4: attn_i4_kernel<D, 4, UNR><<<U, 256, lds, stream>>>(a); break;
         default: attn_i4_kernel<D, 8, UNR><<<U, 512, lds, stream>>>(a); break;
+    }
+    return hipGetLastError();
+}
+
+template <int UNR>
+hipError_t launch_i4_mfma(const AttnArgs& a, int U, int nw, hipStream_t stream) {
+    const size_t lds = ((size_t)a.C + 2 * nw + (size_t)nw * 128) * sizeof(float);
+    switch (nw) {
+        case 1: attn_i4_mfma_kernel<1, UNR><<<U, 64, lds, stream>>>(a); break;
+        case 2: attn_i4_mfma_kernel<2, UNR><<<U, 128, lds, stream>>>(a); break;
+        case 4: attn_i4_mfma_kernel<4, UNR><<<U, 256, lds, stream>>>(a); break;
+        default: attn_i4_mfma_kernel<8, UNR><<<U, 512, lds, stream>>>(a); break;
     }
     return hipGetLastError();
 }
@@ -671,7 +964,7 @@ hipError_t launch_decode_step(const Layout& L, const StepArgs& s, hipStream_t st
         return L.d == 64 ? launch_rows<_Float16, 64, 2>(a, L.U, nw, stream)
                          : launch_rows<_Float16, 128, 2>(a, L.U, nw, stream);
     const int nw4 = pick_waves_i4(L.U);
-    return L.d == 64 ? launch_i4<64, 4>(a, L.U, nw4, stream) : launch_i4<128, 4>(a, L.U, nw4, stream);
+    return L.d == 64 ? launch_i4<64, 4>(a, L.U, nw4, stream) : launch_i4_mfma<4>(a, L.U, nw4, stream);
 }
 
 hipError_t launch_clear_counters(const Layout& L, hipStream_t stream) {
