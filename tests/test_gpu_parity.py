@@ -64,6 +64,38 @@ def test_many_units_select_other_workgroup_shapes(units, kv):
     assert st["compressions"] >= 3
 
 
+@pytest.mark.parametrize("kv,d", [(KV_F16, 128), (KV_I4G64, 128), (KV_F32, 64)])
+def test_extreme_window_parameters(kv, d):
+    """Degenerate settings: every row outside the recent window is dropped at each compression
+    (m = n_trig - r), and a recent window that leaves exactly m candidates."""
+    wl = _wl("drop-all-candidates", 1, 3, d, kv, 60, 40, 24, 5, 20, 20)   # n_trig 25, m = 25 - 5
+    run = ParityRun(wl)
+    st = run.run()
+    assert st["compressions"] >= 4 and run.cache.n <= 24
+    wl = _wl("recent-is-almost-everything", 1, 2, d, kv, 50, 30, 24, 21, 8, 4)  # candidates = m = 4
+    st = ParityRun(wl).run()
+    assert st["compressions"] >= 10
+
+
+def test_maximum_capacity():
+    """The largest cache the library accepts (12288 slots: one unit's scores fill the LDS budget),
+    driven to its first compression and beyond; every 64th step and the steps around the
+    compression are compared with the oracle, all integer state bit for bit."""
+    cap = 12288
+    wl = _wl("max-capacity", 1, 2, 128, KV_F16, cap, 40, cap - 1, 64, 512, 256, 0.02)
+    run = ParityRun(wl)
+    for s in range(wl.total):
+        near = abs(s + 1 - cap) <= 2
+        due = run.step(check=(s % 64 == 0) or near or s == wl.total - 1)
+        if due:
+            run.compress(check_rows=True)
+    assert run.stats["compressions"] == 1 and run.cache.n == cap - 256 + 40
+    cfg = B.make_config(1, 2, 128, KV_F16, cap, 64, 512, 256)
+    with pytest.raises(B.ScError) as e:
+        B.sc_config_sizes(cfg)  # n_trig = 12289 does not fit
+    assert e.value.status == B.SC_ERR_UNSUPPORTED
+
+
 def test_budget_not_reached_is_full_attention():
     wl = _wl("no-evict", 1, 4, 128, KV_F16, 40, 30, 128, 8, 32, 16)
     run = ParityRun(wl)
