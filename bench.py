@@ -180,7 +180,10 @@ def main() -> int:
     else:
         alg = sum(algorithmic_bytes(wl, n) for n in n_log) / len(n_log)
         kern_ms, achieved = None, None
-    kernel_name = "attn_i4_kernel" if wl.kv_dtype not in (KV_F32, KV_F16) else "attn_rows_kernel"
+    if wl.kv_dtype in (KV_F32, KV_F16):
+        kernel_name = "attn_rows_kernel"
+    else:
+        kernel_name = "attn_i4_mfma_kernel" if wl.head_dim == 128 else "attn_i4_kernel"
     res = {
         "metric": "decode tokens/s with budgeted KV cache",
         "value": wl.batch * K / wall,

@@ -46,7 +46,7 @@ typedef enum {
     SC_ERR_WORKSPACE = 2,   /* workspace too small or not 256-byte aligned                    */
     SC_ERR_FULL = 3,        /* sc_decode_step while a compression is due                      */
     SC_ERR_STATE = 4,       /* sc_compress when none is due; sc_prefill on a non-empty cache  */
-    SC_ERR_UNSUPPORTED = 5, /* head_dim / kv_dtype / history-not-multiple-of-drop not built   */
+    SC_ERR_UNSUPPORTED = 5, /* head_dim / kv_dtype / sizes this build does not cover          */
     SC_ERR_DEVICE = 6       /* a kernel launch failed (hipGetLastError)                       */
 } sc_status;
 
@@ -72,6 +72,13 @@ typedef enum {
     SC_THRESH_INV_LEN = 1  /* 1/n, n = resident rows (the true average over a compacted cache)*/
 } sc_thresh;
 
+/* How the importance record of Alg. 2 (low-score counts over the last w steps) is stored.
+ * Both reproduce the history window exactly at every compression; they differ in cost. */
+typedef enum {
+    SC_WINDOW_AUTO = 0,   /* buckets when w is a multiple of m, else the exact ring           */
+    SC_WINDOW_RING = 1    /* one bit per (row, step) in a ring of w bits: any w, w/8 bytes/row */
+} sc_window;
+
 /* Problem statement of Def. 4.1 / inputs of Alg. 1 and Alg. 2. */
 typedef struct {
     int32_t batch, heads; /* U = batch*heads independent units                               */
@@ -79,10 +86,11 @@ typedef struct {
     int32_t kv_dtype;     /* sc_kv_dtype                                                     */
     int32_t budget;       /* B: token budget per unit (Alg. 1)                               */
     int32_t recent;       /* r: most recent rows never evicted (Alg. 2), r >= 1              */
-    int32_t history;      /* w: history window in steps (Alg. 2); must be a multiple of drop */
+    int32_t history;      /* w: history window in steps (Alg. 2), 1 <= w <= 8192             */
     int32_t drop;         /* m: rows dropped per compression (Alg. 2), 1 <= m <= n_trig - r  */
     int32_t trigger;      /* sc_trigger                                                      */
     int32_t thresh_mode;  /* sc_thresh                                                       */
+    int32_t window_mode;  /* sc_window                                                       */
     float scale;          /* score scale; 0 selects 1/sqrt(head_dim)                         */
 } sc_config;
 
@@ -90,9 +98,11 @@ typedef struct {
  *   n_trig   : number of resident rows at which a compression becomes due
  *   capacity : row stride of every per-unit array (n_trig rounded up to a multiple of 64);
  *              also the leading dimension of probs_out
- *   buckets  : E = w/m counter buckets kept per row
+ *   buckets  : E = w/m 16-bit counter buckets kept per row (0 when the exact ring is used)
+ *   ring_words : ceil(w/32) 32-bit ring words kept per row (0 when buckets are used)
  * Returns SC_ERR_INVALID_ARG / SC_ERR_UNSUPPORTED for a bad configuration. */
-sc_status sc_config_sizes(const sc_config *cfg, int32_t *n_trig, int32_t *capacity, int32_t *buckets);
+sc_status sc_config_sizes(const sc_config *cfg, int32_t *n_trig, int32_t *capacity, int32_t *buckets,
+                          int32_t *ring_words);
 
 /* Bytes of device workspace a cache of this configuration needs; 0 if cfg is invalid. */
 size_t sc_workspace_bytes(const sc_config *cfg);
@@ -102,7 +112,8 @@ size_t sc_workspace_bytes(const sc_config *cfg);
  * at or after t (may be negative), `bucket` = epoch mod E the counter bucket that step t
  * increments, `counted` = 0 for steps so early that they have left every history window
  * before the first compression.  The union of the E buckets at a compression step is
- * exactly the history window (t-w, t] of Alg. 2. */
+ * exactly the history window (t-w, t] of Alg. 2.  With the exact ring every step is counted,
+ * step t owns ring bit t mod w, and `bucket` is the index (t mod w)/32 of the word holding it. */
 sc_status sc_schedule(const sc_config *cfg, int64_t t, int64_t *epoch, int32_t *bucket, int32_t *counted);
 
 /* Create an empty cache (n = 0, t = 0) inside dev_workspace (device, 256-byte aligned,
@@ -155,7 +166,9 @@ sc_status sc_cache_len(const sc_cache *c, int32_t *n, int64_t *t);
  *   K_meta, V_meta : I4G64 only (else NULL): [U][capacity][head_dim/64] pairs of fp16
  *             (scale, zero); value = code*scale + zero
  *   pos     : int32 [U][capacity], 0-based position in the stream of the row in each slot
- *   cnt     : uint16 [U][buckets][capacity]; a row's record I is the sum over buckets */
+ *   cnt     : buckets: uint16 [U][buckets][capacity], a row's record I is the sum over buckets;
+ *             exact ring: the same pointer addresses uint32 [U][ring_words][capacity], bit
+ *             (s mod w) of a row's ring is the low-score flag of step s, I is the popcount */
 sc_status sc_cache_view(const sc_cache *c, const void **K, const void **V, const void **K_meta,
                         const void **V_meta, const int32_t **pos, const uint16_t **cnt,
                         int32_t *capacity, int32_t *buckets);

@@ -17,6 +17,7 @@ SC_OK, SC_ERR_INVALID_ARG, SC_ERR_WORKSPACE, SC_ERR_FULL, SC_ERR_STATE, SC_ERR_U
 SC_KV_F32, SC_KV_F16, SC_KV_I4G64 = 0, 1, 2
 SC_TRIGGER_HARD_CAP, SC_TRIGGER_HIGH_WATER = 0, 1
 SC_THRESH_INV_POS, SC_THRESH_INV_LEN = 0, 1
+SC_WINDOW_AUTO, SC_WINDOW_RING = 0, 1
 
 EXPORTS = (
     "sc_config_sizes", "sc_workspace_bytes", "sc_schedule", "sc_cache_create", "sc_cache_destroy",
@@ -27,7 +28,7 @@ EXPORTS = (
 class sc_config(C.Structure):
     _fields_ = [(k, C.c_int32) for k in (
         "batch", "heads", "head_dim", "kv_dtype", "budget", "recent", "history", "drop",
-        "trigger", "thresh_mode")] + [("scale", C.c_float)]
+        "trigger", "thresh_mode", "window_mode")] + [("scale", C.c_float)]
 
 
 class ScError(RuntimeError):
@@ -51,7 +52,7 @@ def lib():
     l = C.CDLL(LIB_PATH)
     vp, i32p, i64p = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int64)
     cfgp = C.POINTER(sc_config)
-    l.sc_config_sizes.argtypes = [cfgp, i32p, i32p, i32p]
+    l.sc_config_sizes.argtypes = [cfgp, i32p, i32p, i32p, i32p]
     l.sc_workspace_bytes.argtypes = [cfgp]
     l.sc_workspace_bytes.restype = C.c_size_t
     l.sc_schedule.argtypes = [cfgp, C.c_int64, i64p, i32p, i32p]
@@ -78,9 +79,10 @@ def _check(status: int, where: str):
 
 
 def make_config(batch, heads, head_dim, kv_dtype, budget, recent, history, drop,
-                trigger=SC_TRIGGER_HARD_CAP, thresh_mode=SC_THRESH_INV_POS, scale=0.0) -> sc_config:
+                trigger=SC_TRIGGER_HARD_CAP, thresh_mode=SC_THRESH_INV_POS, scale=0.0,
+                window_mode=SC_WINDOW_AUTO) -> sc_config:
     return sc_config(batch, heads, head_dim, kv_dtype, budget, recent, history, drop, trigger,
-                     thresh_mode, scale)
+                     thresh_mode, window_mode, scale)
 
 
 # ---- functions with the names of the C ABI -------------------------------------------------
@@ -90,10 +92,11 @@ def sc_status_str(status: int) -> str:
 
 
 def sc_config_sizes(cfg: sc_config):
-    """-> (n_trig, capacity, buckets)"""
-    a, b, c = C.c_int32(), C.c_int32(), C.c_int32()
-    _check(lib().sc_config_sizes(C.byref(cfg), C.byref(a), C.byref(b), C.byref(c)), "sc_config_sizes")
-    return a.value, b.value, c.value
+    """-> (n_trig, capacity, buckets, ring_words)"""
+    a, b, c, d = C.c_int32(), C.c_int32(), C.c_int32(), C.c_int32()
+    _check(lib().sc_config_sizes(C.byref(cfg), C.byref(a), C.byref(b), C.byref(c), C.byref(d)),
+           "sc_config_sizes")
+    return a.value, b.value, c.value, d.value
 
 
 def sc_workspace_bytes(cfg: sc_config) -> int:
@@ -168,7 +171,7 @@ class BudgetCache:
         self._torch = torch
         self.cfg = cfg
         self.device = torch.device(device)
-        self.n_trig, self.capacity, self.buckets = sc_config_sizes(cfg)
+        self.n_trig, self.capacity, self.buckets, self.ring_words = sc_config_sizes(cfg)
         self.units = cfg.batch * cfg.heads
         nbytes = sc_workspace_bytes(cfg)
         self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
@@ -222,7 +225,12 @@ class BudgetCache:
         return self._typed("pos", self._torch.int32, (self.units, self.capacity))
 
     def cnt(self):
+        """Bucket mode: int16 view [U, buckets, C] of the 16-bit counters (empty in ring mode)."""
         return self._typed("cnt", self._torch.int16, (self.units, self.buckets, self.capacity))
+
+    def ring(self):
+        """Ring mode: int32 view [U, ring_words, C] of the per-slot rings (empty in bucket mode)."""
+        return self._typed("cnt", self._torch.int32, (self.units, self.ring_words, self.capacity))
 
     def kv_rows(self):
         """(K, V) as stored: F32/F16 -> [U, C, d] tensors; I4G64 -> uint8 codes [U, C, d/2]."""

@@ -57,7 +57,7 @@ __device__ __forceinline__ void find_cut_bin(const int* hist, int* scan, int nee
 __global__ void __launch_bounds__(SEL_THREADS)
 select_evict_kernel(const uint16_t* __restrict__ cnt, int32_t* __restrict__ srcmap,
                     int32_t* __restrict__ first, int32_t* __restrict__ evicted, int n, int C, int E,
-                    int r, int m) {
+                    int W32, int r, int m) {
     extern __shared__ int smem[];
     int* I = smem;            // [C] record of every slot
     int* hist = I + C;        // [256]
@@ -66,12 +66,20 @@ select_evict_kernel(const uint16_t* __restrict__ cnt, int32_t* __restrict__ srcm
     int* res = wave_tot + SEL_WAVES;  // [2]
     const int u = blockIdx.x, t = threadIdx.x;
     const int ncand = n - r;
-    const uint16_t* cu = cnt + (size_t)u * E * C;
-
-    for (int j = t; j < n; j += SEL_THREADS) {
-        int acc = 0;
-        for (int b = 0; b < E; ++b) acc += cu[(size_t)b * C + j];
-        I[j] = acc;
+    if (W32) {  // exact ring: the record is the number of set bits in the slot's ring
+        const uint32_t* ru = reinterpret_cast<const uint32_t*>(cnt) + (size_t)u * W32 * C;
+        for (int j = t; j < n; j += SEL_THREADS) {
+            int acc = 0;
+            for (int b = 0; b < W32; ++b) acc += __popc(ru[(size_t)b * C + j]);
+            I[j] = acc;
+        }
+    } else {
+        const uint16_t* cu = cnt + (size_t)u * E * C;
+        for (int j = t; j < n; j += SEL_THREADS) {
+            int acc = 0;
+            for (int b = 0; b < E; ++b) acc += cu[(size_t)b * C + j];
+            I[j] = acc;
+        }
     }
     // m-th largest record among the candidates, by two 8-bit digit passes.
     hist[t] = 0;
@@ -157,7 +165,7 @@ struct CompactArgs {
     uint16_t* cnt;
     const int32_t* srcmap;
     const int32_t* first;
-    int C, E;
+    int C, E, W32;
     int row_lanes16;   // 16-byte pieces per K (or V) row
     int meta_words;    // 32-bit words of meta per row (0 when not 4-bit)
     int n_old, n_new;
@@ -182,6 +190,11 @@ __global__ void __launch_bounds__(256) compact_kernel(CompactArgs a) {
         return;
     }
     compact_array<int32_t, 4>(a.pos + (size_t)u * a.C, 1, map, first, a.n_new);
+    for (int b = 0; b < a.W32; ++b) {  // exact ring: every word plane moves with its row
+        uint32_t* rb = reinterpret_cast<uint32_t*>(a.cnt) + ((size_t)u * a.W32 + b) * a.C;
+        compact_array<uint32_t, 4>(rb, 1, map, first, a.n_new);
+        for (int j = a.n_new + threadIdx.x; j < a.n_old; j += blockDim.x) rb[j] = 0;
+    }
     for (int b = 0; b < a.E; ++b) {
         uint16_t* cb = a.cnt + ((size_t)u * a.E + b) * a.C;
         if (b == a.zero_bucket) {
@@ -198,7 +211,7 @@ __global__ void __launch_bounds__(256) compact_kernel(CompactArgs a) {
 hipError_t launch_compress(const Layout& L, const CompressArgs& c, hipStream_t stream) {
     const size_t lds = ((size_t)L.C + 512 + SEL_WAVES + 2) * sizeof(int);
     select_evict_kernel<<<L.U, SEL_THREADS, lds, stream>>>(L.cnt, L.srcmap, L.first, c.evicted, c.n, L.C,
-                                                           L.E, c.r, c.m);
+                                                           L.E, L.W32, c.r, c.m);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     CompactArgs a;
@@ -212,6 +225,7 @@ hipError_t launch_compress(const Layout& L, const CompressArgs& c, hipStream_t s
     a.first = L.first;
     a.C = L.C;
     a.E = L.E;
+    a.W32 = L.W32;
     if (L.kv_dtype == KV_F32) {
         a.row_lanes16 = L.d * 4 / 16;
         a.meta_words = 0;

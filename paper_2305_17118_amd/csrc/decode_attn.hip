@@ -52,8 +52,9 @@ struct AttnArgs {
     void* out;
     long out_stride;
     float* probs;
-    uint16_t* cnt;  // current bucket of unit 0
-    long cnt_unit_stride;
+    uint16_t* cnt;  // bucket mode: current bucket of unit 0; ring mode: this step's word plane
+    long cnt_unit_stride;  // in 16-bit units
+    uint32_t ring_bit;     // ring mode: this step's bit inside its word; 0 selects bucket mode
     int n, C;  // n counts the row appended by this launch
     float qk_log2, tau;
     int counted;
@@ -113,16 +114,19 @@ template <int NT>
 __device__ __forceinline__ void prefetch_counters(const AttnArgs& a, int u, uint32_t (&pre)[cnt_pf(NT)]) {
     constexpr int CNT_PF = cnt_pf(NT);
     const uint32_t* cw = reinterpret_cast<const uint32_t*>(a.cnt + (size_t)u * a.cnt_unit_stride);
+    const int per_word = a.ring_bit ? 1 : 2;  // slots covered by one 32-bit word
 #pragma unroll
     for (int k = 0; k < CNT_PF; ++k) {
         const int i = threadIdx.x + k * NT;
-        pre[k] = (a.counted && 2 * i < a.n) ? cw[i] : 0u;
+        pre[k] = (a.counted && per_word * i < a.n) ? cw[i] : 0u;
     }
 }
 
-// Shared tail of both attention kernels: combine the per-wave partials, write `out`, then the
-// probability epilogue with the counter update.
+// Shared tail of the attention kernels: combine the partials, write `out`, then the
+// probability epilogue with the update of the importance record (Alg. 2, kept online).
 // NT = threads of the workgroup, NP = number of partial (m, l, acc[D]) triples published in LDS.
+// Bucket mode: two 16-bit counters per word, +1 where the probability is below the threshold.
+// Ring mode: one 32-bit ring word per slot; this step's bit is set or cleared.
 template <typename TOut, int D, int NT, int NP>
 __device__ __forceinline__ void finish_unit(const AttnArgs& a, int u, const float* s_lds,
                                             const float* part_m, const float* part_l,
@@ -145,8 +149,24 @@ __device__ __forceinline__ void finish_unit(const AttnArgs& a, int u, const floa
         }
     }
     uint32_t* cw = reinterpret_cast<uint32_t*>(a.cnt + (size_t)u * a.cnt_unit_stride);
-    float2* probs = a.probs ? reinterpret_cast<float2*>(a.probs + (size_t)u * a.C) : nullptr;
     const int n = a.n;
+    if (a.ring_bit) {
+        float* probs = a.probs ? a.probs + (size_t)u * a.C : nullptr;
+        auto do_slot = [&](int j, uint32_t word) {
+            const float p = fast_exp2(s_lds[j] - M) * invL;
+            if (probs) probs[j] = p;
+            const uint32_t upd = (p < a.tau) ? (word | a.ring_bit) : (word & ~a.ring_bit);
+            if (upd != word) cw[j] = upd;
+        };
+#pragma unroll
+        for (int k = 0; k < CNT_PF; ++k) {
+            const int j = tid + k * NT;
+            if (j < n) do_slot(j, pre[k]);
+        }
+        for (int j = tid + CNT_PF * NT; j < n; j += NT) do_slot(j, cw[j]);
+        return;
+    }
+    float2* probs = a.probs ? reinterpret_cast<float2*>(a.probs + (size_t)u * a.C) : nullptr;
     auto do_word = [&](int i, uint32_t word) {
         const int j = 2 * i;  // j < n here; slot j+1 may be the first free one
         const float p0 = fast_exp2(s_lds[j] - M) * invL;
@@ -344,21 +364,30 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 // Two 4-bit codes of a 32-bit word, bits [lo, lo+4) of each 16-bit half, as a pair of fp16
 // numbers without any int->float conversion: OR-ing the bits into the mantissa of 1024.0
 // (0x6400, whose ulp is 1) gives 1024 + code for lo = 0 and 1024 + 16*code for lo = 4.
-__device__ __forceinline__ half2_t nibble_pair(uint32_t w, uint32_t mask) {
-    uint32_t r;
-    // one VALU instruction; the mask sits in a vector register and the constant in a scalar
-    // one because this encoding takes no literals and a single scalar operand
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(w), "v"(mask), "s"(0x64006400u));
-    return __builtin_bit_cast(half2_t, r);
+// The masks live in vector registers and the constant in a scalar one (made opaque to the
+// compiler once per kernel), because the single-instruction form (w & mask) | magic takes no
+// literals and one scalar operand; written as plain C so that the compiler, not inline
+// assembly, emits it and inserts the wait states a matrix instruction reading the result needs.
+struct NibbleConsts {
+    uint32_t lo, hi, magic;
+    __device__ __forceinline__ void init() {
+        asm volatile("v_mov_b32 %0, 0x000F000F" : "=v"(lo));
+        asm volatile("v_mov_b32 %0, 0x00F000F0" : "=v"(hi));
+        asm volatile("s_mov_b32 %0, 0x64006400" : "=s"(magic));
+    }
+};
+
+__device__ __forceinline__ half2_t nibble_pair(uint32_t w, uint32_t mask, uint32_t magic) {
+    return __builtin_bit_cast(half2_t, (w & mask) | magic);
 }
 
 // The eight codes of word w as four such pairs: {n0,n4}, {n1,n5}x16, {n2,n6}, {n3,n7}x16.
-__device__ __forceinline__ void unpack8(uint32_t w, half2_t (&h)[4]) {
+__device__ __forceinline__ void unpack8(uint32_t w, half2_t (&h)[4], const NibbleConsts& nk) {
     const uint32_t t = w >> 8;
-    h[0] = nibble_pair(w, 0x000F000Fu);
-    h[1] = nibble_pair(w, 0x00F000F0u);
-    h[2] = nibble_pair(t, 0x000F000Fu);
-    h[3] = nibble_pair(t, 0x00F000F0u);
+    h[0] = nibble_pair(w, nk.lo, nk.magic);
+    h[1] = nibble_pair(w, nk.hi, nk.magic);
+    h[2] = nibble_pair(t, nk.lo, nk.magic);
+    h[3] = nibble_pair(t, nk.hi, nk.magic);
 }
 
 template <int CTRL>
@@ -410,6 +439,8 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
     const int g = lane / LPR, c = lane % LPR;
     const int gi = c / 2;  // 64-channel group this lane's 32 channels fall in
     const int nc = a.n - 1;
+    NibbleConsts nk;
+    nk.init();
     unsigned char* Kb = (unsigned char*)a.K + (size_t)u * a.C * ROWB;
     unsigned char* Vb = (unsigned char*)a.V + (size_t)u * a.C * ROWB;
     uint32_t* Kmb = (uint32_t*)a.K_meta + (size_t)u * a.C * GPR;
@@ -468,7 +499,7 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             half2_t h[4];
-            unpack8(kw[w], h);
+            unpack8(kw[w], h, nk);
             da = __builtin_amdgcn_fdot2(h[0], qh[w * 4 + 0], da, false);
             db = __builtin_amdgcn_fdot2(h[1], qh[w * 4 + 1], db, false);
             da = __builtin_amdgcn_fdot2(h[2], qh[w * 4 + 2], da, false);
@@ -510,7 +541,7 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             half2_t h[4];
-            unpack8(vw[w], h);
+            unpack8(vw[w], h, nk);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const float wk = (k & 1) ? es16 : es;
@@ -659,6 +690,8 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_mfma_kernel(AttnArgs a) {
     const int kb = lane >> 4;  // which 32 channels of the row this lane holds
     const int gi = kb >> 1;    // their quantisation group
     const int nc = a.n - 1;
+    NibbleConsts nk;
+    nk.init();
     unsigned char* Kb = (unsigned char*)a.K + (size_t)u * a.C * ROWB;
     unsigned char* Vb = (unsigned char*)a.V + (size_t)u * a.C * ROWB;
     uint32_t* Kmb = (uint32_t*)a.K_meta + (size_t)u * a.C * GPR;
@@ -777,7 +810,7 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_mfma_kernel(AttnArgs a) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             CodeOctet b;
-            unpack8(kw[t], b.h2);
+            unpack8(kw[t], b.h2, nk);
             d = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[t], b.h8, d, 0, 0, 0);
         }
         MetaWord k0, k1, vm;
@@ -816,7 +849,7 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_mfma_kernel(AttnArgs a) {
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             half2_t h[4];
-            unpack8(vw[w], h);
+            unpack8(vw[w], h, nk);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const float wk = (k & 1) ? es16 : es;
@@ -949,8 +982,14 @@ hipError_t launch_decode_step(const Layout& L, const StepArgs& s, hipStream_t st
     a.out = s.out;
     a.out_stride = s.out_stride;
     a.probs = s.probs;
-    a.cnt = L.cnt + (size_t)s.bucket * L.C;
-    a.cnt_unit_stride = (long)L.E * L.C;
+    if (L.W32) {  // ring mode: word plane `bucket` of the uint32 [U][W32][C] ring
+        a.cnt = reinterpret_cast<uint16_t*>(reinterpret_cast<uint32_t*>(L.cnt) + (size_t)s.bucket * L.C);
+        a.cnt_unit_stride = 2L * L.W32 * L.C;
+    } else {
+        a.cnt = L.cnt + (size_t)s.bucket * L.C;
+        a.cnt_unit_stride = (long)L.E * L.C;
+    }
+    a.ring_bit = s.ring_bit;
     a.n = s.n;
     a.C = L.C;
     a.qk_log2 = s.qk_log2;
@@ -968,7 +1007,7 @@ hipError_t launch_decode_step(const Layout& L, const StepArgs& s, hipStream_t st
 }
 
 hipError_t launch_clear_counters(const Layout& L, hipStream_t stream) {
-    const size_t words = (size_t)L.U * L.E * L.C / 2;  // C is even
+    const size_t words = L.W32 ? (size_t)L.U * L.W32 * L.C : (size_t)L.U * L.E * L.C / 2;  // C is even
     clear_u32_kernel<<<1024, 256, 0, stream>>>(reinterpret_cast<uint32_t*>(L.cnt), words);
     return hipGetLastError();
 }

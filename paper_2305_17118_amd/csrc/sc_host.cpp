@@ -25,7 +25,7 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Sizes {
-    int32_t n_trig, C, E;
+    int32_t n_trig, C, E, W32;
     size_t row_bytes, meta_bytes;  // per K (or V) row
     size_t off_K, off_V, off_Km, off_Vm, off_pos, off_cnt, off_map, off_first, total;
 };
@@ -44,15 +44,17 @@ sc_status derive(const sc_config* cfg, Sizes* s) {
     if (cfg->budget > (1 << 20) || cfg->drop > (1 << 20)) return SC_ERR_INVALID_ARG;
     if (cfg->head_dim != 64 && cfg->head_dim != 128) return SC_ERR_UNSUPPORTED;
     if (cfg->kv_dtype < SC_KV_F32 || cfg->kv_dtype > SC_KV_I4G64) return SC_ERR_UNSUPPORTED;
-    if (cfg->history % cfg->drop != 0) return SC_ERR_UNSUPPORTED;
-    if (cfg->history > 65535) return SC_ERR_UNSUPPORTED;  // records are 16-bit
+    if (cfg->window_mode != SC_WINDOW_AUTO && cfg->window_mode != SC_WINDOW_RING) return SC_ERR_INVALID_ARG;
+    if (cfg->history > 8192) return SC_ERR_UNSUPPORTED;
     const int64_t n_trig =
         cfg->trigger == SC_TRIGGER_HIGH_WATER ? (int64_t)cfg->budget + cfg->drop : (int64_t)cfg->budget + 1;
     if (cfg->drop > n_trig - cfg->recent) return SC_ERR_INVALID_ARG;
     if (n_trig > 12288) return SC_ERR_UNSUPPORTED;  // one unit's scores must fit in LDS
     s->n_trig = (int32_t)n_trig;
     s->C = (int32_t)((n_trig + 63) / 64 * 64);
-    s->E = cfg->history / cfg->drop;
+    const bool ring = cfg->window_mode == SC_WINDOW_RING || cfg->history % cfg->drop != 0;
+    s->E = ring ? 0 : cfg->history / cfg->drop;
+    s->W32 = ring ? (cfg->history + 31) / 32 : 0;
     const size_t d = (size_t)cfg->head_dim;
     s->row_bytes = cfg->kv_dtype == SC_KV_F32 ? d * 4 : cfg->kv_dtype == SC_KV_F16 ? d * 2 : d / 2;
     s->meta_bytes = cfg->kv_dtype == SC_KV_I4G64 ? d / 64 * 4 : 0;
@@ -63,7 +65,7 @@ sc_status derive(const sc_config* cfg, Sizes* s) {
     s->off_Km = off;    off = align_up(off + rows * s->meta_bytes);
     s->off_Vm = off;    off = align_up(off + rows * s->meta_bytes);
     s->off_pos = off;   off = align_up(off + rows * 4);
-    s->off_cnt = off;   off = align_up(off + rows * (size_t)s->E * 2);
+    s->off_cnt = off;   off = align_up(off + rows * ((size_t)s->E * 2 + (size_t)s->W32 * 4));
     s->off_map = off;   off = align_up(off + rows * 4);
     s->off_first = off; off = align_up(off + (size_t)cfg->batch * cfg->heads * 4);
     s->total = off;
@@ -94,9 +96,17 @@ sc_status step_impl(sc_cache* c, const void* q, const void* k_new, const void* v
     a.probs = probs_out;
     a.n = n1;
     a.pos_value = (int)(t1 - 1);
-    const int64_t ep = epoch_of(t1, c->n_trig, c->cfg.drop);
-    a.bucket = bucket_of(ep, c->L.E);
-    a.counted = ep > -(int64_t)c->L.E;
+    if (c->L.W32) {
+        const int64_t rho = t1 % c->cfg.history;  // ring bit owned by this step
+        a.bucket = (int)(rho >> 5);
+        a.ring_bit = 1u << (rho & 31);
+        a.counted = 1;
+    } else {
+        const int64_t ep = epoch_of(t1, c->n_trig, c->cfg.drop);
+        a.bucket = bucket_of(ep, c->L.E);
+        a.ring_bit = 0;
+        a.counted = ep > -(int64_t)c->L.E;
+    }
     a.qk_log2 = c->qk_log2;
     a.tau = c->cfg.thresh_mode == SC_THRESH_INV_LEN ? 1.0f / (float)n1 : 1.0f / (float)t1;
     if (sc::launch_decode_step(c->L, a, stream) != hipSuccess) return SC_ERR_DEVICE;
@@ -111,8 +121,11 @@ sc_status compress_impl(sc_cache* c, int32_t* evicted_out, hipStream_t stream) {
     a.r = c->cfg.recent;
     a.m = c->cfg.drop;
     // The step that made the cache full closed epoch k; the following steps count into k+1.
-    const int64_t ep = epoch_of(c->t, c->n_trig, c->cfg.drop);
-    a.zero_bucket = bucket_of(ep + 1, c->L.E);
+    a.zero_bucket = -1;
+    if (c->L.E) {
+        const int64_t ep = epoch_of(c->t, c->n_trig, c->cfg.drop);
+        a.zero_bucket = bucket_of(ep + 1, c->L.E);
+    }
     a.evicted = evicted_out;
     if (sc::launch_compress(c->L, a, stream) != hipSuccess) return SC_ERR_DEVICE;
     c->n -= c->cfg.drop;
@@ -123,13 +136,15 @@ sc_status compress_impl(sc_cache* c, int32_t* evicted_out, hipStream_t stream) {
 
 extern "C" {
 
-sc_status sc_config_sizes(const sc_config* cfg, int32_t* n_trig, int32_t* capacity, int32_t* buckets) {
+sc_status sc_config_sizes(const sc_config* cfg, int32_t* n_trig, int32_t* capacity, int32_t* buckets,
+                          int32_t* ring_words) {
     Sizes s;
     const sc_status st = derive(cfg, &s);
     if (st != SC_OK) return st;
     if (n_trig) *n_trig = s.n_trig;
     if (capacity) *capacity = s.C;
     if (buckets) *buckets = s.E;
+    if (ring_words) *ring_words = s.W32;
     return SC_OK;
 }
 
@@ -145,6 +160,11 @@ sc_status sc_schedule(const sc_config* cfg, int64_t t, int64_t* epoch, int32_t* 
     if (t < 1) return SC_ERR_INVALID_ARG;
     const int64_t ep = epoch_of(t, s.n_trig, cfg->drop);
     if (epoch) *epoch = ep;
+    if (s.W32) {
+        if (bucket) *bucket = (int32_t)((t % cfg->history) >> 5);
+        if (counted) *counted = 1;
+        return SC_OK;
+    }
     if (bucket) *bucket = bucket_of(ep, s.E);
     if (counted) *counted = ep > -(int64_t)s.E;
     return SC_OK;
@@ -169,6 +189,7 @@ sc_status sc_cache_create(const sc_config* cfg, void* dev_workspace, size_t byte
     L.kv_dtype = cfg->kv_dtype;
     L.C = s.C;
     L.E = s.E;
+    L.W32 = s.W32;
     L.K = base + s.off_K;
     L.V = base + s.off_V;
     L.K_meta = s.meta_bytes ? base + s.off_Km : nullptr;
@@ -263,7 +284,7 @@ sc_status sc_cache_view(const sc_cache* c, const void** K, const void** V, const
     if (pos) *pos = c->L.pos;
     if (cnt) *cnt = c->L.cnt;
     if (capacity) *capacity = c->L.C;
-    if (buckets) *buckets = c->L.E;
+    if (buckets) *buckets = c->L.E ? c->L.E : c->L.W32;
     return SC_OK;
 }
 

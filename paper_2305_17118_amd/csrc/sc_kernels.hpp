@@ -14,13 +14,14 @@ enum : int { KV_F32 = 0, KV_F16 = 1, KV_I4G64 = 2 };
 struct Layout {
     int U, d, kv_dtype;
     int C;          // slots per unit (multiple of 64)
-    int E;          // counter buckets per slot
+    int E;          // counter buckets per slot (bucket mode)
+    int W32;        // 32-bit ring words per slot (exact ring mode), 0 in bucket mode
     void* K;        // F32/F16: [U][C][d] elements; I4: [U][C][d/2] bytes of codes
     void* V;
     void* K_meta;   // I4 only: [U][C][d/64] x {fp16 scale, fp16 zero}
     void* V_meta;
     int32_t* pos;   // [U][C]
-    uint16_t* cnt;  // [U][E][C]
+    uint16_t* cnt;  // bucket mode: [U][E][C] uint16; ring mode: the same memory as uint32 [U][W32][C]
     int32_t* srcmap;  // [U][C] scratch written by select, read by compact
     int32_t* first;   // [U] scratch: first slot whose row moves
 };
@@ -35,8 +36,9 @@ struct StepArgs {
     float* probs;     // [U][C] or null
     int n;            // resident rows including the one appended by this step
     int pos_value;    // stream position of the appended row (t-1)
-    int bucket;       // counter bucket this step increments
+    int bucket;       // counter bucket this step increments (ring mode: ring word of this step)
     int counted;      // 0: this step falls outside every history window, do not count
+    uint32_t ring_bit;  // ring mode: mask of this step's bit inside its word
     float qk_log2;    // score scale * log2(e)
     float tau;        // low-score threshold
 };

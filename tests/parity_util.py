@@ -36,14 +36,15 @@ class ParityRun:
     """One workload on the GPU (all units) and on the oracle (the units in `sel`)."""
 
     def __init__(self, wl: Workload, sel=None, trigger=B.SC_TRIGGER_HARD_CAP,
-                 thresh=B.SC_THRESH_INV_POS, scale=0.0, steps=None, device="cuda:0", qkv=None):
+                 thresh=B.SC_THRESH_INV_POS, scale=0.0, steps=None, device="cuda:0", qkv=None,
+                 window_mode=B.SC_WINDOW_AUTO):
         self.wl = wl
         self.dev = torch.device(device)
         self.U = wl.units
         self.sel = list(range(self.U)) if sel is None else list(sel)
         self.T = wl.total if steps is None else steps
         self.cfg = B.make_config(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.budget, wl.recent,
-                                 wl.history, wl.drop, trigger, thresh, scale)
+                                 wl.history, wl.drop, trigger, thresh, scale, window_mode)
         self.cache = B.BudgetCache(self.cfg, device)
         self.oracle = Oracle(OracleConfig(1, len(self.sel), wl.head_dim, wl.kv_dtype, wl.budget,
                                           wl.recent, wl.history, wl.drop, trigger, thresh, scale))
@@ -98,6 +99,10 @@ class ParityRun:
     # -- compression on both sides, integer side bit-exact ---------------------------------
     def gpu_record(self):
         n = self.cache.n
+        if self.cache.ring_words:  # exact ring: the record is the popcount of each slot's ring
+            ring = self.cache.ring().index_select(0, self.sel_t)[:, :, :n].cpu().numpy()
+            bits = np.unpackbits(ring.view(np.uint8).reshape(*ring.shape, 4), axis=-1)
+            return bits.sum(axis=(1, 3)).astype(np.int64)
         cnt = self.cache.cnt().index_select(0, self.sel_t)[:, :, :n].to(torch.int32) & 0xFFFF
         return cnt.sum(dim=1).cpu().numpy()
 
@@ -122,7 +127,8 @@ class ParityRun:
         # (the GPU keeps the record in w/m buckets whose union equals the history window only
         # at compression steps, so records are compared there, before each compression)
         # counters of free slots must be clear so that rows appended later start from zero
-        tail = self.cache.cnt().index_select(0, self.sel_t)[:, :, n:]
+        planes = self.cache.ring() if self.cache.ring_words else self.cache.cnt()
+        tail = planes.index_select(0, self.sel_t)[:, :, n:]
         assert int(tail.abs().max().item()) == 0 if tail.numel() else True
         if not check_rows:
             return

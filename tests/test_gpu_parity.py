@@ -96,6 +96,39 @@ def test_maximum_capacity():
     assert e.value.status == B.SC_ERR_UNSUPPORTED
 
 
+@pytest.mark.parametrize("kv,d", [(KV_F16, 128), (KV_I4G64, 128), (KV_F32, 64), (KV_I4G64, 64)])
+@pytest.mark.parametrize("B_,r,w,m", [(40, 3, 7, 5), (64, 10, 40, 32), (50, 4, 33, 8), (30, 2, 70, 9)])
+def test_exact_ring_window_for_any_history_length(kv, d, B_, r, w, m):
+    """History windows that are not a multiple of the drop amount use the exact ring (one bit
+    per row and step); records must equal the oracle's sliding window bit for bit."""
+    wl = _wl("ring-w%d-m%d" % (w, m), 1, 3, d, kv, 3 * B_, B_, B_, r, w, m, 0.05)
+    run = ParityRun(wl)
+    assert run.cache.ring_words == (w + 31) // 32 and run.cache.buckets == 0
+    st = run.run()
+    assert st["compressions"] >= 6
+
+
+def test_ring_and_buckets_agree_where_both_apply():
+    """Forcing the ring on a window that buckets also cover gives the same evictions."""
+    wl = _wl("ring-forced", 1, 4, 128, KV_F16, 150, 80, 64, 8, 32, 16, 0.1)
+    a = ParityRun(wl)
+    b = ParityRun(wl, window_mode=B.SC_WINDOW_RING)
+    assert a.cache.buckets == 2 and b.cache.ring_words == 1
+    sa, sb = a.run(), b.run()
+    assert sa["compressions"] == sb["compressions"] >= 10
+    assert np.array_equal(a.oracle.positions(), b.oracle.positions())
+
+
+def test_papers_hyper_parameters():
+    """r = 10, w = 400, m = B/2 (Sec. 4.1 and the "Overhead Tradeoff" paragraph) on an
+    OPT-6.7B-shaped head count, 2x compression of a 1024-token stream."""
+    wl = _wl("paper-r10-w400-mhalf", 2, 32, 128, KV_F16, 768, 256, 512, 10, 400, 256, 0.05)
+    run = ParityRun(wl, sel=[0, 1, 31, 32, 63])
+    assert run.cache.ring_words == 13
+    st = run.run(check_rows_every=2)
+    assert st["compressions"] == 2 + 0 * wl.total and run.cache.n <= 513
+
+
 def test_budget_not_reached_is_full_attention():
     wl = _wl("no-evict", 1, 4, 128, KV_F16, 40, 30, 128, 8, 32, 16)
     run = ParityRun(wl)

@@ -37,15 +37,15 @@ def test_status_strings():
 
 @pytest.mark.parametrize("trigger,expect", [(B.SC_TRIGGER_HARD_CAP, 65), (B.SC_TRIGGER_HIGH_WATER, 80)])
 def test_sizes(trigger, expect):
-    n_trig, cap, E = B.sc_config_sizes(_cfg(trigger=trigger))
-    assert n_trig == expect and cap == 128 and E == 2
+    n_trig, cap, E, W32 = B.sc_config_sizes(_cfg(trigger=trigger))
+    assert n_trig == expect and cap == 128 and E == 2 and W32 == 0
     assert cap % 64 == 0 and cap >= n_trig
 
 
 def test_workspace_accounts_for_every_array():
     for kv, row in ((B.SC_KV_F32, 512), (B.SC_KV_F16, 256), (B.SC_KV_I4G64, 64 + 8)):
         cfg = _cfg(kv_dtype=kv)
-        _, cap, E = B.sc_config_sizes(cfg)
+        _, cap, E, _ = B.sc_config_sizes(cfg)
         U = 8
         need = U * cap * (2 * row + 4 + 2 * E + 4) + U * 4
         got = B.sc_workspace_bytes(cfg)
@@ -55,7 +55,8 @@ def test_workspace_accounts_for_every_array():
 @pytest.mark.parametrize("kw,status", [
     (dict(head_dim=96), B.SC_ERR_UNSUPPORTED),
     (dict(kv_dtype=7), B.SC_ERR_UNSUPPORTED),
-    (dict(history=40), B.SC_ERR_UNSUPPORTED),      # w not a multiple of m
+    (dict(history=9000), B.SC_ERR_UNSUPPORTED),    # window longer than the build covers
+    (dict(window_mode=5), B.SC_ERR_INVALID_ARG),
     (dict(budget=16, recent=16, drop=16, history=16), B.SC_ERR_INVALID_ARG),  # m > n_trig - r
     (dict(batch=0), B.SC_ERR_INVALID_ARG),
     (dict(recent=0), B.SC_ERR_INVALID_ARG),
@@ -95,7 +96,7 @@ def test_bucket_schedule_reproduces_the_history_window(B_, r, w, m, trigger):
     buckets must be exactly the last w steps (T_k - w, T_k] (those that exist), and the bucket
     cleared after the compression must be the one holding the oldest epoch."""
     cfg = _cfg(budget=B_, recent=r, history=w, drop=m, trigger=trigger)
-    n_trig, _, E = B.sc_config_sizes(cfg)
+    n_trig, _, E, _ = B.sc_config_sizes(cfg)
     assert E == w // m
     buckets = [set() for _ in range(E)]
     n = 0
@@ -117,6 +118,21 @@ def test_bucket_schedule_reproduces_the_history_window(B_, r, w, m, trigger):
             n -= m
             compressions += 1
     assert compressions >= 6
+
+
+@pytest.mark.parametrize("w,m,mode", [(40, 16, 0), (400, 512, 0), (33, 8, 0), (32, 16, 1), (7, 5, 0)])
+def test_ring_mode_sizes_and_schedule(w, m, mode):
+    """A window that is not a multiple of the drop amount (the paper's own w = 400 with
+    m = 0.5 B is one) selects the exact ring: ceil(w/32) words per row, every step counted,
+    step t owns bit t mod w."""
+    cfg = _cfg(budget=1024, recent=10, history=w, drop=m, window_mode=mode)
+    _, cap, E, W32 = B.sc_config_sizes(cfg)
+    assert E == 0 and W32 == (w + 31) // 32
+    bucket_cfg = _cfg(budget=1024, recent=10, history=m * 2, drop=m)
+    assert B.sc_workspace_bytes(cfg) - B.sc_workspace_bytes(bucket_cfg) == 8 * cap * (4 * W32 - 4)
+    for t in (1, 2, w - 1, w, w + 1, 5 * w + 3):
+        _, word, counted = B.sc_schedule(cfg, t)
+        assert counted and word == (t % w) // 32
 
 
 def test_kv_cache_accounting_matches_the_papers_table():
