@@ -148,14 +148,31 @@ sc_status sc_decode_step(sc_cache *c, const void *q, const void *k_new, const vo
  * SC_ERR_STATE unless the previous step reported compress_due. */
 sc_status sc_compress(sc_cache *c, int32_t *evicted_out, void *stream);
 
+/* How sc_prefill computes.  The result is the same function of the inputs either way; the
+ * floating-point rounding differs (summation order, fp16 probabilities in P.V). */
+typedef enum {
+    SC_PREFILL_AUTO = 0,     /* dense causal blocks on the matrix cores where supported (fp16
+                                storage, bucket counters, runs of >= 16 positions), else streamed */
+    SC_PREFILL_STREAMED = 1  /* one decode step per position: bit-identical to calling
+                                sc_decode_step / sc_compress in a loop                            */
+} sc_prefill_mode;
+
 /* Stream a prompt through Alg. 1 (Def. 4.1 treats prompt and generated tokens as one
  * stream): for each of the prompt_len positions in order, one decode step, then a
- * compression whenever one is due.  The cache must be empty.
- *   q, k, v : device, [U][>= prompt_len][head_dim]; consecutive units are `unit_stride`
- *             elements apart (0 = prompt_len*head_dim)
- *   out     : device dense [U][prompt_len][head_dim], or NULL to discard the outputs */
+ * compression whenever one is due.  The cache must be empty.  Between two compressions the
+ * cache only grows, so the positions in between form one dense causal attention block
+ * (Sec. 4.1 estimator per position, Alg. 2 record update per position); SC_PREFILL_AUTO
+ * computes them that way.
+ *   q, k, v   : device, [U][>= prompt_len][head_dim]; consecutive units are `unit_stride`
+ *               elements apart (0 = prompt_len*head_dim)
+ *   out       : device dense [U][prompt_len][head_dim], or NULL to discard the outputs
+ *   probs_out : device fp32 [U][prompt_len][capacity] or NULL; row i receives, for the slots
+ *               resident at position i (numbering at that step), exactly the probabilities
+ *               the threshold test was applied to; other elements are untouched (a slot just
+ *               past the resident ones may be written as 0)
+ *   mode      : sc_prefill_mode */
 sc_status sc_prefill(sc_cache *c, const void *q, const void *k, const void *v, int32_t prompt_len,
-                     int64_t unit_stride, void *out, void *stream);
+                     int64_t unit_stride, void *out, float *probs_out, int32_t mode, void *stream);
 
 /* Resident rows n and tokens seen t (either pointer may be NULL). */
 sc_status sc_cache_len(const sc_cache *c, int32_t *n, int64_t *t);

@@ -18,6 +18,7 @@ SC_KV_F32, SC_KV_F16, SC_KV_I4G64 = 0, 1, 2
 SC_TRIGGER_HARD_CAP, SC_TRIGGER_HIGH_WATER = 0, 1
 SC_THRESH_INV_POS, SC_THRESH_INV_LEN = 0, 1
 SC_WINDOW_AUTO, SC_WINDOW_RING = 0, 1
+SC_PREFILL_AUTO, SC_PREFILL_STREAMED = 0, 1
 
 EXPORTS = (
     "sc_config_sizes", "sc_workspace_bytes", "sc_schedule", "sc_cache_create", "sc_cache_destroy",
@@ -61,7 +62,7 @@ def lib():
     l.sc_cache_destroy.restype = None
     l.sc_decode_step.argtypes = [vp, vp, vp, vp, C.c_int64, vp, vp, i32p, vp]
     l.sc_compress.argtypes = [vp, vp, vp]
-    l.sc_prefill.argtypes = [vp, vp, vp, vp, C.c_int32, C.c_int64, vp, vp]
+    l.sc_prefill.argtypes = [vp, vp, vp, vp, C.c_int32, C.c_int64, vp, vp, C.c_int32, vp]
     l.sc_cache_len.argtypes = [vp, i32p, i64p]
     l.sc_cache_view.argtypes = [vp] + [C.POINTER(vp)] * 6 + [i32p, i32p]
     l.sc_status_str.argtypes = [C.c_int]
@@ -133,9 +134,10 @@ def sc_compress(handle, evicted_ptr=None, stream=0) -> None:
     _check(lib().sc_compress(handle, evicted_ptr, stream), "sc_compress")
 
 
-def sc_prefill(handle, q_ptr, k_ptr, v_ptr, prompt_len, unit_stride, out_ptr=None, stream=0) -> None:
+def sc_prefill(handle, q_ptr, k_ptr, v_ptr, prompt_len, unit_stride, out_ptr=None, probs_ptr=None,
+               mode=SC_PREFILL_AUTO, stream=0) -> None:
     _check(lib().sc_prefill(handle, q_ptr, k_ptr, v_ptr, int(prompt_len), int(unit_stride), out_ptr,
-                            stream), "sc_prefill")
+                            probs_ptr, int(mode), stream), "sc_prefill")
 
 
 def sc_cache_len(handle):
@@ -207,9 +209,11 @@ class BudgetCache:
     def compress(self, evicted_out=None) -> None:
         sc_compress(self.handle, None if evicted_out is None else evicted_out.data_ptr(), self._stream())
 
-    def prefill(self, q, k, v, prompt_len, unit_stride=0, out=None) -> None:
+    def prefill(self, q, k, v, prompt_len, unit_stride=0, out=None, probs_out=None,
+                mode=SC_PREFILL_AUTO) -> None:
         sc_prefill(self.handle, q.data_ptr(), k.data_ptr(), v.data_ptr(), prompt_len, unit_stride,
-                   None if out is None else out.data_ptr(), self._stream())
+                   None if out is None else out.data_ptr(),
+                   None if probs_out is None else probs_out.data_ptr(), mode, self._stream())
 
     def _typed(self, key, dtype, shape):
         """A torch view (no copy) of one of the cache's arrays inside the workspace."""

@@ -52,6 +52,7 @@ struct AttnArgs {
     void* out;
     long out_stride;
     float* probs;
+    long probs_stride;  // floats between units in probs
     uint16_t* cnt;  // bucket mode: current bucket of unit 0; ring mode: this step's word plane
     long cnt_unit_stride;  // in 16-bit units
     uint32_t ring_bit;     // ring mode: this step's bit inside its word; 0 selects bucket mode
@@ -151,7 +152,7 @@ __device__ __forceinline__ void finish_unit(const AttnArgs& a, int u, const floa
     uint32_t* cw = reinterpret_cast<uint32_t*>(a.cnt + (size_t)u * a.cnt_unit_stride);
     const int n = a.n;
     if (a.ring_bit) {
-        float* probs = a.probs ? a.probs + (size_t)u * a.C : nullptr;
+        float* probs = a.probs ? a.probs + (size_t)u * a.probs_stride : nullptr;
         auto do_slot = [&](int j, uint32_t word) {
             const float p = fast_exp2(s_lds[j] - M) * invL;
             if (probs) probs[j] = p;
@@ -166,7 +167,7 @@ __device__ __forceinline__ void finish_unit(const AttnArgs& a, int u, const floa
         for (int j = tid + CNT_PF * NT; j < n; j += NT) do_slot(j, cw[j]);
         return;
     }
-    float2* probs = a.probs ? reinterpret_cast<float2*>(a.probs + (size_t)u * a.C) : nullptr;
+    float2* probs = a.probs ? reinterpret_cast<float2*>(a.probs + (size_t)u * a.probs_stride) : nullptr;
     auto do_word = [&](int i, uint32_t word) {
         const int j = 2 * i;  // j < n here; slot j+1 may be the first free one
         const float p0 = fast_exp2(s_lds[j] - M) * invL;
@@ -982,6 +983,7 @@ hipError_t launch_decode_step(const Layout& L, const StepArgs& s, hipStream_t st
     a.out = s.out;
     a.out_stride = s.out_stride;
     a.probs = s.probs;
+    a.probs_stride = s.probs_stride;
     if (L.W32) {  // ring mode: word plane `bucket` of the uint32 [U][W32][C] ring
         a.cnt = reinterpret_cast<uint16_t*>(reinterpret_cast<uint32_t*>(L.cnt) + (size_t)s.bucket * L.C);
         a.cnt_unit_stride = 2L * L.W32 * L.C;

@@ -4,6 +4,7 @@
 // through sc_kernels.hpp; nothing here reads device memory or synchronises.
 #include "../../include/sc.h"
 
+#include <algorithm>
 #include <cmath>
 #include <new>
 
@@ -83,7 +84,8 @@ int32_t bucket_of(int64_t epoch, int32_t E) { return (int32_t)(((epoch % E) + E)
 size_t elem_bytes(const sc_config& c) { return c.kv_dtype == SC_KV_F32 ? 4 : 2; }
 
 sc_status step_impl(sc_cache* c, const void* q, const void* k_new, const void* v_new, int64_t in_stride,
-                    void* out, int64_t out_stride, float* probs_out, hipStream_t stream) {
+                    void* out, int64_t out_stride, float* probs_out, int64_t probs_stride,
+                    hipStream_t stream) {
     const int64_t t1 = c->t + 1;
     const int32_t n1 = c->n + 1;
     sc::StepArgs a;
@@ -94,6 +96,7 @@ sc_status step_impl(sc_cache* c, const void* q, const void* k_new, const void* v
     a.out = out;
     a.out_stride = (long)out_stride;
     a.probs = probs_out;
+    a.probs_stride = (long)probs_stride;
     a.n = n1;
     a.pos_value = (int)(t1 - 1);
     if (c->L.W32) {
@@ -225,7 +228,7 @@ sc_status sc_decode_step(sc_cache* c, const void* q, const void* k_new, const vo
         return SC_ERR_INVALID_ARG;
     if (c->n >= c->n_trig) return SC_ERR_FULL;
     const int64_t stride = in_stride ? in_stride : c->cfg.head_dim;
-    const sc_status st = step_impl(c, q, k_new, v_new, stride, out, c->cfg.head_dim, probs_out,
+    const sc_status st = step_impl(c, q, k_new, v_new, stride, out, c->cfg.head_dim, probs_out, c->L.C,
                                    static_cast<hipStream_t>(stream));
     if (st != SC_OK) return st;
     if (compress_due) *compress_due = (c->n == c->n_trig);
@@ -239,8 +242,9 @@ sc_status sc_compress(sc_cache* c, int32_t* evicted_out, void* stream) {
 }
 
 sc_status sc_prefill(sc_cache* c, const void* q, const void* k, const void* v, int32_t prompt_len,
-                     int64_t unit_stride, void* out, void* stream) {
+                     int64_t unit_stride, void* out, float* probs_out, int32_t mode, void* stream) {
     if (!c || !q || !k || !v || prompt_len < 1) return SC_ERR_INVALID_ARG;
+    if (mode != SC_PREFILL_AUTO && mode != SC_PREFILL_STREAMED) return SC_ERR_INVALID_ARG;
     if (c->n != 0 || c->t != 0) return SC_ERR_STATE;
     const int64_t d = c->cfg.head_dim;
     const int64_t stride = unit_stride ? unit_stride : (int64_t)prompt_len * d;
@@ -248,18 +252,58 @@ sc_status sc_prefill(sc_cache* c, const void* q, const void* k, const void* v, i
     const size_t eb = elem_bytes(c->cfg);
     if ((stride * eb) % 16 != 0) return SC_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k) | reinterpret_cast<uintptr_t>(v) |
-         reinterpret_cast<uintptr_t>(out)) % 16 != 0)
+         reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(probs_out)) % 16 != 0)
         return SC_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    for (int32_t i = 0; i < prompt_len; ++i) {
+    const int64_t m = c->cfg.drop;
+    const int64_t probs_stride = (int64_t)prompt_len * c->L.C;
+    // Dense runs pay off from a few positions on; a workgroup of the dense kernel serves 64.
+    constexpr int64_t kMinRun = 16;
+    const bool dense_ok = mode == SC_PREFILL_AUTO && sc::prefill_chunk_supported(c->L) &&
+                          (int64_t)c->L.U * ((m + 63) / 64) < (1ll << 31);
+    int64_t i = 0;
+    while (i < prompt_len) {
+        // Positions up to the next boundary of the counter schedule share one bucket, and no
+        // compression falls inside: boundaries are the steps t = n_trig + k*m.
+        const int64_t ep = epoch_of(c->t + 1, c->n_trig, m);
+        const int64_t run = std::min<int64_t>(prompt_len - i, c->n_trig + ep * m - c->t);
         const size_t off = (size_t)i * d * eb;
         void* o = out ? static_cast<char*>(out) + off : nullptr;
-        sc_status st = step_impl(c, static_cast<const char*>(q) + off, static_cast<const char*>(k) + off,
-                                 static_cast<const char*>(v) + off, stride, o, (int64_t)prompt_len * d,
-                                 nullptr, s);
-        if (st != SC_OK) return st;
+        float* pr = probs_out ? probs_out + (size_t)i * c->L.C : nullptr;
+        if (dense_ok && run >= kMinRun) {
+            sc::ChunkArgs a;
+            a.q = static_cast<const char*>(q) + off;
+            a.k = static_cast<const char*>(k) + off;
+            a.v = static_cast<const char*>(v) + off;
+            a.unit_stride = (long)stride;
+            a.out = o;
+            a.out_unit_stride = (long)((int64_t)prompt_len * d);
+            a.probs = pr;
+            a.probs_unit_stride = (long)probs_stride;
+            a.n0 = c->n;
+            a.c = (int)run;
+            a.t0 = (long)c->t;
+            a.bucket = bucket_of(ep, c->L.E);
+            a.counted = ep > -(int64_t)c->L.E;
+            a.thresh_len = c->cfg.thresh_mode == SC_THRESH_INV_LEN;
+            a.qk_log2 = c->qk_log2;
+            if (sc::launch_prefill_chunk(c->L, a, s) != hipSuccess) return SC_ERR_DEVICE;
+            c->t += run;
+            c->n += (int32_t)run;
+        } else {
+            for (int64_t j = 0; j < run; ++j) {
+                const size_t offj = off + (size_t)j * d * eb;
+                sc_status st = step_impl(c, static_cast<const char*>(q) + offj, static_cast<const char*>(k) + offj,
+                                         static_cast<const char*>(v) + offj, stride,
+                                         o ? static_cast<char*>(o) + (size_t)j * d * eb : nullptr,
+                                         (int64_t)prompt_len * d, pr ? pr + (size_t)j * c->L.C : nullptr,
+                                         probs_stride, s);
+                if (st != SC_OK) return st;
+            }
+        }
+        i += run;
         if (c->n == c->n_trig) {
-            st = compress_impl(c, nullptr, s);
+            const sc_status st = compress_impl(c, nullptr, s);
             if (st != SC_OK) return st;
         }
     }

@@ -33,7 +33,8 @@ struct StepArgs {
     long in_stride;   // elements between units in q/k_new/v_new
     void* out;        // [U][d]
     long out_stride;  // elements between units in out
-    float* probs;     // [U][C] or null
+    float* probs;     // unit 0's row of C floats, or null
+    long probs_stride;  // floats between units in probs
     int n;            // resident rows including the one appended by this step
     int pos_value;    // stream position of the appended row (t-1)
     int bucket;       // counter bucket this step increments (ring mode: ring word of this step)
@@ -54,6 +55,32 @@ struct CompressArgs {
 };
 
 hipError_t launch_compress(const Layout& L, const CompressArgs& a, hipStream_t stream);
+
+// A run of `c` consecutive prompt positions with no compression inside and a single counter
+// bucket (the host cuts the prompt accordingly), processed as one dense causal block.
+struct ChunkArgs {
+    const void* q;    // first prompt row of the run, unit 0
+    const void* k;
+    const void* v;
+    long unit_stride;      // elements between units in q, k and v
+    void* out;             // first output row of the run, unit 0, or null; rows are d apart
+    long out_unit_stride;  // elements between units in out
+    float* probs;          // row of the run's first position, unit 0, or null; rows are C apart
+    long probs_unit_stride;  // floats between units in probs
+    int n0;           // resident rows before the run
+    int c;            // positions in the run; n0 + c <= trigger size
+    long t0;          // tokens seen before the run
+    int bucket;       // counter bucket every position of the run increments
+    int counted;      // 0: the run falls outside every history window
+    int thresh_len;   // threshold 1/n (1) or 1/t (0)
+    float qk_log2;
+};
+
+// Whether launch_prefill_chunk handles this cache (fp16 rows, bucket counters).
+bool prefill_chunk_supported(const Layout& L);
+
+// Two launches on `stream`: append the run's rows, then attention + counting.
+hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& a, hipStream_t stream);
 
 // Zero all counters (cache creation).
 hipError_t launch_clear_counters(const Layout& L, hipStream_t stream);

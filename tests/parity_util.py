@@ -96,6 +96,36 @@ class ParityRun:
         st["max_dp"] = max(st["max_dp"], float(dp.max()))
         st["max_sum_err"] = max(st["max_sum_err"], float(sum_err))
 
+    # -- the prompt through sc_prefill, the oracle stepped through the same positions ----------
+    def prefill(self, P, mode=B.SC_PREFILL_AUTO):
+        """Positions 0..P-1 of the streams go through ONE sc_prefill call; the oracle takes them
+        one step at a time with the GPU's probabilities of that position forced, and every
+        position's output and probabilities are compared.  Evictions inside the call are not
+        visible one by one; the positions and stored rows after the call are, and must agree
+        bit for bit (any differing eviction changes them)."""
+        assert self.step_idx == 0
+        d, C = self.wl.head_dim, self.cache.capacity
+        out = torch.empty(self.U, P, d, dtype=self.cache.io_dtype, device=self.dev)
+        probs = torch.zeros(self.U, P, C, dtype=torch.float32, device=self.dev)
+        self.cache.prefill(self.q, self.k, self.v, P, self.T * d, out, probs, mode)
+        o_all = out.index_select(0, self.sel_t).float().cpu().numpy().astype(np.float64)
+        p_all = probs.index_select(0, self.sel_t).cpu().numpy()
+        del out, probs
+        for s in range(P):
+            n = self.oracle.n + 1
+            p_gpu = np.ascontiguousarray(p_all[:, s, :n])
+            o_ref, p_ref, due = self.oracle.step(self.hq[:, s], self.hk[:, s], self.hv[:, s],
+                                                 p_forced=p_gpu)
+            self._compare(o_all[:, s], o_ref, p_gpu, p_ref[:, :n], s)
+            self.stats["steps"] += 1
+            if due:
+                self.oracle.compress()
+                self.stats["compressions"] += 1
+        self.step_idx = P
+        assert (self.cache.n, self.cache.t) == (self.oracle.n, self.oracle.t)
+        self.check_state()
+        return self.stats
+
     # -- compression on both sides, integer side bit-exact ---------------------------------
     def gpu_record(self):
         n = self.cache.n

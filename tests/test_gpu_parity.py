@@ -144,8 +144,8 @@ def test_budget_not_reached_is_full_attention():
     assert np.all(np.linalg.norm(got - ref, axis=1) <= 2e-3 * np.linalg.norm(ref, axis=1))
 
 
-def test_prefill_equals_stepping():
-    """sc_prefill is the prompt streamed through decode steps with a compression whenever one
+def test_streamed_prefill_equals_stepping():
+    """sc_prefill (streamed mode) is the prompt streamed through decode steps with a compression whenever one
     is due: cache contents, counters, positions and outputs must be identical, bit for bit."""
     wl = _wl("prefill", 2, 3, 128, KV_F16, 200, 0, 64, 8, 32, 16, 0.05)
     q, k, v = (torch.from_numpy(a).cuda() for a in streams(wl))
@@ -155,7 +155,7 @@ def test_prefill_equals_stepping():
     T, d, U = wl.total, wl.head_dim, wl.units
     out_a = torch.empty(U, T, d, dtype=torch.float16, device="cuda")
     out_b = torch.zeros(U, T, d, dtype=torch.float16, device="cuda")
-    a.prefill(q, k, v, T, 0, out_a)
+    a.prefill(q, k, v, T, 0, out_a, mode=B.SC_PREFILL_STREAMED)
     step_out = torch.empty(U, d, dtype=torch.float16, device="cuda")
     for s in range(T):
         due = b.decode_step(q[:, s], k[:, s], v[:, s], step_out, in_stride=T * d)
@@ -174,8 +174,58 @@ def test_prefill_equals_stepping():
     c = B.BudgetCache(cfg)
     pad = torch.zeros(U, 8, d, dtype=torch.float16, device="cuda")
     qq, kk, vv = (torch.cat([x, pad], dim=1).contiguous() for x in (q, k, v))
-    c.prefill(qq, kk, vv, T, (T + 8) * d, None)
+    c.prefill(qq, kk, vv, T, (T + 8) * d, None, mode=B.SC_PREFILL_STREAMED)
     assert torch.equal(a.pos()[:, :n], c.pos()[:, :n]) and torch.equal(a.cnt(), c.cnt())
+
+
+DENSE_PREFILL = [
+    # name, batch, heads, d, kv, prompt, decode, B, r, w, m, heavy
+    _wl("pf-d128", 1, 4, 128, KV_F16, 400, 70, 150, 8, 96, 48, 0.05),       # runs of 48 and a first run of 151
+    _wl("pf-d64", 2, 2, 64, KV_F16, 333, 50, 100, 6, 64, 32, 0.05),
+    _wl("pf-short-prompt", 1, 3, 128, KV_F16, 37, 200, 90, 5, 60, 30),      # prompt ends before the first boundary
+    _wl("pf-long-runs", 1, 2, 128, KV_F16, 700, 150, 300, 16, 400, 200, 0.03),  # runs of 200 = 4 query blocks
+    _wl("pf-tiny-drop", 1, 2, 64, KV_F16, 150, 40, 60, 4, 16, 4),           # runs of 4: streamed inside AUTO
+    _wl("pf-mixed", 1, 3, 128, KV_F16, 260, 60, 77, 7, 51, 17, 0.1),        # runs of 17: one ragged query block
+]
+
+
+@pytest.mark.parametrize("wl", DENSE_PREFILL, ids=lambda w: w.name)
+@pytest.mark.parametrize("trigger", [B.SC_TRIGGER_HARD_CAP, B.SC_TRIGGER_HIGH_WATER], ids=["cap", "hw"])
+def test_dense_prefill_matches_oracle(wl, trigger):
+    """The prompt goes through one sc_prefill call (dense causal blocks on the matrix cores);
+    every position is compared with the oracle, then decoding continues so that the
+    compressions that follow check the records accumulated during the prompt bit for bit."""
+    run = ParityRun(wl, trigger=trigger)
+    run.prefill(wl.prompt)
+    st = run.run()
+    assert st["steps"] == wl.total and st["compressions"] >= 2
+
+
+def test_dense_prefill_inverse_length_threshold():
+    wl = _wl("pf-inv-len", 1, 3, 128, KV_F16, 300, 80, 120, 8, 64, 32, 0.05)
+    run = ParityRun(wl, thresh=B.SC_THRESH_INV_LEN, scale=0.2)
+    run.prefill(wl.prompt)
+    run.run()
+
+
+def test_dense_and_streamed_prefill_agree():
+    """Both modes compute the same function; with well separated scores they evict the same
+    rows, and their outputs differ by rounding only."""
+    wl = _wl("pf-modes", 1, 4, 128, KV_F16, 300, 0, 100, 8, 64, 32, 0.05)
+    q, k, v = (torch.from_numpy(a).cuda() for a in streams(wl))
+    cfg = B.make_config(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.budget, wl.recent, wl.history,
+                        wl.drop)
+    a, b = B.BudgetCache(cfg), B.BudgetCache(cfg)
+    T, d, U = wl.total, wl.head_dim, wl.units
+    out_a = torch.empty(U, T, d, dtype=torch.float16, device="cuda")
+    out_b = torch.empty(U, T, d, dtype=torch.float16, device="cuda")
+    a.prefill(q, k, v, T, 0, out_a, mode=B.SC_PREFILL_AUTO)
+    b.prefill(q, k, v, T, 0, out_b, mode=B.SC_PREFILL_STREAMED)
+    assert (a.n, a.t) == (b.n, b.t) and not torch.equal(out_a, out_b)  # two different computations
+    same = (a.pos()[:, :a.n] == b.pos()[:, :b.n]).float().mean().item()
+    assert same > 0.9  # a probability within rounding of its threshold may flip one eviction
+    err = (out_a.float() - out_b.float()).norm(dim=-1) / out_b.float().norm(dim=-1)
+    assert err.median().item() < 2e-3
 
 
 def test_error_codes_leave_state_untouched():

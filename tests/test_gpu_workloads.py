@@ -45,3 +45,18 @@ def test_headline_workload_high_water_policy():
     run = ParityRun(wl, sel=_sample(wl, 8), trigger=B.SC_TRIGGER_HIGH_WATER)
     st = run.run(check_rows_every=2)
     assert st["compressions"] == 2 and run.cache.n == wl.budget + (wl.total - wl.budget - wl.drop) % wl.drop
+
+
+@pytest.mark.parametrize("idx,extra,decode", [(1, 8, 160), (2, 8, 140)], ids=["cfg2", "cfg3"])
+def test_dense_prefill_at_full_size(idx, extra, decode):
+    """The prompt of a full-size fp16 workload through one sc_prefill call (dense causal blocks
+    on the matrix cores), every position compared on the sampled units; the decode steps that
+    follow carry the records accumulated during the prompt into two compressions that must
+    match bit for bit."""
+    wl = CONFIGS[idx].scaled(decode=decode)
+    sel = _sample(wl, extra)
+    run = ParityRun(wl, sel=sel)
+    run.prefill(wl.prompt)
+    st = run.run(check_rows_every=2)
+    print(st, flush=True)
+    assert st["steps"] == wl.total
