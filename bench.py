@@ -24,6 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 matrix peak
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
 # HBM bytes per decode-attention launch measured with rocprofv3 counters (FETCH_SIZE x 2.000 +
@@ -83,6 +84,76 @@ def cpu_baseline(wl, sample_units: int, sample_steps: int) -> dict:
     }
 
 
+def prefill_flops(wl) -> float:
+    """Algorithmic flops of one prompt pass: position i attends over the n_i rows resident at
+    that step (its own included), 2*d multiply-adds for the score and 2*d for P.V per row.
+    The recomputation of the scores in the counting pass is not counted."""
+    n_trig = wl.budget + 1
+    n, total = 0, 0
+    for _ in range(wl.prompt):
+        n += 1
+        total += n
+        if n == n_trig:
+            n -= wl.drop
+    return 4.0 * wl.head_dim * total * wl.units
+
+
+def bench_prefill(args, wl, dev) -> int:
+    """One step = one sc_prefill call over the whole prompt of the workload (dense causal runs
+    on the matrix cores, a compression whenever one is due), on a cache reset to empty."""
+    import torch
+
+    from paper_2305_17118_amd import binding as B
+    from paper_2305_17118_amd.workloads import KV_F16, streams
+
+    if wl.kv_dtype != KV_F16:
+        print("bench.py: the dense prompt phase exists for fp16 storage only", file=sys.stderr)
+        return 2
+    cfg = B.make_config(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.budget, wl.recent, wl.history,
+                        wl.drop)
+    P, d, U = wl.prompt, wl.head_dim, wl.units
+    K, W = min(args.steps, 50), min(args.warmup, 3)
+    q, k, v = (torch.from_numpy(a).to(dev) for a in streams(wl, steps=P, threads=16))
+    out = torch.empty(U, P, d, dtype=torch.float16, device=dev)
+    cache = B.BudgetCache(cfg, dev)
+
+    def one_pass():
+        cache.reset()
+        cache.prefill(q, k, v, P, 0, out)
+
+    for _ in range(W):
+        one_pass()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(K):
+        one_pass()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    dev_ms = e0.elapsed_time(e1) / K
+    flops = prefill_flops(wl)
+    achieved = flops / (dev_ms * 1e-3) / 1e12
+    res = {
+        "metric": "prompt tokens/s into a budgeted KV cache", "value": wl.batch * P * K / wall,
+        "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": wall / K * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "phase": "prefill", "batch": wl.batch, "heads": wl.heads,
+                   "head_dim": d, "prompt": P, "budget": wl.budget, "recent": wl.recent,
+                   "history": wl.history, "drop": wl.drop, "trigger": "hard_cap"},
+        # every launch of the call (append, attention, select, compact) is inside the timed
+        # span, so this is a lower bound on the attention kernel's own rate
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "prefill_chunk_kernel (whole sc_prefill call timed)",
+                     "call_ms_avg": dev_ms, "algorithmic_flops_per_call": flops},
+    }
+    print(json.dumps(res))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -91,6 +162,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = headline)")
     ap.add_argument("--rotate", type=int, default=0, help="cache instances stepped round-robin "
                     "(0 = enough to cover three times the 256 MB last-level cache)")
+    ap.add_argument("--phase", choices=("decode", "prefill"), default="decode",
+                    help="decode = the headline metric; prefill = the prompt phase (fp16 workloads)")
     ap.add_argument("--no-events", action="store_true", help="skip the per-launch HIP events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=512)
@@ -110,6 +183,8 @@ def main() -> int:
     wl = CONFIGS[args.config - 1]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.phase == "prefill":
+        return bench_prefill(args, wl, dev)
     cfg = B.make_config(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.budget, wl.recent, wl.history,
                         wl.drop)
     ws_bytes = B.sc_workspace_bytes(cfg)

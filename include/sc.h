@@ -121,6 +121,11 @@ sc_status sc_schedule(const sc_config *cfg, int64_t t, int64_t *epoch, int32_t *
 sc_status sc_cache_create(const sc_config *cfg, void *dev_workspace, size_t bytes, void *stream,
                           sc_cache **out);
 
+/* Back to the empty state (n = 0, t = 0) for a new batch of sequences in the same workspace:
+ * the Alg. 1 loop starts over.  Enqueues a clear of the counters on `stream`; K, V and
+ * positions need none (only slots below n are ever read). */
+sc_status sc_cache_reset(sc_cache *c, void *stream);
+
 /* Free the host metadata.  The workspace is the caller's. */
 void sc_cache_destroy(sc_cache *c);
 

@@ -21,7 +21,8 @@ SC_WINDOW_AUTO, SC_WINDOW_RING = 0, 1
 SC_PREFILL_AUTO, SC_PREFILL_STREAMED = 0, 1
 
 EXPORTS = (
-    "sc_config_sizes", "sc_workspace_bytes", "sc_schedule", "sc_cache_create", "sc_cache_destroy",
+    "sc_config_sizes", "sc_workspace_bytes", "sc_schedule", "sc_cache_create", "sc_cache_reset",
+    "sc_cache_destroy",
     "sc_decode_step", "sc_compress", "sc_prefill", "sc_cache_len", "sc_cache_view", "sc_status_str",
 )
 
@@ -58,6 +59,7 @@ def lib():
     l.sc_workspace_bytes.restype = C.c_size_t
     l.sc_schedule.argtypes = [cfgp, C.c_int64, i64p, i32p, i32p]
     l.sc_cache_create.argtypes = [cfgp, vp, C.c_size_t, vp, C.POINTER(vp)]
+    l.sc_cache_reset.argtypes = [vp, vp]
     l.sc_cache_destroy.argtypes = [vp]
     l.sc_cache_destroy.restype = None
     l.sc_decode_step.argtypes = [vp, vp, vp, vp, C.c_int64, vp, vp, i32p, vp]
@@ -116,6 +118,10 @@ def sc_cache_create(cfg: sc_config, workspace_ptr: int, nbytes: int, stream: int
     _check(lib().sc_cache_create(C.byref(cfg), workspace_ptr, nbytes, stream, C.byref(h)),
            "sc_cache_create")
     return h
+
+
+def sc_cache_reset(handle, stream=0) -> None:
+    _check(lib().sc_cache_reset(handle, stream), "sc_cache_reset")
 
 
 def sc_cache_destroy(handle) -> None:
@@ -185,6 +191,9 @@ class BudgetCache:
 
     def _stream(self) -> int:
         return int(self._torch.cuda.current_stream(self.device).cuda_stream)
+
+    def reset(self) -> None:
+        sc_cache_reset(self.handle, self._stream())
 
     def close(self):
         if getattr(self, "handle", None):

@@ -16,12 +16,16 @@
 // counts to the 16-bit counters (two per 32-bit atomic).
 #include "sc_kernels.hpp"
 
+#include <type_traits>
+
 namespace sc {
 namespace {
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -67,8 +71,12 @@ struct PrefillArgs {
 // out^T = V^T P^T, whose contraction index (lane group g, element e) stands for cache row
 // 4g + e of one 16-row block (e < 4) or of the next one (e >= 4).  V is staged transposed in
 // LDS so that its A operand is two 8-byte reads.
+// At least two waves per SIMD: the register budget that goes with it (256) also makes the
+// compiler keep the matrix accumulators in ordinary vector registers, where the running-softmax
+// rescale can reach them without copies.
 template <int D>
-__global__ void __launch_bounds__(256) prefill_chunk_kernel(PrefillArgs a) {
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+prefill_chunk_kernel(PrefillArgs a) {
     constexpr int KB = 64;        // cache rows per tile
     constexpr int QB = 64;        // queries per workgroup (16 per wave)
     constexpr int LDK = D + 8;    // halfs per staged K row (padding keeps 16-byte reads conflict-free)
@@ -78,6 +86,7 @@ __global__ void __launch_bounds__(256) prefill_chunk_kernel(PrefillArgs a) {
     constexpr int PIECES = KB * D / 8 / 256;  // 16-byte pieces of a tile per thread
     __shared__ __align__(16) _Float16 Ks[KB * LDK];
     __shared__ __align__(16) _Float16 Vt[D * LDV];
+    __shared__ float stat_m[QB], stat_inv[QB];  // per query: final maximum, 1/sum (pass 1 -> pass 2)
     extern __shared__ int cnt_lds[];  // [tiles * 64] low-score counts of this workgroup's queries
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -90,7 +99,8 @@ __global__ void __launch_bounds__(256) prefill_chunk_kernel(PrefillArgs a) {
     const int q_last = (q0 + QB < a.c ? q0 + QB : a.c) - 1;
     const int hi = a.n0 + q_last + 1;                // rows visible to this workgroup
     const int ntiles = (hi + KB - 1) / KB;
-    const int wave_lim = a.n0 + (q0 + 16 * w + 15 < a.c ? q0 + 16 * w + 15 : a.c - 1);
+    const int wave_lim = a.n0 + (q0 + 16 * w + 15 < a.c ? q0 + 16 * w + 15 : a.c - 1);  // last row any query of the wave sees
+    const int wave_first_lim = a.n0 + (q0 + 16 * w < a.c ? q0 + 16 * w : a.c - 1);      // last row ALL of them see
 
     const _Float16* Kb = a.K + (size_t)u * a.C * D;
     const _Float16* Vb = a.V + (size_t)u * a.C * D;
@@ -102,150 +112,222 @@ __global__ void __launch_bounds__(256) prefill_chunk_kernel(PrefillArgs a) {
         for (int ks = 0; ks < KS; ++ks) qB[ks] = *reinterpret_cast<const half8_t*>(qrow + 32 * ks);
     }
 
-    auto load_tile = [&](int kt, bool with_v) {
+    // A tile travels global -> registers -> LDS; the loads of tile kt+1 are issued before
+    // tile kt is computed on.  K pieces: 16 bytes of one row per thread and piece.  V pieces come
+    // in pairs (the same 8 channels of rows 2*rp and 2*rp+1) so that the transposed tile is
+    // written one 32-bit word (two rows of a channel) at a time.  The row index of the
+    // transposed tile is XORed with 8*(channel/32): with that the 64 lanes of a store hit 64
+    // different banks, and groups of four rows stay contiguous for the operand reads.
+    u32x4_t kreg[PIECES];
+    half8_t vreg[PIECES];
+    constexpr int RPP = 256 / (D / 8);  // tile rows covered by one K piece index step
+    const int prow_k = tid / (D / 8), pcb8 = tid % (D / 8);
+    const uint32_t koff = (uint32_t)(prow_k * D + pcb8 * 8) * 2u;       // bytes inside a tile
+    const uint32_t voff = (uint32_t)(2 * prow_k * D + pcb8 * 8) * 2u;
+    auto fetch = [&](int kt, bool with_v) {
+        const char* kt_base = reinterpret_cast<const char*>(Kb) + (size_t)kt * KB * D * 2;
+        const char* vt_base = reinterpret_cast<const char*>(Vb) + (size_t)kt * KB * D * 2;
+        if (kt * KB + KB <= hi) {  // whole tile holds data
 #pragma unroll
-        for (int x = 0; x < PIECES; ++x) {
-            const int idx = tid + 256 * x;
-            const int row = idx / (D / 8), cb8 = idx % (D / 8);
-            int grow = kt * KB + row;
-            grow = grow < hi ? grow : hi - 1;  // stay inside rows that hold data
-            const size_t off = (size_t)grow * D + cb8 * 8;
-            *reinterpret_cast<uint4*>(&Ks[row * LDK + cb8 * 8]) = *reinterpret_cast<const uint4*>(Kb + off);
+            for (int x = 0; x < PIECES; ++x)
+                kreg[x] = *reinterpret_cast<const u32x4_t*>(kt_base + koff + (uint32_t)(x * RPP * D * 2));
             if (with_v) {
-                const half8_t vv = *reinterpret_cast<const half8_t*>(Vb + off);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) Vt[(cb8 * 8 + e) * LDV + row] = vv[e];
+                for (int x = 0; x < PIECES / 2; ++x)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+                        vreg[2 * x + h] = *reinterpret_cast<const half8_t*>(
+                            vt_base + voff + (uint32_t)((2 * x * RPP + h) * D * 2));
+            }
+        } else {  // last tile: rows past the data are read from the last row that holds some
+            const int last = hi - 1 - kt * KB;
+#pragma unroll
+            for (int x = 0; x < PIECES; ++x) {
+                const int row = prow_k + x * RPP;
+                kreg[x] = *reinterpret_cast<const u32x4_t*>(
+                    kt_base + (uint32_t)(((row < last ? row : last) * D + pcb8 * 8) * 2));
+            }
+            if (with_v) {
+#pragma unroll
+                for (int x = 0; x < PIECES / 2; ++x)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const int row = 2 * (prow_k + x * RPP) + h;
+                        vreg[2 * x + h] = *reinterpret_cast<const half8_t*>(
+                            vt_base + (uint32_t)(((row < last ? row : last) * D + pcb8 * 8) * 2));
+                    }
             }
         }
     };
-    // d[rb][r] = <k_j, q> for cache row j = 64*kt + 16*rb + 4*g + r and this lane's query
-    auto scores = [&](float4_t (&d)[4]) {
+    auto stage = [&](bool with_v) {
+#pragma unroll
+        for (int x = 0; x < PIECES; ++x)
+            *reinterpret_cast<u32x4_t*>(&Ks[(prow_k + x * RPP) * LDK + pcb8 * 8]) = kreg[x];
+        if (with_v) {
+#pragma unroll
+            for (int x = 0; x < PIECES / 2; ++x) {
+                const int col = (2 * (prow_k + x * RPP)) ^ (8 * (pcb8 >> 2));
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const half2_t two = {vreg[2 * x][e], vreg[2 * x + 1][e]};
+                    *reinterpret_cast<half2_t*>(&Vt[(pcb8 * 8 + e) * LDV + col]) = two;
+                }
+            }
+        }
+    };
+    // Raw dot products of a 64-row tile with the wave's 16 queries.
+    // TRANSPOSED: d[rb][r] = <k_j, q_i> for cache row j = 64*kt + 16*rb + 4*g + r and query i = li
+    //             (a lane holds one query: what the running softmax and P.V want);
+    // otherwise:  d[rb][r] = <k_j, q_i> for cache row j = 64*kt + 16*rb + li and query i = 4*g + r
+    //             (a lane holds one cache row: what the per-row counts want).
+    auto scores = [&](auto transposed, float4_t (&d)[4]) {
+        constexpr bool TRANSPOSED = decltype(transposed)::value;
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) d[rb] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int rb = 0; rb < 4; ++rb) {
-                const half8_t A = *reinterpret_cast<const half8_t*>(&Ks[(16 * rb + li) * LDK + 32 * ks + 8 * g]);
-                d[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, qB[ks], d[rb], 0, 0, 0);
+                const half8_t kf = *reinterpret_cast<const half8_t*>(&Ks[(16 * rb + li) * LDK + 32 * ks + 8 * g]);
+                if constexpr (TRANSPOSED)
+                    d[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qB[ks], d[rb], 0, 0, 0);
+                else
+                    d[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qB[ks], kf, d[rb], 0, 0, 0);
             }
     };
+    using Transposed = std::integral_constant<bool, true>;
+    using Plain = std::integral_constant<bool, false>;
 
     // ---- pass 1: running softmax and P.V --------------------------------------------------
-    float m = -INFINITY, l32 = 0.f, l16 = 0.f;
+    // m is kept in the scaled (log2) domain; the scale is positive, so the maximum can be
+    // taken over the raw dot products and scaled once.
+    const float c2 = a.qk_log2;
+    float m = -INFINITY, lsum = 0.f;
     float4_t acc[CB];
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) acc[cb] = float4_t{0.f, 0.f, 0.f, 0.f};
+    fetch(0, true);
     for (int kt = 0; kt < ntiles; ++kt) {
         __syncthreads();
-        load_tile(kt, true);
+        stage(true);
         __syncthreads();
+        if (kt + 1 < ntiles) fetch(kt + 1, true);
         if (kt * KB > wave_lim) continue;  // nothing in this tile is visible to this wave
         float4_t d[4];
-        scores(d);
-        float tmax = -INFINITY;
+        scores(Transposed{}, d);
+        if (kt * KB + KB - 1 > wave_first_lim) {  // the causal boundary crosses this tile
+            const int rel = lim - (kt * KB + 4 * g);  // rows 16*rb + r <= rel are visible
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb)
+            for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int j = kt * KB + 16 * rb + 4 * g + r;
-                const float s = j <= lim ? d[rb][r] * a.qk_log2 : -INFINITY;
-                d[rb][r] = s;
-                tmax = fmaxf(tmax, s);
-            }
+                for (int r = 0; r < 4; ++r) d[rb][r] = (16 * rb + r <= rel) ? d[rb][r] : -INFINITY;
+        }
+        float tmax = fmaxf(fmaxf(d[0][0], d[0][1]), fmaxf(d[0][2], d[0][3]));
+#pragma unroll
+        for (int rb = 1; rb < 4; ++rb)
+            tmax = fmaxf(tmax, fmaxf(fmaxf(d[rb][0], d[rb][1]), fmaxf(d[rb][2], d[rb][3])));
         tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float m_new = fmaxf(m, tmax);  // finite: row 0 of tile 0 is visible to every query
-        const float alpha = fast_exp2(m - m_new);
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0ull) {
-            l32 *= alpha;
-            l16 *= alpha;
+        const float m_new = fmaxf(m, tmax * c2);  // finite: row 0 of tile 0 is visible to every query
+        if (__builtin_amdgcn_ballot_w64(m_new != m) != 0ull) {
+            const float alpha = fast_exp2(m - m_new);
+            lsum *= alpha;
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) acc[cb] *= alpha;
+            m = m_new;
         }
-        m = m_new;
         half4_t ph[4];
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb)
+        for (int rb = 0; rb < 4; ++rb) {
+            float4_t p;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float p = fast_exp2(d[rb][r] - m);
-                const _Float16 p16 = (_Float16)p;
-                l32 += p;
-                l16 += (float)p16;
-                ph[rb][r] = p16;
+                p[r] = fast_exp2(fmaf(d[rb][r], c2, -m));
+                lsum += p[r];
             }
+            ph[rb] = __builtin_convertvector(p, half4_t);
+        }
 #pragma unroll
         for (int kp = 0; kp < 2; ++kp) {
-            const half8_t B = __builtin_shufflevector(ph[2 * kp], ph[2 * kp + 1], 0, 1, 2, 3, 4, 5, 6, 7);
+            // The swizzle of the transposed tile decides which of the two 4-row groups of a
+            // lane sits at the lower LDS address; the probabilities are ordered to match, so
+            // that the operand is one two-address read with no register shuffling.
+            const half8_t B01 = __builtin_shufflevector(ph[2 * kp], ph[2 * kp + 1], 0, 1, 2, 3, 4, 5, 6, 7);
+            const half8_t B10 = __builtin_shufflevector(ph[2 * kp + 1], ph[2 * kp], 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) {
-                const _Float16* vrow = &Vt[(16 * cb + li) * LDV + 32 * kp + 4 * g];
+                const int swz = 8 * (cb >> 1);  // channel/32 == cb/2
+                const _Float16* vrow = &Vt[(16 * cb + li) * LDV + (((32 * kp + 4 * g) ^ swz) & ~16)];
                 const half4_t a0 = *reinterpret_cast<const half4_t*>(vrow);
                 const half4_t a1 = *reinterpret_cast<const half4_t*>(vrow + 16);
                 const half8_t A = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
-                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, B, acc[cb], 0, 0, 0);
+                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, (swz & 16) ? B10 : B01, acc[cb], 0, 0, 0);
             }
         }
     }
-    l32 += __shfl_xor(l32, 16);
-    l32 += __shfl_xor(l32, 32);
-    l16 += __shfl_xor(l16, 16);
-    l16 += __shfl_xor(l16, 32);
+    const bool pass2 = a.counted || a.probs;
+    if (pass2) fetch(0, false);  // in flight while the outputs are written
+    lsum += __shfl_xor(lsum, 16);
+    lsum += __shfl_xor(lsum, 32);
+    const float invL = 1.0f / lsum;
     if (a.out && qi < a.c) {
-        const float inv = 1.0f / l16;
         _Float16* orow = a.out + (size_t)u * a.out_unit_stride + (size_t)qi * D + 4 * g;
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-            half4_t o;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) o[r] = (_Float16)(acc[cb][r] * inv);
-            *reinterpret_cast<half4_t*>(orow + 16 * cb) = o;
-        }
+        for (int cb = 0; cb < CB; ++cb)
+            *reinterpret_cast<half4_t*>(orow + 16 * cb) = __builtin_convertvector(acc[cb] * invL, half4_t);
     }
-    if (!a.counted && !a.probs) return;
+    if (!pass2) return;
 
     // ---- pass 2: the probabilities themselves, thresholds, counts ---------------------------
+    // Scores are recomputed untransposed, so a lane holds ONE cache row and four queries
+    // (4*g + r of its wave): the per-row count is a sum inside the lane plus one LDS atomic.
+    // Each query's maximum and 1/sum come from the lane that owned it in pass 1, through LDS.
+    if (g == 0) {
+        stat_m[16 * w + li] = m;
+        stat_inv[16 * w + li] = invL;
+    }
     for (int i = tid; i < ntiles * KB; i += 256) cnt_lds[i] = 0;
-    const float invL = 1.0f / l32;
-    const long tq = a.thresh_len ? (long)a.n0 + qi + 1 : a.t0 + qi + 1;
-    const float tau = __fdiv_rn(1.0f, (float)tq);
-    const bool real = qi < a.c;
-    float* prow = a.probs ? a.probs + (size_t)u * a.probs_unit_stride + (size_t)qc * a.C : nullptr;
-    const int rb_l = lane >> 4, g_l = (lane >> 2) & 3, r_l = lane & 3;  // the tile row this lane counts for
+    __syncthreads();
+    float qm[4], qinv[4], qtau[4];
+    const int qbase = q0 + 16 * w + 4 * g;  // this lane's first query
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        qm[r] = stat_m[16 * w + 4 * g + r];
+        qinv[r] = stat_inv[16 * w + 4 * g + r];
+        const long tq = a.thresh_len ? (long)a.n0 + qbase + r + 1 : a.t0 + qbase + r + 1;
+        // a padding query (past the end of the run) never counts: no probability is below -1
+        qtau[r] = qbase + r < a.c ? __fdiv_rn(1.0f, (float)tq) : -1.0f;
+    }
+    float* pbase = a.probs ? a.probs + (size_t)u * a.probs_unit_stride + (size_t)qbase * a.C : nullptr;
     for (int kt = 0; kt < ntiles; ++kt) {
         __syncthreads();
-        load_tile(kt, false);
+        stage(false);
         __syncthreads();
+        if (kt + 1 < ntiles) fetch(kt + 1, false);
         if (kt * KB > wave_lim) continue;
         float4_t d[4];
-        scores(d);
-        uint32_t mine = 0;
+        scores(Plain{}, d);
+        const bool diag = kt * KB + KB - 1 > wave_first_lim;
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) {
-            const int j0 = kt * KB + 16 * rb + 4 * g;
+            const int j = kt * KB + 16 * rb + li;
+            const int rel = j - a.n0 - qbase;  // query r of this lane sees row j iff rel <= r
             float4_t p;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) p[r] = fast_exp2(d[rb][r] * a.qk_log2 - m) * invL;
-            if (prow && real) {
-                if (j0 + 3 <= lim) {
-                    *reinterpret_cast<float4_t*>(prow + j0) = p;
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (j0 + r <= lim) prow[j0 + r] = p[r];
-                }
-            }
+            int cnt = 0;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const bool low = real && (j0 + r <= lim) && (p[r] < tau);
-                const unsigned long long bal = __builtin_amdgcn_ballot_w64(low);
-                const uint32_t half = (g_l & 2) ? (uint32_t)(bal >> 32) : (uint32_t)bal;
-                const uint32_t cnt = __popc((half >> ((g_l & 1) * 16)) & 0xFFFFu);
-                mine = (rb == rb_l && r == r_l) ? cnt : mine;
+                p[r] = fast_exp2(fmaf(d[rb][r], c2, -qm[r])) * qinv[r];
+                bool low = p[r] < qtau[r];
+                if (diag) low = low && rel <= r;
+                cnt += low ? 1 : 0;
+            }
+            if (cnt) atomicAdd(&cnt_lds[j], cnt);
+            if (pbase) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (qbase + r < a.c && rel <= r) pbase[(size_t)r * a.C + j] = p[r];
             }
         }
-        if (mine) atomicAdd(&cnt_lds[kt * KB + lane], (int)mine);
     }
     __syncthreads();
     if (!a.counted) return;

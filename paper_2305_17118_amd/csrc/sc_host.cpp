@@ -214,6 +214,14 @@ sc_status sc_cache_create(const sc_config* cfg, void* dev_workspace, size_t byte
     return SC_OK;
 }
 
+sc_status sc_cache_reset(sc_cache* c, void* stream) {
+    if (!c) return SC_ERR_INVALID_ARG;
+    if (sc::launch_clear_counters(c->L, static_cast<hipStream_t>(stream)) != hipSuccess) return SC_ERR_DEVICE;
+    c->n = 0;
+    c->t = 0;
+    return SC_OK;
+}
+
 void sc_cache_destroy(sc_cache* c) { delete c; }
 
 sc_status sc_decode_step(sc_cache* c, const void* q, const void* k_new, const void* v_new,
