@@ -104,10 +104,10 @@ def bench_prefill(args, wl, dev) -> int:
     import torch
 
     from paper_2305_17118_amd import binding as B
-    from paper_2305_17118_amd.workloads import KV_F16, streams
+    from paper_2305_17118_amd.workloads import KV_F16, KV_F32, streams
 
-    if wl.kv_dtype != KV_F16:
-        print("bench.py: the dense prompt phase exists for fp16 storage only", file=sys.stderr)
+    if wl.kv_dtype == KV_F32:
+        print("bench.py: the dense prompt phase exists for fp16 and 4-bit storage only", file=sys.stderr)
         return 2
     cfg = B.make_config(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.budget, wl.recent, wl.history,
                         wl.drop)
@@ -138,8 +138,8 @@ def bench_prefill(args, wl, dev) -> int:
     res = {
         "metric": "prompt tokens/s into a budgeted KV cache", "value": wl.batch * P * K / wall,
         "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": wall / K * 1e3,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
-        "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16" if wl.kv_dtype == KV_F16 else "i4+f16", "data": "synthetic",
         "config": {"workload": wl.name, "phase": "prefill", "batch": wl.batch, "heads": wl.heads,
                    "head_dim": d, "prompt": P, "budget": wl.budget, "recent": wl.recent,
                    "history": wl.history, "drop": wl.drop, "trigger": "hard_cap"},
@@ -147,7 +147,8 @@ def bench_prefill(args, wl, dev) -> int:
         # span, so this is a lower bound on the attention kernel's own rate
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None,
-                     "kernel": "prefill_chunk_kernel (whole sc_prefill call timed)",
+                     "kernel": ("prefill_chunk_kernel" if wl.kv_dtype == KV_F16 else "prefill_chunk_i4_kernel")
+                     + " (whole sc_prefill call timed)",
                      "call_ms_avg": dev_ms, "algorithmic_flops_per_call": flops},
     }
     print(json.dumps(res))
@@ -164,6 +165,9 @@ def main() -> int:
                     "(0 = enough to cover three times the 256 MB last-level cache)")
     ap.add_argument("--phase", choices=("decode", "prefill"), default="decode",
                     help="decode = the headline metric; prefill = the prompt phase (fp16 workloads)")
+    ap.add_argument("--window", choices=("auto", "ring"), default="auto",
+                    help="importance record: bucket counters (auto, when w is a multiple of m) or "
+                         "the exact one-bit-per-step ring")
     ap.add_argument("--no-events", action="store_true", help="skip the per-launch HIP events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=512)
@@ -186,7 +190,7 @@ def main() -> int:
     if args.phase == "prefill":
         return bench_prefill(args, wl, dev)
     cfg = B.make_config(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.budget, wl.recent, wl.history,
-                        wl.drop)
+                        wl.drop, window_mode=B.SC_WINDOW_RING if args.window == "ring" else B.SC_WINDOW_AUTO)
     ws_bytes = B.sc_workspace_bytes(cfg)
     R = args.rotate or min(8, max(1, -(-3 * 256 * 2 ** 20 // ws_bytes)))
     T, d, U = wl.total, wl.head_dim, wl.units
@@ -275,7 +279,7 @@ def main() -> int:
         "config": {
             "workload": wl.name, "batch": wl.batch, "heads": wl.heads, "head_dim": wl.head_dim,
             "prompt": wl.prompt, "decode": wl.decode, "budget": wl.budget, "recent": wl.recent,
-            "history": wl.history, "drop": wl.drop, "trigger": "hard_cap",
+            "history": wl.history, "drop": wl.drop, "trigger": "hard_cap", "window": args.window,
             "cache_instances_round_robin": R, "compressions_in_timed_region": compress_events,
             "resident_rows_avg": sum(n_log) / len(n_log),
         },

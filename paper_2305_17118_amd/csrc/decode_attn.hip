@@ -12,6 +12,7 @@
 // when the maximum moves; raw scores are parked in LDS so that, once the unit's global max
 // and sum are known, the epilogue can form every probability, test it against the
 // threshold, bump the counters and (optionally) dump the probabilities.
+#include "quant.hpp"
 #include "sc_kernels.hpp"
 
 #include <type_traits>
@@ -313,53 +314,6 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
 //   <q, k>   = sum_groups scale_g * sum_c q_c*code_c + zero_g * sum_c q_c
 //   sum_j p_j v_j[c] = sum_j (p_j*scale_jg) * code_jc + sum_j p_j*zero_jg
 // ---------------------------------------------------------------------------------------
-union MetaWord {
-    uint32_t u32;
-    _Float16 h[2];  // scale, zero
-};
-
-// Quantise one row of D fp16 channels held two per lane (lane i holds x0 = channel 2i and
-// x1 = channel 2i+1; lanes >= D/2 idle) and store codes and meta to `codes` / `meta` (global)
-// and to their LDS copies.
-// Every operation is a single IEEE fp32 operation so the codes are reproducible anywhere:
-// zero = min, scale = fp16((max-min)/15) (1 when that is 0),
-// code = clamp(rint((x-zero)/scale), 0, 15).
-template <int D>
-__device__ __forceinline__ void quantise_row(float x0, float x1, unsigned char* codes, uint32_t* meta,
-                                             unsigned char* lds_codes, uint32_t* lds_meta, int lane) {
-    if (lane < D / 2) {
-        float mn = fminf(x0, x1), mx = fmaxf(x0, x1);
-#pragma unroll
-        for (int off = 1; off < 32; off <<= 1) {
-            mn = fminf(mn, __shfl_xor(mn, off));
-            mx = fmaxf(mx, __shfl_xor(mx, off));
-        }
-        const float range = __fsub_rn(mx, mn);
-        _Float16 sh = (_Float16)__fdiv_rn(range, 15.0f);
-        float s = (float)sh;
-        if (s == 0.0f) {
-            s = 1.0f;
-            sh = (_Float16)1.0f;
-        }
-        const _Float16 zh = (_Float16)mn;
-        const float z = (float)zh;
-        float c0 = rintf(__fdiv_rn(__fsub_rn(x0, z), s));
-        float c1 = rintf(__fdiv_rn(__fsub_rn(x1, z), s));
-        c0 = fminf(fmaxf(c0, 0.f), 15.f);
-        c1 = fminf(fmaxf(c1, 0.f), 15.f);
-        const unsigned char byte = (unsigned char)((uint32_t)c0 | ((uint32_t)c1 << 4));
-        codes[lane] = byte;
-        lds_codes[lane] = byte;
-        if ((lane & 31) == 0) {
-            MetaWord mw;
-            mw.h[0] = sh;
-            mw.h[1] = zh;
-            meta[lane >> 5] = mw.u32;
-            lds_meta[lane >> 5] = mw.u32;
-        }
-    }
-}
-
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
 // Two 4-bit codes of a 32-bit word, bits [lo, lo+4) of each 16-bit half, as a pair of fp16

@@ -14,6 +14,7 @@
 // pass 2 recomputes the scores against the final maximum and sum to form the very
 // probabilities the threshold is applied to, counts the low ones per cache row and adds the
 // counts to the 16-bit counters (two per 32-bit atomic).
+#include "quant.hpp"
 #include "sc_kernels.hpp"
 
 #include <type_traits>
@@ -49,8 +50,10 @@ append_rows_kernel(const char* __restrict__ k, const char* __restrict__ v, long 
 struct PrefillArgs {
     const _Float16* q;
     long unit_stride;
-    const _Float16* K;
-    const _Float16* V;
+    const void* K;  // fp16 rows, or 4-bit codes
+    const void* V;
+    const uint32_t* K_meta;  // 4-bit only: {fp16 scale, fp16 zero} per row and 64 channels
+    const uint32_t* V_meta;
     _Float16* out;
     long out_unit_stride;
     float* probs;
@@ -102,8 +105,8 @@ prefill_chunk_kernel(PrefillArgs a) {
     const int wave_lim = a.n0 + (q0 + 16 * w + 15 < a.c ? q0 + 16 * w + 15 : a.c - 1);  // last row any query of the wave sees
     const int wave_first_lim = a.n0 + (q0 + 16 * w < a.c ? q0 + 16 * w : a.c - 1);      // last row ALL of them see
 
-    const _Float16* Kb = a.K + (size_t)u * a.C * D;
-    const _Float16* Vb = a.V + (size_t)u * a.C * D;
+    const _Float16* Kb = static_cast<const _Float16*>(a.K) + (size_t)u * a.C * D;
+    const _Float16* Vb = static_cast<const _Float16*>(a.V) + (size_t)u * a.C * D;
 
     half8_t qB[KS];
     {
@@ -338,25 +341,371 @@ prefill_chunk_kernel(PrefillArgs a) {
     }
 }
 
+
+// ---------------------------------------------------------------------------------------
+// 4-bit storage (head size 128).  The run's rows are quantised into their slots first (one
+// wave per row, the same single-operation fp32 arithmetic as the decode kernel, so the
+// codes are identical to what stepping would have stored).  The attention kernel has the
+// structure of prefill_chunk_kernel; what differs is how a tile is staged and how a score
+// is finished:
+//  * keys stay codes: the staged K tile holds the codes as fp16 integers (exact), the matrix
+//    instructions accumulate sum_c q_c*code_c per group of 64 channels, and the score is
+//    scale_0*S_0 + scale_1*S_1 + zero_0*sum(q over group 0) + zero_1*sum(q over group 1)
+//    in fp32, i.e. <q, code*scale + zero> without ever rounding a dequantised key;
+//  * values are dequantised while they are transposed into LDS: fp16(code*scale + zero).
+// Unpacking a word of eight codes with two masks gives the channel pairs (0,4) (1,5) (2,6)
+// (3,7); the staged K tile keeps that order inside every 8 channels and the query operand is
+// permuted once to match.
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+append_rows_i4_kernel(const _Float16* __restrict__ k, const _Float16* __restrict__ v, long unit_stride,
+                      unsigned char* __restrict__ K, unsigned char* __restrict__ V,
+                      uint32_t* __restrict__ Km, uint32_t* __restrict__ Vm, int32_t* __restrict__ pos,
+                      int C, int n0, int c, int t0) {
+    constexpr int D = 128;
+    const int u = blockIdx.x, lane = threadIdx.x & 63;
+    const int row = blockIdx.y * 4 + (threadIdx.x >> 6);
+    if (row >= c) return;
+    const size_t src = (size_t)u * unit_stride + (size_t)row * D + 2 * lane;
+    const size_t slot = (size_t)u * C + n0 + row;
+    const half2_t kk = *reinterpret_cast<const half2_t*>(k + src);
+    const half2_t vv = *reinterpret_cast<const half2_t*>(v + src);
+    quantise_row<D>((float)kk[0], (float)kk[1], K + slot * (D / 2), Km + slot * (D / 64), nullptr, nullptr, lane);
+    quantise_row<D>((float)vv[0], (float)vv[1], V + slot * (D / 2), Vm + slot * (D / 64), nullptr, nullptr, lane);
+    if (lane == 0) pos[slot] = t0 + row;
+}
+
+// The eight codes of word w as fp16 integers, in the order (n0,n4) (n1,n5) (n2,n6) (n3,n7).
+__device__ __forceinline__ void codes_to_half(uint32_t w, half2_t (&h)[4]) {
+    const uint32_t t = w >> 8;
+    const half2_t k1024 = {(_Float16)1024.f, (_Float16)1024.f};
+    const half2_t k64 = {(_Float16)64.f, (_Float16)64.f};
+    const half2_t sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
+    // (w & mask) | 0x6400 per half is the fp16 number 1024 + code (low nibble) or 1024 + 16*code
+    h[0] = __builtin_bit_cast(half2_t, (w & 0x000F000Fu) | 0x64006400u) - k1024;
+    h[1] = __builtin_bit_cast(half2_t, (w & 0x00F000F0u) | 0x64006400u) * sixteenth - k64;
+    h[2] = __builtin_bit_cast(half2_t, (t & 0x000F000Fu) | 0x64006400u) - k1024;
+    h[3] = __builtin_bit_cast(half2_t, (t & 0x00F000F0u) | 0x64006400u) * sixteenth - k64;
+}
+
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+prefill_chunk_i4_kernel(PrefillArgs a) {
+    constexpr int D = 128, KB = 64, QB = 64;
+    constexpr int LDK = D + 8, LDV = KB + 4, CB = D / 16;
+    constexpr uint32_t ROWB = D / 2;  // bytes of codes per row
+    __shared__ __align__(16) _Float16 Ks[KB * LDK];
+    __shared__ __align__(16) _Float16 Vt[D * LDV];
+    __shared__ __align__(16) uint32_t Kmeta[KB * 2];
+    __shared__ float stat_m[QB], stat_inv[QB], stat_q0[QB], stat_q1[QB];
+    extern __shared__ int cnt_lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int li = lane & 15, g = lane >> 4;
+    const int u = blockIdx.x / a.nqb;
+    const int q0 = (a.nqb - 1 - (int)(blockIdx.x % a.nqb)) * QB;
+    const int qi = q0 + 16 * w + li;
+    const int qc = qi < a.c ? qi : a.c - 1;
+    const int lim = a.n0 + qc;
+    const int q_last = (q0 + QB < a.c ? q0 + QB : a.c) - 1;
+    const int hi = a.n0 + q_last + 1;
+    const int ntiles = (hi + KB - 1) / KB;
+    const int wave_lim = a.n0 + (q0 + 16 * w + 15 < a.c ? q0 + 16 * w + 15 : a.c - 1);
+    const int wave_first_lim = a.n0 + (q0 + 16 * w < a.c ? q0 + 16 * w : a.c - 1);
+
+    const unsigned char* Kb = static_cast<const unsigned char*>(a.K) + (size_t)u * a.C * ROWB;
+    const unsigned char* Vb = static_cast<const unsigned char*>(a.V) + (size_t)u * a.C * ROWB;
+    const uint32_t* Kmb = a.K_meta + (size_t)u * a.C * 2;
+    const uint32_t* Vmb = a.V_meta + (size_t)u * a.C * 2;
+
+    // Query operand: channels 32*ks + 8*g + {0,4,1,5,2,6,3,7}; sums of q over the two groups.
+    half8_t qB[4];
+    float qsum0, qsum1;
+    {
+        const _Float16* qrow = a.q + (size_t)u * a.unit_stride + (size_t)qc * D + 8 * g;
+        float part[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const half8_t x = *reinterpret_cast<const half8_t*>(qrow + 32 * ks);
+            qB[ks] = __builtin_shufflevector(x, x, 0, 4, 1, 5, 2, 6, 3, 7);
+            float acc = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc += (float)x[e];
+            part[ks] = acc;
+        }
+        float s0 = part[0] + part[1], s1 = part[2] + part[3];
+        s0 += __shfl_xor(s0, 16);
+        s0 += __shfl_xor(s0, 32);
+        s1 += __shfl_xor(s1, 16);
+        s1 += __shfl_xor(s1, 32);
+        qsum0 = s0;
+        qsum1 = s1;
+    }
+
+    // Tile staging: thread = (row tid/4, 32 channels starting at 32*(tid%4)).
+    const int srow = tid >> 2, sp = tid & 3;
+    u32x4_t kreg, vreg;
+    uint32_t kmreg, vmreg;
+    auto fetch = [&](int kt, bool with_v) {
+        int grow = kt * KB + srow;
+        grow = grow < hi ? grow : hi - 1;  // stay inside rows that hold data
+        kreg = *reinterpret_cast<const u32x4_t*>(Kb + (size_t)grow * ROWB + sp * 16);
+        kmreg = Kmb[(size_t)grow * 2 + (sp >> 1)];
+        if (with_v) {
+            vreg = *reinterpret_cast<const u32x4_t*>(Vb + (size_t)grow * ROWB + sp * 16);
+            vmreg = Vmb[(size_t)grow * 2 + (sp >> 1)];
+        }
+    };
+    auto stage = [&](bool with_v) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            half2_t h[4];
+            codes_to_half(kreg[i], h);
+            const half4_t lo = __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3);
+            const half4_t hi4 = __builtin_shufflevector(h[2], h[3], 0, 1, 2, 3);
+            *reinterpret_cast<half8_t*>(&Ks[srow * LDK + 32 * sp + 8 * i]) =
+                __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+        if ((sp & 1) == 0) Kmeta[srow * 2 + (sp >> 1)] = kmreg;
+        if (with_v) {
+            MetaWord mw;
+            mw.u32 = vmreg;
+            const float sc = (float)mw.h[0], zr = (float)mw.h[1];
+            // x[c] = value of channel 32*sp + c of this thread's row, c = 0..31, as fp16
+            _Float16 x[32];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    x[8 * i + e] = (_Float16)fmaf((float)((vreg[i] >> (4 * e)) & 15u), sc, zr);
+            // Rows 2k and 2k+1 sit four lanes apart.  The even-row thread ends up with channels
+            // 0..15 of both rows, the odd-row thread with channels 16..31, so that each writes
+            // 32-bit words {row 2k, row 2k+1} of the transposed tile.
+            const bool odd = srow & 1;
+            const int col = (srow & ~1) ^ (8 * sp);  // swizzle: channel/32 == sp
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const half2_t lower = {x[2 * j], x[2 * j + 1]}, upper = {x[16 + 2 * j], x[17 + 2 * j]};
+                const uint32_t send = __builtin_bit_cast(uint32_t, odd ? lower : upper);
+                const half2_t got = __builtin_bit_cast(half2_t, (uint32_t)__shfl_xor((int)send, 4));
+                const half2_t mine = odd ? upper : lower;
+                const half2_t r0 = odd ? got : mine, r1 = odd ? mine : got;  // rows 2k, 2k+1
+                const int ch = 32 * sp + (odd ? 16 : 0) + 2 * j;
+                const half2_t w0 = {r0[0], r1[0]}, w1 = {r0[1], r1[1]};
+                *reinterpret_cast<half2_t*>(&Vt[ch * LDV + col]) = w0;
+                *reinterpret_cast<half2_t*>(&Vt[(ch + 1) * LDV + col]) = w1;
+            }
+        }
+    };
+    // Per group: sum_c q_c*code_c for a 64-row tile against the wave's 16 queries (see
+    // prefill_chunk_kernel for the two orientations).
+    auto code_dots = [&](auto transposed, float4_t (&d0)[4], float4_t (&d1)[4]) {
+        constexpr bool TRANSPOSED = decltype(transposed)::value;
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) d0[rb] = d1[rb] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) {
+                const half8_t kf = *reinterpret_cast<const half8_t*>(&Ks[(16 * rb + li) * LDK + 32 * ks + 8 * g]);
+                float4_t& d = ks < 2 ? d0[rb] : d1[rb];
+                if constexpr (TRANSPOSED)
+                    d = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qB[ks], d, 0, 0, 0);
+                else
+                    d = __builtin_amdgcn_mfma_f32_16x16x32_f16(qB[ks], kf, d, 0, 0, 0);
+            }
+    };
+    // <q, k> from the two code sums and the row's meta words.
+    auto finish_score = [](float s0, float s1, uint32_t m0, uint32_t m1, float q0s, float q1s) {
+        MetaWord a0, a1;
+        a0.u32 = m0;
+        a1.u32 = m1;
+        float s = (float)a0.h[1] * q0s;
+        s = fmaf((float)a1.h[1], q1s, s);
+        s = fmaf((float)a0.h[0], s0, s);
+        return fmaf((float)a1.h[0], s1, s);
+    };
+    using Transposed = std::integral_constant<bool, true>;
+    using Plain = std::integral_constant<bool, false>;
+
+    // ---- pass 1 ----------------------------------------------------------------------------
+    const float c2 = a.qk_log2;
+    float m = -INFINITY, lsum = 0.f;
+    float4_t acc[CB];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) acc[cb] = float4_t{0.f, 0.f, 0.f, 0.f};
+    fetch(0, true);
+    for (int kt = 0; kt < ntiles; ++kt) {
+        __syncthreads();
+        stage(true);
+        __syncthreads();
+        if (kt + 1 < ntiles) fetch(kt + 1, true);
+        if (kt * KB > wave_lim) continue;
+        float4_t d[4], d1[4];
+        code_dots(Transposed{}, d, d1);
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+            // meta words of rows 16*rb + 4*g + r, r = 0..3: eight consecutive words
+            const u32x4_t ma = *reinterpret_cast<const u32x4_t*>(&Kmeta[(16 * rb + 4 * g) * 2]);
+            const u32x4_t mb = *reinterpret_cast<const u32x4_t*>(&Kmeta[(16 * rb + 4 * g) * 2 + 4]);
+            d[rb][0] = finish_score(d[rb][0], d1[rb][0], ma[0], ma[1], qsum0, qsum1);
+            d[rb][1] = finish_score(d[rb][1], d1[rb][1], ma[2], ma[3], qsum0, qsum1);
+            d[rb][2] = finish_score(d[rb][2], d1[rb][2], mb[0], mb[1], qsum0, qsum1);
+            d[rb][3] = finish_score(d[rb][3], d1[rb][3], mb[2], mb[3], qsum0, qsum1);
+        }
+        if (kt * KB + KB - 1 > wave_first_lim) {
+            const int rel = lim - (kt * KB + 4 * g);
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) d[rb][r] = (16 * rb + r <= rel) ? d[rb][r] : -INFINITY;
+        }
+        float tmax = fmaxf(fmaxf(d[0][0], d[0][1]), fmaxf(d[0][2], d[0][3]));
+#pragma unroll
+        for (int rb = 1; rb < 4; ++rb)
+            tmax = fmaxf(tmax, fmaxf(fmaxf(d[rb][0], d[rb][1]), fmaxf(d[rb][2], d[rb][3])));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float m_new = fmaxf(m, tmax * c2);
+        if (__builtin_amdgcn_ballot_w64(m_new != m) != 0ull) {
+            const float alpha = fast_exp2(m - m_new);
+            lsum *= alpha;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) acc[cb] *= alpha;
+            m = m_new;
+        }
+        half4_t ph[4];
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+            float4_t p;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                p[r] = fast_exp2(fmaf(d[rb][r], c2, -m));
+                lsum += p[r];
+            }
+            ph[rb] = __builtin_convertvector(p, half4_t);
+        }
+#pragma unroll
+        for (int kp = 0; kp < 2; ++kp) {
+            const half8_t B01 = __builtin_shufflevector(ph[2 * kp], ph[2 * kp + 1], 0, 1, 2, 3, 4, 5, 6, 7);
+            const half8_t B10 = __builtin_shufflevector(ph[2 * kp + 1], ph[2 * kp], 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                const int swz = 8 * (cb >> 1);
+                const _Float16* vrow = &Vt[(16 * cb + li) * LDV + (((32 * kp + 4 * g) ^ swz) & ~16)];
+                const half4_t a0 = *reinterpret_cast<const half4_t*>(vrow);
+                const half4_t a1 = *reinterpret_cast<const half4_t*>(vrow + 16);
+                const half8_t A = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, (swz & 16) ? B10 : B01, acc[cb], 0, 0, 0);
+            }
+        }
+    }
+    const bool pass2 = a.counted || a.probs;
+    if (pass2) fetch(0, false);
+    lsum += __shfl_xor(lsum, 16);
+    lsum += __shfl_xor(lsum, 32);
+    const float invL = 1.0f / lsum;
+    if (a.out && qi < a.c) {
+        _Float16* orow = a.out + (size_t)u * a.out_unit_stride + (size_t)qi * D + 4 * g;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+            *reinterpret_cast<half4_t*>(orow + 16 * cb) = __builtin_convertvector(acc[cb] * invL, half4_t);
+    }
+    if (!pass2) return;
+
+    // ---- pass 2 ----------------------------------------------------------------------------
+    if (g == 0) {
+        stat_m[16 * w + li] = m;
+        stat_inv[16 * w + li] = invL;
+        stat_q0[16 * w + li] = qsum0;
+        stat_q1[16 * w + li] = qsum1;
+    }
+    for (int i = tid; i < ntiles * KB; i += 256) cnt_lds[i] = 0;
+    __syncthreads();
+    float qm[4], qinv[4], qtau[4], qs0[4], qs1[4];
+    const int qbase = q0 + 16 * w + 4 * g;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        qm[r] = stat_m[16 * w + 4 * g + r];
+        qinv[r] = stat_inv[16 * w + 4 * g + r];
+        qs0[r] = stat_q0[16 * w + 4 * g + r];
+        qs1[r] = stat_q1[16 * w + 4 * g + r];
+        const long tq = a.thresh_len ? (long)a.n0 + qbase + r + 1 : a.t0 + qbase + r + 1;
+        qtau[r] = qbase + r < a.c ? __fdiv_rn(1.0f, (float)tq) : -1.0f;
+    }
+    float* pbase = a.probs ? a.probs + (size_t)u * a.probs_unit_stride + (size_t)qbase * a.C : nullptr;
+    for (int kt = 0; kt < ntiles; ++kt) {
+        __syncthreads();
+        stage(false);
+        __syncthreads();
+        if (kt + 1 < ntiles) fetch(kt + 1, false);
+        if (kt * KB > wave_lim) continue;
+        float4_t d[4], d1[4];
+        code_dots(Plain{}, d, d1);
+        const bool diag = kt * KB + KB - 1 > wave_first_lim;
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+            const int j = kt * KB + 16 * rb + li;
+            const int rel = j - a.n0 - qbase;
+            const uint2 mw = *reinterpret_cast<const uint2*>(&Kmeta[(16 * rb + li) * 2]);
+            float4_t p;
+            int cnt = 0;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float s = finish_score(d[rb][r], d1[rb][r], mw.x, mw.y, qs0[r], qs1[r]);
+                p[r] = fast_exp2(fmaf(s, c2, -qm[r])) * qinv[r];
+                bool low = p[r] < qtau[r];
+                if (diag) low = low && rel <= r;
+                cnt += low ? 1 : 0;
+            }
+            if (cnt) atomicAdd(&cnt_lds[j], cnt);
+            if (pbase) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (qbase + r < a.c && rel <= r) pbase[(size_t)r * a.C + j] = p[r];
+            }
+        }
+    }
+    __syncthreads();
+    if (!a.counted) return;
+    uint32_t* cw = reinterpret_cast<uint32_t*>(a.cnt + (size_t)u * a.cnt_unit_stride);
+    for (int i = tid; 2 * i < hi; i += 256) {
+        const uint32_t word = (uint32_t)cnt_lds[2 * i] | ((uint32_t)cnt_lds[2 * i + 1] << 16);
+        if (word) atomicAdd(&cw[i], word);
+    }
+}
+
 }  // namespace
 
 bool prefill_chunk_supported(const Layout& L) {
-    return L.kv_dtype == KV_F16 && L.E > 0 && L.C <= 6144;
+    if (L.E == 0 || L.C > 6144) return false;
+    return L.kv_dtype == KV_F16 || (L.kv_dtype == KV_I4G64 && L.d == 128);
 }
 
 hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t stream) {
-    const int row16 = L.d * 2 / 16;
-    const dim3 grid_a(L.U, (c.c * row16 + 255) / 256);
-    append_rows_kernel<<<grid_a, 256, 0, stream>>>(
-        static_cast<const char*>(c.k), static_cast<const char*>(c.v), c.unit_stride * 2,
-        static_cast<char*>(L.K), static_cast<char*>(L.V), L.pos, L.C, row16, c.n0, c.c, (int)c.t0);
+    const bool i4 = L.kv_dtype == KV_I4G64;
+    if (i4) {
+        const dim3 grid_a(L.U, (c.c + 3) / 4);
+        append_rows_i4_kernel<<<grid_a, 256, 0, stream>>>(
+            static_cast<const _Float16*>(c.k), static_cast<const _Float16*>(c.v), c.unit_stride,
+            static_cast<unsigned char*>(L.K), static_cast<unsigned char*>(L.V),
+            static_cast<uint32_t*>(L.K_meta), static_cast<uint32_t*>(L.V_meta), L.pos, L.C, c.n0, c.c,
+            (int)c.t0);
+    } else {
+        const int row16 = L.d * 2 / 16;
+        const dim3 grid_a(L.U, (c.c * row16 + 255) / 256);
+        append_rows_kernel<<<grid_a, 256, 0, stream>>>(
+            static_cast<const char*>(c.k), static_cast<const char*>(c.v), c.unit_stride * 2,
+            static_cast<char*>(L.K), static_cast<char*>(L.V), L.pos, L.C, row16, c.n0, c.c, (int)c.t0);
+    }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     PrefillArgs a;
     a.q = static_cast<const _Float16*>(c.q);
     a.unit_stride = c.unit_stride;
-    a.K = static_cast<const _Float16*>(L.K);
-    a.V = static_cast<const _Float16*>(L.V);
+    a.K = L.K;
+    a.V = L.V;
+    a.K_meta = static_cast<const uint32_t*>(L.K_meta);
+    a.V_meta = static_cast<const uint32_t*>(L.V_meta);
     a.out = static_cast<_Float16*>(c.out);
     a.out_unit_stride = c.out_unit_stride;
     a.probs = c.probs;
@@ -373,7 +722,9 @@ hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t
     a.qk_log2 = c.qk_log2;
     const size_t lds = (size_t)L.C * sizeof(int);
     const unsigned grid = (unsigned)L.U * (unsigned)a.nqb;
-    if (L.d == 64)
+    if (i4)
+        prefill_chunk_i4_kernel<<<grid, 256, lds, stream>>>(a);
+    else if (L.d == 64)
         prefill_chunk_kernel<64><<<grid, 256, lds, stream>>>(a);
     else
         prefill_chunk_kernel<128><<<grid, 256, lds, stream>>>(a);

@@ -186,6 +186,10 @@ DENSE_PREFILL = [
     _wl("pf-long-runs", 1, 2, 128, KV_F16, 700, 150, 300, 16, 400, 200, 0.03),  # runs of 200 = 4 query blocks
     _wl("pf-tiny-drop", 1, 2, 64, KV_F16, 150, 40, 60, 4, 16, 4),           # runs of 4: streamed inside AUTO
     _wl("pf-mixed", 1, 3, 128, KV_F16, 260, 60, 77, 7, 51, 17, 0.1),        # runs of 17: one ragged query block
+    _wl("pf-i4", 1, 4, 128, KV_I4G64, 400, 70, 150, 8, 96, 48, 0.05),       # 4-bit rows quantised by the run
+    _wl("pf-i4-long-runs", 2, 2, 128, KV_I4G64, 700, 120, 300, 16, 400, 200, 0.03),
+    _wl("pf-i4-ragged", 1, 3, 128, KV_I4G64, 260, 60, 77, 7, 51, 17, 0.1),
+    _wl("pf-i4-d64-streamed", 1, 2, 64, KV_I4G64, 150, 40, 60, 4, 32, 16),  # no dense kernel: streamed inside AUTO
 ]
 
 
