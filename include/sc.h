@@ -179,6 +179,16 @@ typedef enum {
 sc_status sc_prefill(sc_cache *c, const void *q, const void *k, const void *v, int32_t prompt_len,
                      int64_t unit_stride, void *out, float *probs_out, int32_t mode, void *stream);
 
+/* The runs sc_prefill cuts a prompt into (host only, no GPU needed): consecutive positions
+ * that share one counter bucket with no compression in between.  Entry i of the output
+ * arrays (any may be NULL; at most max_runs entries are written) describes run i:
+ *   run_len      : positions in the run
+ *   run_dense    : 1 if computed as one dense causal block, 0 if streamed step by step
+ *   run_compress : 1 if a compression (Alg. 2) follows the run
+ * *n_runs receives the total number of runs, which may exceed max_runs. */
+sc_status sc_prefill_plan(const sc_config *cfg, int32_t prompt_len, int32_t mode, int32_t max_runs,
+                          int32_t *run_len, int32_t *run_dense, int32_t *run_compress, int32_t *n_runs);
+
 /* Resident rows n and tokens seen t (either pointer may be NULL). */
 sc_status sc_cache_len(const sc_cache *c, int32_t *n, int64_t *t);
 

@@ -23,7 +23,7 @@ SC_PREFILL_AUTO, SC_PREFILL_STREAMED = 0, 1
 EXPORTS = (
     "sc_config_sizes", "sc_workspace_bytes", "sc_schedule", "sc_cache_create", "sc_cache_reset",
     "sc_cache_destroy",
-    "sc_decode_step", "sc_compress", "sc_prefill", "sc_cache_len", "sc_cache_view", "sc_status_str",
+    "sc_decode_step", "sc_compress", "sc_prefill", "sc_prefill_plan", "sc_cache_len", "sc_cache_view", "sc_status_str",
 )
 
 
@@ -65,6 +65,7 @@ def lib():
     l.sc_decode_step.argtypes = [vp, vp, vp, vp, C.c_int64, vp, vp, i32p, vp]
     l.sc_compress.argtypes = [vp, vp, vp]
     l.sc_prefill.argtypes = [vp, vp, vp, vp, C.c_int32, C.c_int64, vp, vp, C.c_int32, vp]
+    l.sc_prefill_plan.argtypes = [cfgp, C.c_int32, C.c_int32, C.c_int32, i32p, i32p, i32p, i32p]
     l.sc_cache_len.argtypes = [vp, i32p, i64p]
     l.sc_cache_view.argtypes = [vp] + [C.POINTER(vp)] * 6 + [i32p, i32p]
     l.sc_status_str.argtypes = [C.c_int]
@@ -144,6 +145,17 @@ def sc_prefill(handle, q_ptr, k_ptr, v_ptr, prompt_len, unit_stride, out_ptr=Non
                mode=SC_PREFILL_AUTO, stream=0) -> None:
     _check(lib().sc_prefill(handle, q_ptr, k_ptr, v_ptr, int(prompt_len), int(unit_stride), out_ptr,
                             probs_ptr, int(mode), stream), "sc_prefill")
+
+
+def sc_prefill_plan(cfg: sc_config, prompt_len: int, mode: int = SC_PREFILL_AUTO):
+    """-> list of (run_len, dense, compress_follows)"""
+    n = C.c_int32()
+    _check(lib().sc_prefill_plan(C.byref(cfg), prompt_len, mode, 0, None, None, None, C.byref(n)),
+           "sc_prefill_plan")
+    arr = [(C.c_int32 * n.value)() for _ in range(3)]
+    _check(lib().sc_prefill_plan(C.byref(cfg), prompt_len, mode, n.value, arr[0], arr[1], arr[2],
+                                 C.byref(n)), "sc_prefill_plan")
+    return [(arr[0][i], bool(arr[1][i]), bool(arr[2][i])) for i in range(n.value)]
 
 
 def sc_cache_len(handle):

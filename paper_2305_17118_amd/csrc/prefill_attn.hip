@@ -676,11 +676,6 @@ prefill_chunk_i4_kernel(PrefillArgs a) {
 
 }  // namespace
 
-bool prefill_chunk_supported(const Layout& L) {
-    if (L.E == 0 || L.C > 6144) return false;
-    return L.kv_dtype == KV_F16 || (L.kv_dtype == KV_I4G64 && L.d == 128);
-}
-
 hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t stream) {
     const bool i4 = L.kv_dtype == KV_I4G64;
     if (i4) {

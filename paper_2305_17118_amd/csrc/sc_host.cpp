@@ -81,6 +81,27 @@ int64_t epoch_of(int64_t t, int64_t n_trig, int64_t m) {
 
 int32_t bucket_of(int64_t epoch, int32_t E) { return (int32_t)(((epoch % E) + E) % E); }
 
+// How sc_prefill cuts a prompt: positions up to the next boundary of the counter schedule
+// share one bucket and no compression falls inside a run; the boundaries are the steps
+// t = n_trig + k*m, the same steps after which a compression is due.
+constexpr int64_t kMinDenseRun = 16;  // a workgroup of the dense kernel serves 64 positions
+
+struct Run {
+    int64_t len, epoch;
+    bool dense;
+};
+
+Run next_run(const sc_config& cfg, const Sizes& z, int32_t mode, int64_t t, int64_t remaining) {
+    Run r;
+    r.epoch = epoch_of(t + 1, z.n_trig, cfg.drop);
+    r.len = std::min<int64_t>(remaining, z.n_trig + r.epoch * cfg.drop - t);
+    const int64_t units = (int64_t)cfg.batch * cfg.heads;
+    r.dense = mode == SC_PREFILL_AUTO && r.len >= kMinDenseRun &&
+              sc::prefill_chunk_supported(cfg.kv_dtype, cfg.head_dim, z.E, z.C) &&
+              units * ((r.len + 63) / 64) < (1ll << 31);
+    return r;
+}
+
 size_t elem_bytes(const sc_config& c) { return c.kv_dtype == SC_KV_F32 ? 4 : 2; }
 
 sc_status step_impl(sc_cache* c, const void* q, const void* k_new, const void* v_new, int64_t in_stride,
@@ -263,22 +284,17 @@ sc_status sc_prefill(sc_cache* c, const void* q, const void* k, const void* v, i
          reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(probs_out)) % 16 != 0)
         return SC_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int64_t m = c->cfg.drop;
     const int64_t probs_stride = (int64_t)prompt_len * c->L.C;
-    // Dense runs pay off from a few positions on; a workgroup of the dense kernel serves 64.
-    constexpr int64_t kMinRun = 16;
-    const bool dense_ok = mode == SC_PREFILL_AUTO && sc::prefill_chunk_supported(c->L) &&
-                          (int64_t)c->L.U * ((m + 63) / 64) < (1ll << 31);
+    Sizes z;
+    if (derive(&c->cfg, &z) != SC_OK) return SC_ERR_INVALID_ARG;
     int64_t i = 0;
     while (i < prompt_len) {
-        // Positions up to the next boundary of the counter schedule share one bucket, and no
-        // compression falls inside: boundaries are the steps t = n_trig + k*m.
-        const int64_t ep = epoch_of(c->t + 1, c->n_trig, m);
-        const int64_t run = std::min<int64_t>(prompt_len - i, c->n_trig + ep * m - c->t);
+        const Run r = next_run(c->cfg, z, mode, c->t, prompt_len - i);
+        const int64_t run = r.len, ep = r.epoch;
         const size_t off = (size_t)i * d * eb;
         void* o = out ? static_cast<char*>(out) + off : nullptr;
         float* pr = probs_out ? probs_out + (size_t)i * c->L.C : nullptr;
-        if (dense_ok && run >= kMinRun) {
+        if (r.dense) {
             sc::ChunkArgs a;
             a.q = static_cast<const char*>(q) + off;
             a.k = static_cast<const char*>(k) + off;
@@ -315,6 +331,33 @@ sc_status sc_prefill(sc_cache* c, const void* q, const void* k, const void* v, i
             if (st != SC_OK) return st;
         }
     }
+    return SC_OK;
+}
+
+sc_status sc_prefill_plan(const sc_config* cfg, int32_t prompt_len, int32_t mode, int32_t max_runs,
+                          int32_t* run_len, int32_t* run_dense, int32_t* run_compress, int32_t* n_runs) {
+    Sizes z;
+    const sc_status st = derive(cfg, &z);
+    if (st != SC_OK) return st;
+    if (prompt_len < 1 || max_runs < 0 || !n_runs) return SC_ERR_INVALID_ARG;
+    if (mode != SC_PREFILL_AUTO && mode != SC_PREFILL_STREAMED) return SC_ERR_INVALID_ARG;
+    int64_t t = 0, n = 0, i = 0;
+    int32_t count = 0;
+    while (i < prompt_len) {
+        const Run r = next_run(*cfg, z, mode, t, prompt_len - i);
+        t += r.len;
+        n += r.len;
+        const bool due = n == z.n_trig;
+        if (due) n -= cfg->drop;
+        if (count < max_runs) {
+            if (run_len) run_len[count] = (int32_t)r.len;
+            if (run_dense) run_dense[count] = r.dense;
+            if (run_compress) run_compress[count] = due;
+        }
+        ++count;
+        i += r.len;
+    }
+    *n_runs = count;
     return SC_OK;
 }
 

@@ -76,8 +76,12 @@ struct ChunkArgs {
     float qk_log2;
 };
 
-// Whether launch_prefill_chunk handles this cache (fp16 rows, bucket counters).
-bool prefill_chunk_supported(const Layout& L);
+// Whether launch_prefill_chunk handles such a cache: fp16 rows (either head size) or 4-bit rows
+// of 128 channels, bucket counters, and a per-slot LDS array that fits beside the tiles.
+inline bool prefill_chunk_supported(int kv_dtype, int d, int E, int C) {
+    if (E == 0 || C > 6144) return false;
+    return kv_dtype == KV_F16 || (kv_dtype == KV_I4G64 && d == 128);
+}
 
 // Two launches on `stream`: append the run's rows, then attention + counting.
 hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& a, hipStream_t stream);

@@ -153,3 +153,52 @@ def test_compression_ratio_of_the_workloads():
     from paper_2305_17118_amd.workloads import CONFIGS
     ratios = [round(2048 / c.budget) for c in CONFIGS]
     assert ratios[1:] == [2, 5, 3, 3]
+
+
+@pytest.mark.parametrize("kw,prompt", [
+    (dict(), 500),
+    (dict(budget=410, recent=64, history=256, drop=128), 2048),
+    (dict(budget=1024, recent=64, history=256, drop=128), 1024),          # never reaches the trigger
+    (dict(trigger=B.SC_TRIGGER_HIGH_WATER), 333),
+    (dict(budget=60, recent=4, history=16, drop=4), 150),                 # runs too short for a dense block
+    (dict(kv_dtype=B.SC_KV_I4G64), 200),
+    (dict(kv_dtype=B.SC_KV_F32, head_dim=64), 200),                       # no dense kernel for fp32 rows
+    (dict(history=40), 200),                                              # ring record: streamed
+])
+def test_prefill_plan_follows_the_schedule(kw, prompt):
+    """The runs sc_prefill cuts a prompt into, against a position-by-position simulation of
+    Alg. 1: runs tile the prompt, every position of a run falls into the same counter epoch, a
+    compression can only follow the last position of a run, and it follows exactly when the
+    cache has reached its trigger size."""
+    cfg = _cfg(**kw)
+    n_trig, cap, E, W32 = B.sc_config_sizes(cfg)
+    plan = B.sc_prefill_plan(cfg, prompt)
+    assert sum(r[0] for r in plan) == prompt and all(r[0] >= 1 for r in plan)
+    dense_capable = E > 0 and (cfg.kv_dtype == B.SC_KV_F16 or
+                               (cfg.kv_dtype == B.SC_KV_I4G64 and cfg.head_dim == 128))
+    t = n = 0
+    for length, dense, compress in plan:
+        epochs = {B.sc_schedule(cfg, t + 1 + i)[0] for i in range(length)}
+        assert len(epochs) == 1
+        for i in range(length):
+            t += 1
+            n += 1
+            assert n <= n_trig
+            if i < length - 1:
+                assert n < n_trig  # no compression inside a run
+        assert compress == (n == n_trig)
+        if compress:
+            n -= cfg.drop
+        assert dense == (dense_capable and length >= 16)
+    streamed = B.sc_prefill_plan(cfg, prompt, B.SC_PREFILL_STREAMED)
+    assert [r[0] for r in streamed] == [r[0] for r in plan] and not any(r[1] for r in streamed)
+
+
+def test_prefill_plan_rejects_bad_arguments():
+    cfg = _cfg()
+    with pytest.raises(B.ScError) as e:
+        B.sc_prefill_plan(cfg, 0)
+    assert e.value.status == B.SC_ERR_INVALID_ARG
+    with pytest.raises(B.ScError) as e:
+        B.sc_prefill_plan(cfg, 10, 7)
+    assert e.value.status == B.SC_ERR_INVALID_ARG
