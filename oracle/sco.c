@@ -14,6 +14,8 @@
  *             importance record of Alg. 2 kept online as Sec. 4.1 "Overhead Tradeoff"
  *             allows: a row is "low" at this step when its probability is below the
  *             threshold 1/t; the low flags of the last w steps are kept per row.
+ *             (Alg. 2 as printed instead recomputes the record at compression time with
+ *             "an extra attention computation": record mode "recompute", below.)
  *   compress  Alg. 2: importance I = number of low flags inside the history window,
  *             the r most recent rows are not candidates, the m candidates with the
  *             largest I are dropped (equal I: the lowest slot goes first), survivors
@@ -31,6 +33,14 @@
  *     Optional mode: 1/n (resident rows).
  *   - trigger: "hard cap" compresses when n == B+1 (Alg. 1 "if n > B"), leaving
  *     B+1-m rows; "high water" compresses when n == B+m, leaving exactly B rows.
+ *   - record mode "recompute" (Alg. 2 literal; Sec. 4.1 "Overhead Tradeoff" names the extra
+ *     attention computation): the queries of the last w steps are kept; at a compression
+ *     at step t, for every step i in (t-w, t] the attention of q_i is recomputed over the
+ *     rows resident NOW that step i could see (original position <= i-1), softmax over
+ *     exactly those rows, and a row is low for step i when that probability is below
+ *     1/i (or 1/(number of those rows) in the 1/n mode); I = number of low flags.  It
+ *     differs from the online record only in that evicted rows no longer take part in
+ *     the old queries' softmax.  A step none of whose rows survive contributes nothing.
  *   - 4-bit storage (Table 3 only names it): per row and per group of 64 channels,
  *     asymmetric: zero = min, scale = fp16(max-min)/15 (1 if that is 0),
  *     code = clamp(rint((x-zero)/scale), 0, 15) in fp32; the stored value is
@@ -52,6 +62,7 @@
 enum { SCO_F32 = 0, SCO_F16 = 1, SCO_I4G64 = 2 };
 enum { SCO_HARD_CAP = 0, SCO_HIGH_WATER = 1 };
 enum { SCO_INV_POS = 0, SCO_INV_LEN = 1 };
+enum { SCO_RECORD_ONLINE = 0, SCO_RECORD_RECOMPUTE = 1 };
 
 typedef struct {
     int32_t batch, heads, head_dim;
@@ -59,6 +70,7 @@ typedef struct {
     int32_t budget, recent, history, drop;
     int32_t trigger, thresh_mode;
     double scale; /* 0 -> 1/sqrt(head_dim) */
+    int32_t record_mode;
 } sco_config;
 
 typedef struct sco_cache {
@@ -70,6 +82,7 @@ typedef struct sco_cache {
     float *K, *V;   /* [U][cap][d] stored values; every storage format is exact in fp32 */
     int64_t *pos;   /* [U][cap] original position (0-based) of the row in each slot */
     uint8_t *low;   /* [U][cap][w] ring: low[.][.][s % w] = flag written at step s */
+    float *Qh;      /* [U][w][d] ring: Qh[.][s % w] = query of step s (as handed in) */
     int nthreads;
 } sco_cache;
 
@@ -182,6 +195,7 @@ sco_cache *sco_create(const sco_config *cfg, int nthreads) {
     if (cfg->budget < 1 || cfg->recent < 1 || cfg->history < 1 || cfg->drop < 1) return NULL;
     if (cfg->trigger < 0 || cfg->trigger > 1 || cfg->thresh_mode < 0 || cfg->thresh_mode > 1)
         return NULL;
+    if (cfg->record_mode < 0 || cfg->record_mode > 1) return NULL;
     int cap = trigger_rows(cfg);
     if (cfg->drop > cap - cfg->recent) return NULL; /* not enough candidates to drop m */
     sco_cache *h = (sco_cache *)calloc(1, sizeof(*h));
@@ -200,8 +214,9 @@ sco_cache *sco_create(const sco_config *cfg, int nthreads) {
     h->V = (float *)calloc(rows * (size_t)h->d, sizeof(float));
     h->pos = (int64_t *)calloc(rows, sizeof(int64_t));
     h->low = (uint8_t *)calloc(rows * (size_t)h->w, 1);
-    if (!h->K || !h->V || !h->pos || !h->low) {
-        free(h->K); free(h->V); free(h->pos); free(h->low); free(h);
+    h->Qh = (float *)calloc((size_t)h->U * (size_t)h->w * (size_t)h->d, sizeof(float));
+    if (!h->K || !h->V || !h->pos || !h->low || !h->Qh) {
+        free(h->K); free(h->V); free(h->pos); free(h->low); free(h->Qh); free(h);
         return NULL;
     }
     return h;
@@ -209,7 +224,7 @@ sco_cache *sco_create(const sco_config *cfg, int nthreads) {
 
 void sco_destroy(sco_cache *h) {
     if (!h) return;
-    free(h->K); free(h->V); free(h->pos); free(h->low); free(h);
+    free(h->K); free(h->V); free(h->pos); free(h->low); free(h->Qh); free(h);
 }
 
 int sco_len(const sco_cache *h, int32_t *n, int64_t *t, int32_t *cap) {
@@ -290,6 +305,26 @@ static void store_row(const sco_cache *h, float *dst, const void *src, size_t of
     }
 }
 
+/* Sec. 4.1 estimator, probability part: s[j] = softmax_j(scale * <q, k_j>) over the first n
+ * rows of K (the query already widened to double). */
+static void attention_probabilities(const sco_cache *h, const float *K, int n, const double *qd,
+                                    double *s) {
+    const int d = h->d;
+    double mx = -INFINITY;
+    for (int j = 0; j < n; ++j) {
+        double acc = 0.0;
+        for (int ch = 0; ch < d; ++ch) acc += qd[ch] * (double)K[(size_t)j * d + ch];
+        s[j] = h->scale * acc;
+        if (s[j] > mx) mx = s[j];
+    }
+    double denom = 0.0;
+    for (int j = 0; j < n; ++j) {
+        s[j] = exp(s[j] - mx);
+        denom += s[j];
+    }
+    for (int j = 0; j < n; ++j) s[j] /= denom;
+}
+
 static void step_unit(void *vctx, int u) {
     step_ctx *c = (step_ctx *)vctx;
     sco_cache *h = c->h;
@@ -313,19 +348,9 @@ static void step_unit(void *vctx, int u) {
     for (int ch = 0; ch < d; ++ch)
         qd[ch] = (double)load_elem(c->q, h->cfg.kv_dtype == SCO_F32 ? SCO_F32 : SCO_F16,
                                    (size_t)u * d + (size_t)ch);
-    double mx = -INFINITY;
-    for (int j = 0; j < n; ++j) {
-        double acc = 0.0;
-        for (int ch = 0; ch < d; ++ch) acc += qd[ch] * (double)K[(size_t)j * d + ch];
-        s[j] = h->scale * acc;
-        if (s[j] > mx) mx = s[j];
-    }
-    double denom = 0.0;
-    for (int j = 0; j < n; ++j) {
-        s[j] = exp(s[j] - mx);
-        denom += s[j];
-    }
-    for (int j = 0; j < n; ++j) s[j] /= denom; /* s now holds the probabilities */
+    float *qkeep = h->Qh + ((size_t)u * w + (size_t)(c->t_after % w)) * d;
+    for (int ch = 0; ch < d; ++ch) qkeep[ch] = (float)qd[ch]; /* exact: the input is fp32 or fp16 */
+    attention_probabilities(h, K, n, qd, s); /* s now holds the probabilities */
     double *o = c->out + (size_t)u * d;
     for (int ch = 0; ch < d; ++ch) o[ch] = 0.0;
     for (int j = 0; j < n; ++j)
@@ -381,8 +406,63 @@ static int importance_of(const sco_cache *h, int u, int j) {
     return acc;
 }
 
-/* I [U][n]: importance record of every resident row over the current history window. */
+/* Number of steps in the history window at the current step: min(w, t). */
+static int window_steps(const sco_cache *h) { return h->t < (int64_t)h->w ? (int)h->t : h->w; }
+
+/* Record mode "recompute" for one unit: I[0..n) from the kept queries and the rows resident
+ * now.  Window entry k (0-based) is step i = t - W + 1 + k, W = window_steps.
+ * probs (nullable) [W][cap] receives this oracle's probabilities (0 where a row is not
+ * visible to the step); p_forced (nullable) [W][ld] replaces them in the low decision. */
+static void recompute_record_unit(const sco_cache *h, int u, int *I, double *probs,
+                                  const float *p_forced, int ld) {
+    const int n = h->n, d = h->d, cap = h->cap, w = h->w;
+    const int W = window_steps(h);
+    const float *K = h->K + (size_t)u * cap * d;
+    const int64_t *pos = h->pos + (size_t)u * cap;
+    double *s = (double *)malloc(sizeof(double) * (size_t)(n + d));
+    double *qd = s + n;
+    for (int j = 0; j < n; ++j) I[j] = 0;
+    for (int k = 0; k < W; ++k) {
+        const int64_t i = h->t - W + 1 + k; /* the step whose query is replayed */
+        const float *q = h->Qh + ((size_t)u * w + (size_t)(i % w)) * d;
+        int vis = 0; /* rows are kept in order of position, so the visible ones come first */
+        while (vis < n && pos[vis] <= i - 1) ++vis;
+        if (probs)
+            for (int j = 0; j < cap; ++j) probs[(size_t)k * cap + j] = 0.0;
+        if (vis == 0) continue;
+        for (int ch = 0; ch < d; ++ch) qd[ch] = (double)q[ch];
+        attention_probabilities(h, K, vis, qd, s);
+        const float tau = h->cfg.thresh_mode == SCO_INV_LEN ? 1.0f / (float)vis : 1.0f / (float)i;
+        for (int j = 0; j < vis; ++j) {
+            const double p = s[j];
+            if (probs) probs[(size_t)k * cap + j] = p;
+            const float pf = p_forced ? p_forced[(size_t)k * ld + j] : (float)p;
+            I[j] += (pf < tau);
+        }
+    }
+    free(s);
+}
+
+/* I [U][n]: importance record of every resident row over the current history window
+ * (online flags, or recomputed from the kept queries, according to the record mode). */
 int sco_importance(const sco_cache *h, int32_t *I) {
+    if (!h || !I) return 1;
+    for (int u = 0; u < h->U; ++u) {
+        if (h->cfg.record_mode == SCO_RECORD_RECOMPUTE) {
+            int *tmp = (int *)malloc(sizeof(int) * (size_t)h->n);
+            recompute_record_unit(h, u, tmp, NULL, NULL, 0);
+            for (int j = 0; j < h->n; ++j) I[(size_t)u * h->n + j] = tmp[j];
+            free(tmp);
+        } else {
+            for (int j = 0; j < h->n; ++j) I[(size_t)u * h->n + j] = importance_of(h, u, j);
+        }
+    }
+    return 0;
+}
+
+/* The online record whatever the mode (the flags are always kept): lets a test compare the
+ * two records on the same run. */
+int sco_importance_online(const sco_cache *h, int32_t *I) {
     if (!h || !I) return 1;
     for (int u = 0; u < h->U; ++u)
         for (int j = 0; j < h->n; ++j) I[(size_t)u * h->n + j] = importance_of(h, u, j);
@@ -413,6 +493,11 @@ int sco_rows(const sco_cache *h, float *K, float *V) {
 typedef struct {
     sco_cache *h;
     int32_t *evicted; /* [U][m] or NULL */
+    /* record mode "recompute" only (all nullable): */
+    double *re_probs;        /* [U][W][cap] */
+    const float *re_forced;  /* [U][W][re_ld] */
+    int re_ld;
+    int32_t *record_out;     /* [U][n] the record the selection used */
 } compress_ctx;
 
 static void compress_unit(void *vctx, int u) {
@@ -422,7 +507,15 @@ static void compress_unit(void *vctx, int u) {
     const int ncand = n - h->r; /* the r most recent slots are never candidates */
     int *I = (int *)malloc(sizeof(int) * (size_t)n);
     uint8_t *gone = (uint8_t *)calloc((size_t)n, 1);
-    for (int j = 0; j < n; ++j) I[j] = importance_of(h, u, j);
+    if (h->cfg.record_mode == SCO_RECORD_RECOMPUTE) {
+        const int W = window_steps(h);
+        recompute_record_unit(h, u, I, c->re_probs ? c->re_probs + (size_t)u * W * cap : NULL,
+                              c->re_forced ? c->re_forced + (size_t)u * W * c->re_ld : NULL, c->re_ld);
+    } else {
+        for (int j = 0; j < n; ++j) I[j] = importance_of(h, u, j);
+    }
+    if (c->record_out)
+        for (int j = 0; j < n; ++j) c->record_out[(size_t)u * n + j] = I[j];
     /* Drop the m candidates with the largest record; equal records: lowest slot first. */
     for (int k = 0; k < m; ++k) {
         int best = -1;
@@ -455,6 +548,12 @@ static void compress_unit(void *vctx, int u) {
     free(gone);
 }
 
+static void run_compression(compress_ctx *c) {
+    sco_cache *h = c->h;
+    for_each_unit(h, compress_unit, c);
+    h->n -= h->m;
+}
+
 /* Alg. 2.  Only legal when the last step reported due.  evicted [U][m] (nullable)
  * receives the dropped slots of each unit in ascending order (slot numbers before
  * compaction).  Returns 0, or 1 when not due. */
@@ -462,9 +561,31 @@ int sco_compress(sco_cache *h, int32_t *evicted) {
     if (!h) return 1;
     if (h->n != h->cap) return 1;
     compress_ctx c;
+    memset(&c, 0, sizeof(c));
     c.h = h;
     c.evicted = evicted;
-    for_each_unit(h, compress_unit, &c);
-    h->n -= h->m;
+    run_compression(&c);
+    return 0;
+}
+
+/* Alg. 2 in record mode "recompute", with the replayed attention exposed:
+ * probs [U][W][cap] double (nullable) receives the oracle's probabilities of the W = min(w, t)
+ * replayed steps (oldest first); p_forced [U][W][ld] fp32 (nullable) replaces them in the
+ * low decision; record_out [U][n] (nullable) receives the record the selection used.
+ * Returns 0, or 1 when not due or not in that mode. */
+int sco_compress_recompute(sco_cache *h, int32_t *evicted, double *probs, const float *p_forced,
+                           int ld, int32_t *record_out) {
+    if (!h) return 1;
+    if (h->n != h->cap || h->cfg.record_mode != SCO_RECORD_RECOMPUTE) return 1;
+    if (p_forced && ld < h->n) return 1;
+    compress_ctx c;
+    memset(&c, 0, sizeof(c));
+    c.h = h;
+    c.evicted = evicted;
+    c.re_probs = probs;
+    c.re_forced = p_forced;
+    c.re_ld = ld;
+    c.record_out = record_out;
+    run_compression(&c);
     return 0;
 }

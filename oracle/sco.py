@@ -24,6 +24,7 @@ _LIB = os.path.join(_HERE, "libsco.so")
 F32, F16, I4G64 = 0, 1, 2
 HARD_CAP, HIGH_WATER = 0, 1
 INV_POS, INV_LEN = 0, 1
+RECORD_ONLINE, RECORD_RECOMPUTE = 0, 1
 
 
 def build(force: bool = False) -> str:
@@ -41,7 +42,7 @@ def build(force: bool = False) -> str:
 class _Cfg(C.Structure):
     _fields_ = [(k, C.c_int32) for k in (
         "batch", "heads", "head_dim", "kv_dtype", "budget", "recent", "history", "drop",
-        "trigger", "thresh_mode")] + [("scale", C.c_double)]
+        "trigger", "thresh_mode")] + [("scale", C.c_double), ("record_mode", C.c_int32)]
 
 
 _lib = None
@@ -58,7 +59,10 @@ def lib():
                               C.POINTER(C.c_int32)]
         l.sco_step.argtypes = [C.c_void_p] + [C.c_void_p] * 6 + [C.c_int, C.POINTER(C.c_int32)]
         l.sco_compress.argtypes = [C.c_void_p, C.c_void_p]
+        l.sco_compress_recompute.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                             C.c_void_p]
         l.sco_importance.argtypes = [C.c_void_p, C.c_void_p]
+        l.sco_importance_online.argtypes = [C.c_void_p, C.c_void_p]
         l.sco_positions.argtypes = [C.c_void_p, C.c_void_p]
         l.sco_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         l.sco_i4_roundtrip.argtypes = [C.c_void_p, C.c_int] + [C.c_void_p] * 4
@@ -83,6 +87,7 @@ class OracleConfig:
     trigger: int = HARD_CAP
     thresh_mode: int = INV_POS
     scale: float = 0.0
+    record_mode: int = RECORD_ONLINE
 
 
 def _ptr(a):
@@ -96,7 +101,8 @@ class Oracle:
         self.cfg = cfg
         self.nthreads = int(nthreads or os.cpu_count() or 1)
         c = _Cfg(cfg.batch, cfg.heads, cfg.head_dim, cfg.kv_dtype, cfg.budget, cfg.recent,
-                 cfg.history, cfg.drop, cfg.trigger, cfg.thresh_mode, float(cfg.scale))
+                 cfg.history, cfg.drop, cfg.trigger, cfg.thresh_mode, float(cfg.scale),
+                 cfg.record_mode)
         self._h = lib().sco_create(C.byref(c), self.nthreads)
         if not self._h:
             raise ValueError("oracle rejected the configuration: %r" % (cfg,))
@@ -155,9 +161,34 @@ class Oracle:
             raise RuntimeError("sco_compress called while no compression is due")
         return ev
 
+    def compress_recompute(self, p_forced=None, want_probs=True):
+        """Alg. 2 in record mode "recompute".  Returns (evicted [U, m], probs [U, W, cap] f64 or
+        None, record [U, n]) where W = min(w, t) replayed steps, oldest first.  ``p_forced``
+        [U, W, >=n] fp32 replaces the oracle's probabilities in the low-score decision."""
+        n, t, _ = self.lengths()
+        W = min(self.cfg.history, t)
+        ev = np.empty((self.U, self.cfg.drop), dtype=np.int32)
+        probs = np.empty((self.U, W, self.cap), dtype=np.float64) if want_probs else None
+        rec = np.empty((self.U, n), dtype=np.int32)
+        ld = 0
+        if p_forced is not None:
+            p_forced = np.ascontiguousarray(p_forced, dtype=np.float32)
+            assert p_forced.ndim == 3 and p_forced.shape[:2] == (self.U, W)
+            ld = p_forced.shape[2]
+        rc = lib().sco_compress_recompute(self._h, _ptr(ev), _ptr(probs), _ptr(p_forced), ld, _ptr(rec))
+        if rc:
+            raise RuntimeError("sco_compress_recompute refused the call (not due, or online mode)")
+        return ev, probs, rec
+
     def importance(self):
         I = np.empty((self.U, self.n), dtype=np.int32)
         lib().sco_importance(self._h, _ptr(I))
+        return I
+
+    def importance_online(self):
+        """The online record whatever the record mode."""
+        I = np.empty((self.U, self.n), dtype=np.int32)
+        lib().sco_importance_online(self._h, _ptr(I))
         return I
 
     def positions(self):

@@ -27,8 +27,8 @@ MUTATIONS = {
                                "o[ch] += s[j] * (double)V[(size_t)j * d + (d - 1 - ch)];"),
     "key-used-as-value": ("o[ch] += s[j] * (double)V[(size_t)j * d + ch];",
                           "o[ch] += s[j] * (double)K[(size_t)j * d + ch];"),
-    "self-row-excluded": ("for (int j = 0; j < n; ++j) {\n        double acc = 0.0;",
-                          "for (int j = 0; j < n - 1 + (n == 1); ++j) {\n        double acc = 0.0;"),
+    "self-row-excluded": ("attention_probabilities(h, K, n, qd, s); /* s now",
+                          "attention_probabilities(h, K, n - 1 + (n == 1), qd, s); s[n - 1] = n == 1 ? s[0] : 0.0; /* s now"),
     "threshold-not-strict": ("(uint8_t)(pj < c->tau)", "(uint8_t)(pj <= c->tau)"),
     "threshold-on-length": ("1.0f / (float)c.n_after : 1.0f / (float)c.t_after",
                             "1.0f / (float)c.n_after : 1.0f / (float)c.n_after"),
@@ -45,6 +45,17 @@ MUTATIONS = {
     "trigger-at-budget": ("c->budget + 1;", "c->budget;"),
     "int4-truncates": ("float rq = nearbyintf(qv);", "float rq = floorf(qv);"),
     "int4-scale-from-max": ("volatile float range = mx - mn;", "volatile float range = mx;"),
+    # record mode "recompute"
+    "replay-sees-one-future-row": ("while (vis < n && pos[vis] <= i - 1) ++vis;",
+                                   "while (vis < n && pos[vis] <= i) ++vis;"),
+    "replay-threshold-uses-current-step": ("1.0f / (float)vis : 1.0f / (float)i;",
+                                           "1.0f / (float)vis : 1.0f / (float)h->t;"),
+    "replay-window-off-by-one": ("const int64_t i = h->t - W + 1 + k;", "const int64_t i = h->t - W + k;"),
+    "replay-wrong-query": ("const float *q = h->Qh + ((size_t)u * w + (size_t)(i % w)) * d;",
+                           "const float *q = h->Qh + ((size_t)u * w + (size_t)((i + 1) % w)) * d;"),
+    "query-not-kept": ("qkeep[ch] = (float)qd[ch];", "qkeep[ch] = 0.0f;"),
+    "replay-counts-invisible-rows": ("for (int j = 0; j < vis; ++j) {\n            const double p = s[j];",
+                                     "for (int j = 0; j < n; ++j) {\n            const double p = j < vis ? s[j] : 0.0;"),
 }
 
 
@@ -62,10 +73,10 @@ def _build(tmp_path, name, old, new):
 class _Cache:
     """Minimal driver of a (possibly mutated) oracle library."""
 
-    def __init__(self, lib, heads, d, kv, B, r, w, m, trigger=0, thresh=0):
+    def __init__(self, lib, heads, d, kv, B, r, w, m, trigger=0, thresh=0, record_mode=0):
         self.l = C.CDLL(lib)
         self.l.sco_create.restype = C.c_void_p
-        cfg = sco._Cfg(1, heads, d, kv, B, r, w, m, trigger, thresh, 0.0)
+        cfg = sco._Cfg(1, heads, d, kv, B, r, w, m, trigger, thresh, 0.0, record_mode)
         self.h = C.c_void_p(self.l.sco_create(C.byref(cfg), 1))
         assert self.h
         self.U, self.d, self.m = heads, d, m
@@ -109,6 +120,20 @@ class _Cache:
         ev = np.zeros((self.U, self.m), np.int32)
         assert self.l.sco_compress(self.h, ev.ctypes.data_as(C.c_void_p)) == 0
         return ev
+
+    def importance_online(self):
+        I = np.zeros((self.U, self.n()), np.int32)
+        self.l.sco_importance_online(self.h, I.ctypes.data_as(C.c_void_p))
+        return I
+
+    def compress_recompute(self, W):
+        n = self.n()
+        ev = np.zeros((self.U, self.m), np.int32)
+        probs = np.zeros((self.U, W, self.cap))
+        rec = np.zeros((self.U, n), np.int32)
+        p = lambda a: a.ctypes.data_as(C.c_void_p)
+        assert self.l.sco_compress_recompute(self.h, p(ev), p(probs), None, 0, p(rec)) == 0
+        return ev, probs, rec
 
 
 def _pins(lib):
@@ -164,6 +189,38 @@ def _pins(lib):
                     if tot > best_sum:
                         best, best_sum = sub, tot
                 assert tuple(ev[u].tolist()) == best
+    # (2b) record mode "recompute": equal to the online record while nothing has been evicted;
+    # afterwards the replayed probabilities are full attention restricted to the survivors
+    # and the record is their count below 1/i over the rows each replayed step could see
+    B, r, w, m = 10, 3, 5, 3
+    T = 40
+    q, k, v = (rng.standard_normal((U, T, d)).astype(np.float32) for _ in range(3))
+    q *= 3.0
+    c = _Cache(lib, U, d, sco.F32, B, r, w, m, record_mode=1)
+    evicted_yet = False
+    for s in range(T):
+        out, probs, due = c.step(q[:, s], k[:, s], v[:, s])
+        t = s + 1
+        if not evicted_yet:
+            assert np.array_equal(c.importance(), c.importance_online())
+        if due:
+            pos = c.positions()
+            n = c.n()
+            W = min(w, t)
+            ev, pr, rec = c.compress_recompute(W)
+            want = np.zeros((U, n), np.int64)
+            for kk in range(W):
+                i = t - W + 1 + kk
+                for u in range(U):
+                    vis = pos[u] <= i - 1
+                    lg = (k[u, :i].astype(np.float64) @ q[u, i - 1].astype(np.float64)) / np.sqrt(d)
+                    beta = np.exp(lg - lg.max())
+                    b = beta[pos[u][vis]]
+                    np.testing.assert_allclose(pr[u, kk, :n][vis], b / b.sum(), rtol=1e-9)
+                    assert np.all(pr[u, kk, :n][~vis] == 0.0)
+                    want[u] += (pr[u, kk, :n].astype(np.float32) < np.float32(1.0) / np.float32(i)) & vis
+            assert np.array_equal(rec, want)
+            evicted_yet = True
     # (3) identical keys: nothing is ever low (strict threshold on 1/t)
     c = _Cache(lib, 1, 4, sco.F32, 64, 1, 64, 1)
     one = np.ones((1, 4), np.float32)

@@ -433,3 +433,110 @@ def test_int4_cache_attends_over_stored_values():
         p = torch.softmax(lg, 0).numpy()
         np.testing.assert_allclose(probs[u, :T], p, rtol=1e-12)
         np.testing.assert_allclose(out[u], p @ Vs[u].astype(np.float64), rtol=1e-11, atol=1e-13)
+
+
+# --------------------------------------------------------------------------------------
+# Record mode "recompute": Alg. 2 as printed collects the record at compression time with an
+# extra attention computation over the history window (Sec. 4.1, "Overhead Tradeoff").
+# --------------------------------------------------------------------------------------
+def _recompute_cfg(**kw):
+    return _cfg(record_mode=sco.RECORD_RECOMPUTE, **kw)
+
+
+@pytest.mark.parametrize("thresh", [sco.INV_POS, sco.INV_LEN])
+def test_recompute_equals_online_until_the_first_eviction(thresh):
+    """Before anything has been evicted the rows resident now that step i could see are the
+    rows step i did see, so replaying its attention changes nothing: the recomputed record is
+    the online record, at every step up to and including the first compression."""
+    rng = np.random.default_rng(21)
+    U, d, B, r, w, m = 3, 16, 14, 2, 6, 4
+    T = B + 1
+    q, k, v = _rand(rng, U, T, d)
+    q *= 2.5
+    o = Oracle(_recompute_cfg(heads=U, head_dim=d, budget=B, recent=r, history=w, drop=m,
+                              thresh_mode=thresh))
+    for s in range(T):
+        _, _, due = o.step(q[:, s], k[:, s], v[:, s])
+        assert np.array_equal(o.importance(), o.importance_online()), "step %d" % s
+        assert o.importance().max() > 0 or s < 3
+    assert due
+    online = o.importance_online()
+    ev, probs, rec = o.compress_recompute()
+    assert np.array_equal(rec, online)
+
+
+def test_recompute_with_window_of_one_is_the_online_record():
+    """With w = 1 only the current step is replayed, over exactly the rows it has just
+    attended over: both record modes coincide at every compression, also after evictions."""
+    rng = np.random.default_rng(22)
+    U, d, B, r, m = 2, 8, 9, 2, 3
+    T = 40
+    q, k, v = _rand(rng, U, T, d)
+    q *= 3.0
+    o = Oracle(_recompute_cfg(heads=U, head_dim=d, budget=B, recent=r, history=1, drop=m))
+    seen = 0
+    for s in range(T):
+        _, _, due = o.step(q[:, s], k[:, s], v[:, s])
+        if due:
+            online = o.importance_online()
+            _, _, rec = o.compress_recompute()
+            assert np.array_equal(rec, online)
+            seen += 1
+    assert seen >= 5
+
+
+def test_recompute_probabilities_are_full_attention_restricted_to_the_survivors():
+    """Restricted-softmax identity used in the proof of Lemma A.4: the replayed attention of
+    step i over the rows that survive is the full-attention distribution of step i restricted
+    to those rows and renormalised.  The full-attention side comes from a shadow cache that
+    never evicts (pinned above against a library softmax).  The record then follows from
+    those probabilities and the threshold 1/i; rows born after step i are not seen by it."""
+    rng = np.random.default_rng(23)
+    U, d, B, r, w, m = 2, 16, 12, 3, 7, 4
+    T = 60
+    q, k, v = _rand(rng, U, T, d)
+    q *= 2.0
+    o = Oracle(_recompute_cfg(heads=U, head_dim=d, budget=B, recent=r, history=w, drop=m))
+    full = Oracle(_cfg(heads=U, head_dim=d, budget=T, recent=r, history=w, drop=m))
+    beta = []  # beta[s][u, :s+1]: full attention of step s+1 over all tokens
+    compressions = 0
+    for s in range(T):
+        _, _, due = o.step(q[:, s], k[:, s], v[:, s])
+        _, pf, _ = full.step(q[:, s], k[:, s], v[:, s])
+        beta.append(pf[:, : s + 1].copy())
+        if not due:
+            continue
+        t = s + 1
+        pos = o.positions()
+        n = o.n
+        ev, probs, rec = o.compress_recompute()
+        W = min(w, t)
+        want = np.zeros((U, n), dtype=np.int64)
+        for kk in range(W):
+            i = t - W + 1 + kk
+            for u in range(U):
+                vis = pos[u] <= i - 1
+                assert vis.any()
+                b = beta[i - 1][u][pos[u][vis]]
+                np.testing.assert_allclose(probs[u, kk, :n][vis], b / b.sum(), rtol=1e-9)
+                assert np.all(probs[u, kk, :n][~vis] == 0.0)
+                low = probs[u, kk, :n].astype(np.float32) < np.float32(1.0) / np.float32(i)
+                want[u] += low & vis
+        assert np.array_equal(rec, want)
+        compressions += 1
+    assert compressions >= 8
+
+
+def test_recompute_forced_probabilities_drive_only_the_record():
+    rng = np.random.default_rng(24)
+    U, d, B, r, w, m = 2, 8, 9, 2, 4, 3
+    q, k, v = _rand(rng, U, B + 1, d)
+    o = Oracle(_recompute_cfg(heads=U, head_dim=d, budget=B, recent=r, history=w, drop=m))
+    for s in range(B + 1):
+        o.step(q[:, s], k[:, s], v[:, s])
+    forced = np.ones((U, w, B + 1), dtype=np.float32)   # nothing is low ...
+    forced[:, :, 5] = 0.0                                # ... except slot 5, for every replayed step
+    ev, probs, rec = o.compress_recompute(p_forced=forced)
+    assert np.all(rec[:, 5] == w) and rec.sum() == U * w
+    assert np.array_equal(ev, np.array([[0, 1, 5]] * U))  # the largest record, then ties by age
+    assert np.all(np.abs(probs.sum(axis=2) - 1.0) < 1e-12)  # the oracle's own probabilities are untouched
