@@ -168,6 +168,9 @@ def main() -> int:
     ap.add_argument("--window", choices=("auto", "ring"), default="auto",
                     help="importance record: bucket counters (auto, when w is a multiple of m) or "
                          "the exact one-bit-per-step ring")
+    ap.add_argument("--record", choices=("online", "recompute"), default="online",
+                    help="importance record kept during the steps (headline) or rebuilt at each "
+                         "compression by replaying the last w queries (fp16 workloads)")
     ap.add_argument("--no-events", action="store_true", help="skip the per-launch HIP events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=512)
@@ -190,7 +193,8 @@ def main() -> int:
     if args.phase == "prefill":
         return bench_prefill(args, wl, dev)
     cfg = B.make_config(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.budget, wl.recent, wl.history,
-                        wl.drop, window_mode=B.SC_WINDOW_RING if args.window == "ring" else B.SC_WINDOW_AUTO)
+                        wl.drop, window_mode=B.SC_WINDOW_RING if args.window == "ring" else B.SC_WINDOW_AUTO,
+                        record_mode=B.SC_RECORD_RECOMPUTE if args.record == "recompute" else B.SC_RECORD_ONLINE)
     ws_bytes = B.sc_workspace_bytes(cfg)
     R = args.rotate or min(8, max(1, -(-3 * 256 * 2 ** 20 // ws_bytes)))
     T, d, U = wl.total, wl.head_dim, wl.units
@@ -279,7 +283,7 @@ def main() -> int:
         "config": {
             "workload": wl.name, "batch": wl.batch, "heads": wl.heads, "head_dim": wl.head_dim,
             "prompt": wl.prompt, "decode": wl.decode, "budget": wl.budget, "recent": wl.recent,
-            "history": wl.history, "drop": wl.drop, "trigger": "hard_cap", "window": args.window,
+            "history": wl.history, "drop": wl.drop, "trigger": "hard_cap", "window": args.window, "record": args.record,
             "cache_instances_round_robin": R, "compressions_in_timed_region": compress_events,
             "resident_rows_avg": sum(n_log) / len(n_log),
         },

@@ -79,6 +79,17 @@ typedef enum {
     SC_WINDOW_RING = 1    /* one bit per (row, step) in a ring of w bits: any w, w/8 bytes/row */
 } sc_window;
 
+/* When the importance record of Alg. 2 is collected.  Sec. 4.1 ("Overhead Tradeoff") names
+ * both: Alg. 2 as printed spends "an extra attention computation" at the compression step,
+ * or a little memory keeps the record up to date during the generation steps. */
+typedef enum {
+    SC_RECORD_ONLINE = 0,    /* counted at every step from that step's own probabilities        */
+    SC_RECORD_RECOMPUTE = 1  /* the last w queries are kept; at a compression each is replayed
+                                over the rows resident then that its step could see (stream
+                                position <= its own), softmax over exactly those rows, low =
+                                below that step's threshold.  fp16 storage only.                */
+} sc_record;
+
 /* Problem statement of Def. 4.1 / inputs of Alg. 1 and Alg. 2. */
 typedef struct {
     int32_t batch, heads; /* U = batch*heads independent units                               */
@@ -91,6 +102,7 @@ typedef struct {
     int32_t trigger;      /* sc_trigger                                                      */
     int32_t thresh_mode;  /* sc_thresh                                                       */
     int32_t window_mode;  /* sc_window                                                       */
+    int32_t record_mode;  /* sc_record                                                       */
     float scale;          /* score scale; 0 selects 1/sqrt(head_dim)                         */
 } sc_config;
 
@@ -98,7 +110,8 @@ typedef struct {
  *   n_trig   : number of resident rows at which a compression becomes due
  *   capacity : row stride of every per-unit array (n_trig rounded up to a multiple of 64);
  *              also the leading dimension of probs_out
- *   buckets  : E = w/m 16-bit counter buckets kept per row (0 when the exact ring is used)
+ *   buckets  : E = w/m 16-bit counter buckets kept per row (0 when the exact ring is used;
+ *              1 with SC_RECORD_RECOMPUTE: the record itself, rebuilt at every compression)
  *   ring_words : ceil(w/32) 32-bit ring words kept per row (0 when buckets are used)
  * Returns SC_ERR_INVALID_ARG / SC_ERR_UNSUPPORTED for a bad configuration. */
 sc_status sc_config_sizes(const sc_config *cfg, int32_t *n_trig, int32_t *capacity, int32_t *buckets,
@@ -150,8 +163,12 @@ sc_status sc_decode_step(sc_cache *c, const void *q, const void *k_new, const vo
  * order; n <- n - m.
  *   evicted_out : device int32 [U][m] or NULL; the dropped slots (numbering before
  *                 compaction) of each unit in ascending order
+ *   probs_out   : SC_RECORD_RECOMPUTE only (ignored otherwise), device fp32
+ *                 [U][min(w, t)][capacity] or NULL: row k receives, for the rows that replayed
+ *                 step t - min(w, t) + 1 + k sees, exactly the probabilities its threshold
+ *                 test was applied to; other elements are untouched
  * SC_ERR_STATE unless the previous step reported compress_due. */
-sc_status sc_compress(sc_cache *c, int32_t *evicted_out, void *stream);
+sc_status sc_compress(sc_cache *c, int32_t *evicted_out, float *probs_out, void *stream);
 
 /* How sc_prefill computes.  The result is the same function of the inputs either way; the
  * floating-point rounding differs (summation order, fp16 probabilities in P.V). */

@@ -19,6 +19,7 @@ SC_TRIGGER_HARD_CAP, SC_TRIGGER_HIGH_WATER = 0, 1
 SC_THRESH_INV_POS, SC_THRESH_INV_LEN = 0, 1
 SC_WINDOW_AUTO, SC_WINDOW_RING = 0, 1
 SC_PREFILL_AUTO, SC_PREFILL_STREAMED = 0, 1
+SC_RECORD_ONLINE, SC_RECORD_RECOMPUTE = 0, 1
 
 EXPORTS = (
     "sc_config_sizes", "sc_workspace_bytes", "sc_schedule", "sc_cache_create", "sc_cache_reset",
@@ -30,7 +31,7 @@ EXPORTS = (
 class sc_config(C.Structure):
     _fields_ = [(k, C.c_int32) for k in (
         "batch", "heads", "head_dim", "kv_dtype", "budget", "recent", "history", "drop",
-        "trigger", "thresh_mode", "window_mode")] + [("scale", C.c_float)]
+        "trigger", "thresh_mode", "window_mode", "record_mode")] + [("scale", C.c_float)]
 
 
 class ScError(RuntimeError):
@@ -63,7 +64,7 @@ def lib():
     l.sc_cache_destroy.argtypes = [vp]
     l.sc_cache_destroy.restype = None
     l.sc_decode_step.argtypes = [vp, vp, vp, vp, C.c_int64, vp, vp, i32p, vp]
-    l.sc_compress.argtypes = [vp, vp, vp]
+    l.sc_compress.argtypes = [vp, vp, vp, vp]
     l.sc_prefill.argtypes = [vp, vp, vp, vp, C.c_int32, C.c_int64, vp, vp, C.c_int32, vp]
     l.sc_prefill_plan.argtypes = [cfgp, C.c_int32, C.c_int32, C.c_int32, i32p, i32p, i32p, i32p]
     l.sc_cache_len.argtypes = [vp, i32p, i64p]
@@ -84,9 +85,9 @@ def _check(status: int, where: str):
 
 def make_config(batch, heads, head_dim, kv_dtype, budget, recent, history, drop,
                 trigger=SC_TRIGGER_HARD_CAP, thresh_mode=SC_THRESH_INV_POS, scale=0.0,
-                window_mode=SC_WINDOW_AUTO) -> sc_config:
+                window_mode=SC_WINDOW_AUTO, record_mode=SC_RECORD_ONLINE) -> sc_config:
     return sc_config(batch, heads, head_dim, kv_dtype, budget, recent, history, drop, trigger,
-                     thresh_mode, window_mode, scale)
+                     thresh_mode, window_mode, record_mode, scale)
 
 
 # ---- functions with the names of the C ABI -------------------------------------------------
@@ -137,8 +138,8 @@ def sc_decode_step(handle, q_ptr, k_ptr, v_ptr, in_stride, out_ptr, probs_ptr=No
     return bool(due.value)
 
 
-def sc_compress(handle, evicted_ptr=None, stream=0) -> None:
-    _check(lib().sc_compress(handle, evicted_ptr, stream), "sc_compress")
+def sc_compress(handle, evicted_ptr=None, probs_ptr=None, stream=0) -> None:
+    _check(lib().sc_compress(handle, evicted_ptr, probs_ptr, stream), "sc_compress")
 
 
 def sc_prefill(handle, q_ptr, k_ptr, v_ptr, prompt_len, unit_stride, out_ptr=None, probs_ptr=None,
@@ -227,8 +228,9 @@ class BudgetCache:
                               out.data_ptr(), None if probs_out is None else probs_out.data_ptr(),
                               self._stream())
 
-    def compress(self, evicted_out=None) -> None:
-        sc_compress(self.handle, None if evicted_out is None else evicted_out.data_ptr(), self._stream())
+    def compress(self, evicted_out=None, probs_out=None) -> None:
+        sc_compress(self.handle, None if evicted_out is None else evicted_out.data_ptr(),
+                    None if probs_out is None else probs_out.data_ptr(), self._stream())
 
     def prefill(self, q, k, v, prompt_len, unit_stride=0, out=None, probs_out=None,
                 mode=SC_PREFILL_AUTO) -> None:

@@ -60,6 +60,8 @@ struct AttnArgs {
     int n, C;  // n counts the row appended by this launch
     float qk_log2, tau;
     int counted;
+    void* q_keep;         // where unit 0's query of this step is kept (record rebuilt at
+    long q_keep_stride;   // compression time), elements between units; null: not kept
 };
 
 template <typename T, int N>
@@ -227,6 +229,8 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
     F qr;
     qr.raw = *reinterpret_cast<const uint4*>((const T*)a.q + in_off);
     const bool owner = (wv == 0) && (g == 0);  // Alg. 1 model update: who holds the new row
+    if (a.q_keep && owner)  // Alg. 2 as printed replays this query at the next compressions
+        *reinterpret_cast<uint4*>((T*)a.q_keep + (size_t)u * a.q_keep_stride + c * EPL) = qr.raw;
     F k_own, v_own;
     k_own.raw = make_uint4(0, 0, 0, 0);
     v_own.raw = make_uint4(0, 0, 0, 0);
@@ -951,6 +955,8 @@ hipError_t launch_decode_step(const Layout& L, const StepArgs& s, hipStream_t st
     a.qk_log2 = s.qk_log2;
     a.tau = s.tau;
     a.counted = s.counted;
+    a.q_keep = s.q_keep;
+    a.q_keep_stride = (long)L.w * L.d;
     const int nw = pick_waves(L.U);
     if (L.kv_dtype == KV_F32)
         return L.d == 64 ? launch_rows<float, 64, 2>(a, L.U, nw, stream)

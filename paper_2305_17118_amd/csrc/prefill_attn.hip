@@ -47,6 +47,20 @@ append_rows_kernel(const char* __restrict__ k, const char* __restrict__ v, long 
     if (e - row * row16 == 0) pos[(size_t)u * C + n0 + row] = t0 + row;
 }
 
+// grid (U, pieces/256): one 16-byte piece of a query row per thread; step t0+1+row goes to
+// ring slot (t0 + row) mod w.  count <= w, so no two rows share a slot.
+__global__ void __launch_bounds__(256)
+store_queries_kernel(const char* __restrict__ q, long unit_stride_bytes, char* __restrict__ ring, int w,
+                     int row16, int count, long t0) {
+    const int u = blockIdx.x;
+    const int e = blockIdx.y * 256 + threadIdx.x;
+    if (e >= count * row16) return;
+    const int row = e / row16, piece = e - row * row16;
+    const size_t slot = (size_t)((t0 + row) % w);
+    *reinterpret_cast<uint4*>(ring + (((size_t)u * w + slot) * row16 + piece) * 16) =
+        *reinterpret_cast<const uint4*>(q + (size_t)u * unit_stride_bytes + (size_t)e * 16);
+}
+
 struct PrefillArgs {
     const _Float16* q;
     long unit_stride;
@@ -64,6 +78,11 @@ struct PrefillArgs {
     long t0;
     int counted, thresh_len;
     float qk_log2;
+    // Replay of kept queries (record collected at compression time): positions of the resident
+    // rows, their number, and the length of the query ring; null / 0 for a prompt run.
+    const int32_t* pos;
+    int n_rows;
+    int ring_w;
 };
 
 // Matrix-instruction operand layout (16x16x32, fp16 in, fp32 out), lane l, i = l%16, g = l/16:
@@ -77,7 +96,14 @@ struct PrefillArgs {
 // At least two waves per SIMD: the register budget that goes with it (256) also makes the
 // compiler keep the matrix accumulators in ordinary vector registers, where the running-softmax
 // rescale can reach them without copies.
-template <int D>
+//
+// WITH_PV = false drops the value side (no V tile, no P.V, no output): that is the replay of
+// Alg. 2 as printed, which recomputes the attention of the last w queries over the rows
+// resident at compression time only to count low probabilities.  There the queries come
+// from a ring (step i in slot (i-1) mod w) and the last row step i may see is found from the
+// rows' stream positions (rows are kept in order of position): the last one with
+// position <= i-1.
+template <int D, bool WITH_PV>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
 prefill_chunk_kernel(PrefillArgs a) {
     constexpr int KB = 64;        // cache rows per tile
@@ -90,6 +116,7 @@ prefill_chunk_kernel(PrefillArgs a) {
     __shared__ __align__(16) _Float16 Ks[KB * LDK];
     __shared__ __align__(16) _Float16 Vt[D * LDV];
     __shared__ float stat_m[QB], stat_inv[QB];  // per query: final maximum, 1/sum (pass 1 -> pass 2)
+    __shared__ int stat_lim[QB];                // per query: last row it sees (-1: none)
     extern __shared__ int cnt_lds[];  // [tiles * 64] low-score counts of this workgroup's queries
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -98,19 +125,43 @@ prefill_chunk_kernel(PrefillArgs a) {
     const int q0 = (a.nqb - 1 - (int)(blockIdx.x % a.nqb)) * QB;  // longest query blocks first
     const int qi = q0 + 16 * w + li;                 // this lane's query (position in the run)
     const int qc = qi < a.c ? qi : a.c - 1;          // clamped: padding lanes shadow the last query
-    const int lim = a.n0 + qc;                       // last cache row query qc sees
     const int q_last = (q0 + QB < a.c ? q0 + QB : a.c) - 1;
-    const int hi = a.n0 + q_last + 1;                // rows visible to this workgroup
+    // Last cache row each of the workgroup's queries sees.  Prompt run: n0 + query index.
+    // Replay: rows with position <= t0 + query index (binary search over the positions, staged
+    // in the LDS array that later holds the counts).
+    if (a.pos) {
+        const int32_t* pu = a.pos + (size_t)u * a.C;
+        for (int i = tid; i < a.n_rows; i += 256) cnt_lds[i] = pu[i];
+        __syncthreads();
+        if (tid < QB) {
+            const int q = q0 + tid < a.c ? q0 + tid : a.c - 1;
+            const int want = (int)a.t0 + q;
+            int lo = 0, up = a.n_rows;
+            while (lo < up) {
+                const int mid = (lo + up) >> 1;
+                if (cnt_lds[mid] <= want) lo = mid + 1; else up = mid;
+            }
+            stat_lim[tid] = lo - 1;
+        }
+    } else if (tid < QB) {
+        stat_lim[tid] = a.n0 + (q0 + tid < a.c ? q0 + tid : a.c - 1);
+    }
+    __syncthreads();
+    const int lim_raw = stat_lim[16 * w + li];
+    const bool valid = qi < a.c && lim_raw >= 0;     // a real query that sees at least one row
+    const int lim = lim_raw > 0 ? lim_raw : 0;       // (a query that sees nothing shadows row 0, never stored)
+    const int hi = (stat_lim[q_last - q0] > 0 ? stat_lim[q_last - q0] : 0) + 1;  // rows visible to this workgroup
     const int ntiles = (hi + KB - 1) / KB;
-    const int wave_lim = a.n0 + (q0 + 16 * w + 15 < a.c ? q0 + 16 * w + 15 : a.c - 1);  // last row any query of the wave sees
-    const int wave_first_lim = a.n0 + (q0 + 16 * w < a.c ? q0 + 16 * w : a.c - 1);      // last row ALL of them see
+    const int wave_lim = stat_lim[16 * w + 15] > 0 ? stat_lim[16 * w + 15] : 0;  // last row any query of the wave sees
+    const int wave_first_lim = stat_lim[16 * w] > 0 ? stat_lim[16 * w] : 0;      // last row ALL of them see
 
     const _Float16* Kb = static_cast<const _Float16*>(a.K) + (size_t)u * a.C * D;
     const _Float16* Vb = static_cast<const _Float16*>(a.V) + (size_t)u * a.C * D;
 
     half8_t qB[KS];
     {
-        const _Float16* qrow = a.q + (size_t)u * a.unit_stride + (size_t)qc * D + 8 * g;
+        const long qslot = a.ring_w ? (a.t0 + qc) % a.ring_w : qc;
+        const _Float16* qrow = a.q + (size_t)u * a.unit_stride + (size_t)qslot * D + 8 * g;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qB[ks] = *reinterpret_cast<const half8_t*>(qrow + 32 * ks);
     }
@@ -209,12 +260,12 @@ prefill_chunk_kernel(PrefillArgs a) {
     float4_t acc[CB];
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) acc[cb] = float4_t{0.f, 0.f, 0.f, 0.f};
-    fetch(0, true);
+    fetch(0, WITH_PV);
     for (int kt = 0; kt < ntiles; ++kt) {
         __syncthreads();
-        stage(true);
+        stage(WITH_PV);
         __syncthreads();
-        if (kt + 1 < ntiles) fetch(kt + 1, true);
+        if (kt + 1 < ntiles) fetch(kt + 1, WITH_PV);
         if (kt * KB > wave_lim) continue;  // nothing in this tile is visible to this wave
         float4_t d[4];
         scores(Transposed{}, d);
@@ -250,6 +301,7 @@ prefill_chunk_kernel(PrefillArgs a) {
             }
             ph[rb] = __builtin_convertvector(p, half4_t);
         }
+        if constexpr (WITH_PV) {
 #pragma unroll
         for (int kp = 0; kp < 2; ++kp) {
             // The swizzle of the transposed tile decides which of the two 4-row groups of a
@@ -267,13 +319,14 @@ prefill_chunk_kernel(PrefillArgs a) {
                 acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, (swz & 16) ? B10 : B01, acc[cb], 0, 0, 0);
             }
         }
+        }
     }
     const bool pass2 = a.counted || a.probs;
     if (pass2) fetch(0, false);  // in flight while the outputs are written
     lsum += __shfl_xor(lsum, 16);
     lsum += __shfl_xor(lsum, 32);
     const float invL = 1.0f / lsum;
-    if (a.out && qi < a.c) {
+    if (WITH_PV && a.out && valid) {
         _Float16* orow = a.out + (size_t)u * a.out_unit_stride + (size_t)qi * D + 4 * g;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb)
@@ -292,14 +345,18 @@ prefill_chunk_kernel(PrefillArgs a) {
     for (int i = tid; i < ntiles * KB; i += 256) cnt_lds[i] = 0;
     __syncthreads();
     float qm[4], qinv[4], qtau[4];
+    int qlim[4];
     const int qbase = q0 + 16 * w + 4 * g;  // this lane's first query
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         qm[r] = stat_m[16 * w + 4 * g + r];
         qinv[r] = stat_inv[16 * w + 4 * g + r];
-        const long tq = a.thresh_len ? (long)a.n0 + qbase + r + 1 : a.t0 + qbase + r + 1;
-        // a padding query (past the end of the run) never counts: no probability is below -1
-        qtau[r] = qbase + r < a.c ? __fdiv_rn(1.0f, (float)tq) : -1.0f;
+        qlim[r] = stat_lim[16 * w + 4 * g + r];
+        // threshold 1/t (tokens seen at that step) or 1/(rows it sees)
+        const long tq = a.thresh_len ? (long)qlim[r] + 1 : a.t0 + qbase + r + 1;
+        // a padding query (past the end of the run) or one that sees no row never counts: no
+        // probability is below -1
+        qtau[r] = (qbase + r < a.c && qlim[r] >= 0) ? __fdiv_rn(1.0f, (float)tq) : -1.0f;
     }
     float* pbase = a.probs ? a.probs + (size_t)u * a.probs_unit_stride + (size_t)qbase * a.C : nullptr;
     for (int kt = 0; kt < ntiles; ++kt) {
@@ -314,21 +371,20 @@ prefill_chunk_kernel(PrefillArgs a) {
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) {
             const int j = kt * KB + 16 * rb + li;
-            const int rel = j - a.n0 - qbase;  // query r of this lane sees row j iff rel <= r
             float4_t p;
             int cnt = 0;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 p[r] = fast_exp2(fmaf(d[rb][r], c2, -qm[r])) * qinv[r];
                 bool low = p[r] < qtau[r];
-                if (diag) low = low && rel <= r;
+                if (diag) low = low && j <= qlim[r];
                 cnt += low ? 1 : 0;
             }
             if (cnt) atomicAdd(&cnt_lds[j], cnt);
             if (pbase) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    if (qbase + r < a.c && rel <= r) pbase[(size_t)r * a.C + j] = p[r];
+                    if (qbase + r < a.c && j <= qlim[r]) pbase[(size_t)r * a.C + j] = p[r];
             }
         }
     }
@@ -715,14 +771,69 @@ hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t
     a.counted = c.counted;
     a.thresh_len = c.thresh_len;
     a.qk_log2 = c.qk_log2;
+    a.pos = nullptr;
+    a.n_rows = 0;
+    a.ring_w = 0;
     const size_t lds = (size_t)L.C * sizeof(int);
     const unsigned grid = (unsigned)L.U * (unsigned)a.nqb;
     if (i4)
         prefill_chunk_i4_kernel<<<grid, 256, lds, stream>>>(a);
     else if (L.d == 64)
-        prefill_chunk_kernel<64><<<grid, 256, lds, stream>>>(a);
+        prefill_chunk_kernel<64, true><<<grid, 256, lds, stream>>>(a);
     else
-        prefill_chunk_kernel<128><<<grid, 256, lds, stream>>>(a);
+        prefill_chunk_kernel<128, true><<<grid, 256, lds, stream>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_store_queries(const Layout& L, const void* q, long unit_stride, int count, long t0,
+                                hipStream_t stream) {
+    const int row16 = L.d * 2 / 16;
+    const char* src = static_cast<const char*>(q);
+    if (count > L.w) {  // only the last w matter
+        src += (size_t)(count - L.w) * L.d * 2;
+        t0 += count - L.w;
+        count = L.w;
+    }
+    const dim3 grid(L.U, (count * row16 + 255) / 256);
+    store_queries_kernel<<<grid, 256, 0, stream>>>(src, unit_stride * 2, static_cast<char*>(L.Qh), L.w, row16,
+                                                   count, t0);
+    return hipGetLastError();
+}
+
+hipError_t launch_recompute_record(const Layout& L, const ReplayArgs& r, hipStream_t stream) {
+    hipError_t err = launch_clear_counters(L, stream);
+    if (err != hipSuccess) return err;
+    const int W = r.t < (long)L.w ? (int)r.t : L.w;
+    PrefillArgs a;
+    a.q = static_cast<const _Float16*>(L.Qh);
+    a.unit_stride = (long)L.w * L.d;
+    a.K = L.K;
+    a.V = L.V;
+    a.K_meta = nullptr;
+    a.V_meta = nullptr;
+    a.out = nullptr;
+    a.out_unit_stride = 0;
+    a.probs = r.probs;
+    a.probs_unit_stride = (long)W * L.C;
+    a.cnt = L.cnt;
+    a.cnt_unit_stride = (long)L.E * L.C;
+    a.C = L.C;
+    a.n0 = 0;
+    a.c = W;
+    a.nqb = (W + 63) / 64;
+    a.t0 = r.t - W;
+    a.counted = 1;
+    a.thresh_len = r.thresh_len;
+    a.qk_log2 = r.qk_log2;
+    a.pos = L.pos;
+    a.n_rows = r.n;
+    a.ring_w = L.w;
+    const size_t lds = (size_t)L.C * sizeof(int);
+    const unsigned grid = (unsigned)L.U * (unsigned)a.nqb;
+    if (L.d == 64)
+        prefill_chunk_kernel<64, false><<<grid, 256, lds, stream>>>(a);
+    else
+        prefill_chunk_kernel<128, false><<<grid, 256, lds, stream>>>(a);
     return hipGetLastError();
 }
 

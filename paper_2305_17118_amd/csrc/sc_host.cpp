@@ -28,7 +28,8 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct Sizes {
     int32_t n_trig, C, E, W32;
     size_t row_bytes, meta_bytes;  // per K (or V) row
-    size_t off_K, off_V, off_Km, off_Vm, off_pos, off_cnt, off_map, off_first, total;
+    size_t off_K, off_V, off_Km, off_Vm, off_pos, off_cnt, off_qh, off_map, off_first, total;
+    bool recompute;
 };
 
 sc_status derive(const sc_config* cfg, Sizes* s) {
@@ -46,6 +47,9 @@ sc_status derive(const sc_config* cfg, Sizes* s) {
     if (cfg->head_dim != 64 && cfg->head_dim != 128) return SC_ERR_UNSUPPORTED;
     if (cfg->kv_dtype < SC_KV_F32 || cfg->kv_dtype > SC_KV_I4G64) return SC_ERR_UNSUPPORTED;
     if (cfg->window_mode != SC_WINDOW_AUTO && cfg->window_mode != SC_WINDOW_RING) return SC_ERR_INVALID_ARG;
+    if (cfg->record_mode != SC_RECORD_ONLINE && cfg->record_mode != SC_RECORD_RECOMPUTE)
+        return SC_ERR_INVALID_ARG;
+    if (cfg->record_mode == SC_RECORD_RECOMPUTE && cfg->kv_dtype != SC_KV_F16) return SC_ERR_UNSUPPORTED;
     if (cfg->history > 8192) return SC_ERR_UNSUPPORTED;
     const int64_t n_trig =
         cfg->trigger == SC_TRIGGER_HIGH_WATER ? (int64_t)cfg->budget + cfg->drop : (int64_t)cfg->budget + 1;
@@ -53,9 +57,13 @@ sc_status derive(const sc_config* cfg, Sizes* s) {
     if (n_trig > 12288) return SC_ERR_UNSUPPORTED;  // one unit's scores must fit in LDS
     s->n_trig = (int32_t)n_trig;
     s->C = (int32_t)((n_trig + 63) / 64 * 64);
-    const bool ring = cfg->window_mode == SC_WINDOW_RING || cfg->history % cfg->drop != 0;
-    s->E = ring ? 0 : cfg->history / cfg->drop;
+    // Recomputed record: one 16-bit count per slot, rebuilt at every compression; the window
+    // is exact for any w because the kept queries are replayed one by one.
+    s->recompute = cfg->record_mode == SC_RECORD_RECOMPUTE;
+    const bool ring = !s->recompute && (cfg->window_mode == SC_WINDOW_RING || cfg->history % cfg->drop != 0);
+    s->E = s->recompute ? 1 : ring ? 0 : cfg->history / cfg->drop;
     s->W32 = ring ? (cfg->history + 31) / 32 : 0;
+    if (s->recompute && s->C > 6144) return SC_ERR_UNSUPPORTED;  // the replay kernel's LDS budget
     const size_t d = (size_t)cfg->head_dim;
     s->row_bytes = cfg->kv_dtype == SC_KV_F32 ? d * 4 : cfg->kv_dtype == SC_KV_F16 ? d * 2 : d / 2;
     s->meta_bytes = cfg->kv_dtype == SC_KV_I4G64 ? d / 64 * 4 : 0;
@@ -67,6 +75,9 @@ sc_status derive(const sc_config* cfg, Sizes* s) {
     s->off_Vm = off;    off = align_up(off + rows * s->meta_bytes);
     s->off_pos = off;   off = align_up(off + rows * 4);
     s->off_cnt = off;   off = align_up(off + rows * ((size_t)s->E * 2 + (size_t)s->W32 * 4));
+    s->off_qh = off;
+    if (s->recompute)
+        off = align_up(off + (size_t)cfg->batch * cfg->heads * (size_t)cfg->history * d * 2);
     s->off_map = off;   off = align_up(off + rows * 4);
     s->off_first = off; off = align_up(off + (size_t)cfg->batch * cfg->heads * 4);
     s->total = off;
@@ -120,7 +131,11 @@ sc_status step_impl(sc_cache* c, const void* q, const void* k_new, const void* v
     a.probs_stride = (long)probs_stride;
     a.n = n1;
     a.pos_value = (int)(t1 - 1);
-    if (c->L.W32) {
+    if (c->L.Qh) {  // the record is rebuilt at compression time: nothing is counted here
+        a.bucket = 0;
+        a.ring_bit = 0;
+        a.counted = 0;
+    } else if (c->L.W32) {
         const int64_t rho = t1 % c->cfg.history;  // ring bit owned by this step
         a.bucket = (int)(rho >> 5);
         a.ring_bit = 1u << (rho & 31);
@@ -133,20 +148,34 @@ sc_status step_impl(sc_cache* c, const void* q, const void* k_new, const void* v
     }
     a.qk_log2 = c->qk_log2;
     a.tau = c->cfg.thresh_mode == SC_THRESH_INV_LEN ? 1.0f / (float)n1 : 1.0f / (float)t1;
+    // Record rebuilt at compression time: the attention kernel also keeps this step's query
+    // (step t1 in ring slot (t1-1) mod w).
+    a.q_keep = c->L.Qh ? static_cast<char*>(c->L.Qh) +
+                             (size_t)((t1 - 1) % c->cfg.history) * c->cfg.head_dim * elem_bytes(c->cfg)
+                       : nullptr;
     if (sc::launch_decode_step(c->L, a, stream) != hipSuccess) return SC_ERR_DEVICE;
     c->t = t1;
     c->n = n1;
     return SC_OK;
 }
 
-sc_status compress_impl(sc_cache* c, int32_t* evicted_out, hipStream_t stream) {
+sc_status compress_impl(sc_cache* c, int32_t* evicted_out, float* probs_out, hipStream_t stream) {
+    if (c->L.Qh) {  // Alg. 2 as printed: the extra attention computation over the history window
+        sc::ReplayArgs r;
+        r.n = c->n;
+        r.t = (long)c->t;
+        r.thresh_len = c->cfg.thresh_mode == SC_THRESH_INV_LEN;
+        r.qk_log2 = c->qk_log2;
+        r.probs = probs_out;
+        if (sc::launch_recompute_record(c->L, r, stream) != hipSuccess) return SC_ERR_DEVICE;
+    }
     sc::CompressArgs a;
     a.n = c->n;
     a.r = c->cfg.recent;
     a.m = c->cfg.drop;
     // The step that made the cache full closed epoch k; the following steps count into k+1.
     a.zero_bucket = -1;
-    if (c->L.E) {
+    if (c->L.E && !c->L.Qh) {
         const int64_t ep = epoch_of(c->t, c->n_trig, c->cfg.drop);
         a.zero_bucket = bucket_of(ep + 1, c->L.E);
     }
@@ -220,6 +249,8 @@ sc_status sc_cache_create(const sc_config* cfg, void* dev_workspace, size_t byte
     L.V_meta = s.meta_bytes ? base + s.off_Vm : nullptr;
     L.pos = reinterpret_cast<int32_t*>(base + s.off_pos);
     L.cnt = reinterpret_cast<uint16_t*>(base + s.off_cnt);
+    L.Qh = s.recompute ? base + s.off_qh : nullptr;
+    L.w = cfg->history;
     L.srcmap = reinterpret_cast<int32_t*>(base + s.off_map);
     L.first = reinterpret_cast<int32_t*>(base + s.off_first);
     c->n_trig = s.n_trig;
@@ -264,10 +295,10 @@ sc_status sc_decode_step(sc_cache* c, const void* q, const void* k_new, const vo
     return SC_OK;
 }
 
-sc_status sc_compress(sc_cache* c, int32_t* evicted_out, void* stream) {
+sc_status sc_compress(sc_cache* c, int32_t* evicted_out, float* probs_out, void* stream) {
     if (!c) return SC_ERR_INVALID_ARG;
     if (c->n != c->n_trig) return SC_ERR_STATE;
-    return compress_impl(c, evicted_out, static_cast<hipStream_t>(stream));
+    return compress_impl(c, evicted_out, probs_out, static_cast<hipStream_t>(stream));
 }
 
 sc_status sc_prefill(sc_cache* c, const void* q, const void* k, const void* v, int32_t prompt_len,
@@ -308,10 +339,12 @@ sc_status sc_prefill(sc_cache* c, const void* q, const void* k, const void* v, i
             a.c = (int)run;
             a.t0 = (long)c->t;
             a.bucket = bucket_of(ep, c->L.E);
-            a.counted = ep > -(int64_t)c->L.E;
+            a.counted = !c->L.Qh && ep > -(int64_t)c->L.E;
             a.thresh_len = c->cfg.thresh_mode == SC_THRESH_INV_LEN;
             a.qk_log2 = c->qk_log2;
             if (sc::launch_prefill_chunk(c->L, a, s) != hipSuccess) return SC_ERR_DEVICE;
+            if (c->L.Qh && sc::launch_store_queries(c->L, a.q, (long)stride, (int)run, (long)c->t, s) != hipSuccess)
+                return SC_ERR_DEVICE;
             c->t += run;
             c->n += (int32_t)run;
         } else {
@@ -327,7 +360,7 @@ sc_status sc_prefill(sc_cache* c, const void* q, const void* k, const void* v, i
         }
         i += run;
         if (c->n == c->n_trig) {
-            const sc_status st = compress_impl(c, nullptr, s);
+            const sc_status st = compress_impl(c, nullptr, nullptr, s);
             if (st != SC_OK) return st;
         }
     }

@@ -22,6 +22,8 @@ struct Layout {
     void* V_meta;
     int32_t* pos;   // [U][C]
     uint16_t* cnt;  // bucket mode: [U][E][C] uint16; ring mode: the same memory as uint32 [U][W32][C]
+    void* Qh;       // record recomputed at compression time: ring of the last w queries [U][w][d], else null
+    int w;          // history window in steps
     int32_t* srcmap;  // [U][C] scratch written by select, read by compact
     int32_t* first;   // [U] scratch: first slot whose row moves
 };
@@ -42,6 +44,8 @@ struct StepArgs {
     uint32_t ring_bit;  // ring mode: mask of this step's bit inside its word
     float qk_log2;    // score scale * log2(e)
     float tau;        // low-score threshold
+    void* q_keep;     // ring slot of this step for unit 0 (units are w*d elements apart), or null;
+                      // honoured by the fp32/fp16 kernels (the only storage the replay supports)
 };
 
 // One launch on `stream`: append the new row and attend.
@@ -85,6 +89,23 @@ inline bool prefill_chunk_supported(int kv_dtype, int d, int E, int C) {
 
 // Two launches on `stream`: append the run's rows, then attention + counting.
 hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& a, hipStream_t stream);
+
+// Keep the queries of `count` consecutive steps, the first being step t0+1, in the ring
+// L.Qh (step i goes to slot (i-1) mod w).  q points at the first of them for unit 0; rows
+// are d elements apart, units unit_stride elements.
+hipError_t launch_store_queries(const Layout& L, const void* q, long unit_stride, int count, long t0,
+                                hipStream_t stream);
+
+// Alg. 2 as printed: rebuild the record (16-bit counts in L.cnt, cleared first) by replaying
+// the kept queries of steps (t - min(w,t), t] over the n resident rows.
+struct ReplayArgs {
+    int n;
+    long t;
+    int thresh_len;
+    float qk_log2;
+    float* probs;  // [U][min(w,t)][C] or null
+};
+hipError_t launch_recompute_record(const Layout& L, const ReplayArgs& a, hipStream_t stream);
 
 // Zero all counters (cache creation).
 hipError_t launch_clear_counters(const Layout& L, hipStream_t stream);

@@ -37,17 +37,19 @@ class ParityRun:
 
     def __init__(self, wl: Workload, sel=None, trigger=B.SC_TRIGGER_HARD_CAP,
                  thresh=B.SC_THRESH_INV_POS, scale=0.0, steps=None, device="cuda:0", qkv=None,
-                 window_mode=B.SC_WINDOW_AUTO):
+                 window_mode=B.SC_WINDOW_AUTO, record_mode=B.SC_RECORD_ONLINE):
         self.wl = wl
         self.dev = torch.device(device)
         self.U = wl.units
         self.sel = list(range(self.U)) if sel is None else list(sel)
         self.T = wl.total if steps is None else steps
         self.cfg = B.make_config(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.budget, wl.recent,
-                                 wl.history, wl.drop, trigger, thresh, scale, window_mode)
+                                 wl.history, wl.drop, trigger, thresh, scale, window_mode, record_mode)
+        self.recompute = record_mode == B.SC_RECORD_RECOMPUTE
         self.cache = B.BudgetCache(self.cfg, device)
         self.oracle = Oracle(OracleConfig(1, len(self.sel), wl.head_dim, wl.kv_dtype, wl.budget,
-                                          wl.recent, wl.history, wl.drop, trigger, thresh, scale))
+                                          wl.recent, wl.history, wl.drop, trigger, thresh, scale,
+                                          record_mode))
         q, k, v = qkv if qkv is not None else streams(wl, steps=self.T, threads=16)
         self.hq, self.hk, self.hv = (np.ascontiguousarray(a[self.sel]) for a in (q, k, v))
         self.q, self.k, self.v = (torch.from_numpy(a).to(self.dev) for a in (q, k, v))
@@ -119,6 +121,7 @@ class ParityRun:
             self._compare(o_all[:, s], o_ref, p_gpu, p_ref[:, :n], s)
             self.stats["steps"] += 1
             if due:
+                assert not self.recompute, "prefill parity with a recomputed record: step instead"
                 self.oracle.compress()
                 self.stats["compressions"] += 1
         self.step_idx = P
@@ -136,7 +139,36 @@ class ParityRun:
         cnt = self.cache.cnt().index_select(0, self.sel_t)[:, :, :n].to(torch.int32) & 0xFFFF
         return cnt.sum(dim=1).cpu().numpy()
 
+    def compress_recompute(self, check_rows=True):
+        """Record mode "recompute": the GPU replays the kept queries inside sc_compress and
+        dumps the probabilities its thresholds saw; the oracle replays the same steps with
+        those probabilities forced, so the evicted slots must agree bit for bit, and its own
+        (double precision) replayed probabilities are compared within tolerance."""
+        n, t = self.cache.n, self.cache.t
+        W = min(self.wl.history, t)
+        probs = torch.zeros(self.U, W, self.cache.capacity, dtype=torch.float32, device=self.dev)
+        self.evicted.fill_(-1)
+        self.cache.compress(self.evicted, probs)
+        p_gpu = probs.index_select(0, self.sel_t)[:, :, :n].cpu().numpy()
+        ev_ref, p_ref, rec = self.oracle.compress_recompute(p_forced=p_gpu)
+        p_ref = p_ref[:, :, :n]
+        assert np.all(np.isfinite(p_gpu))
+        seen = p_ref.sum(axis=2) > 0.5  # replayed steps that see at least one resident row
+        sum_err = np.abs(p_gpu.astype(np.float64).sum(axis=2) - 1.0)[seen].max()
+        assert sum_err <= 1e-5, "replayed probabilities sum off by %g" % sum_err
+        assert np.all(p_gpu[~seen] == 0.0)
+        dp = np.abs(p_gpu - p_ref).max(axis=2)
+        lim = self.tol * p_ref.max(axis=2) if self.wl.kv_dtype != B.SC_KV_F32 else 1e-5
+        assert np.all(dp <= lim), "replayed probability error %g" % dp.max()
+        ev_gpu = self.evicted.index_select(0, self.sel_t).cpu().numpy()
+        assert np.array_equal(ev_gpu, ev_ref), "evicted slots differ"
+        self.check_state(check_rows)
+        self.stats["compressions"] += 1
+        self.stats["max_dp"] = max(self.stats["max_dp"], float(dp.max()))
+
     def compress(self, check_rows=True):
+        if self.recompute:
+            return self.compress_recompute(check_rows)
         I_gpu = self.gpu_record()
         I_ref = self.oracle.importance()
         assert np.array_equal(I_gpu, I_ref), "importance records differ before compression %d" % (

@@ -232,6 +232,37 @@ def test_dense_and_streamed_prefill_agree():
     assert err.median().item() < 2e-3
 
 
+RECOMPUTE = [
+    # name, batch, heads, d, kv, prompt, decode, B, r, w, m, heavy
+    _wl("re-d128", 1, 4, 128, KV_F16, 150, 100, 100, 7, 32, 16, 0.05),
+    _wl("re-d64", 2, 2, 64, KV_F16, 120, 60, 50, 4, 20, 10),
+    _wl("re-paper-params", 1, 3, 128, KV_F16, 300, 400, 200, 10, 400, 100, 0.05),  # w = 400: 7 query blocks
+    _wl("re-window-longer-than-cache", 1, 2, 128, KV_F16, 90, 80, 20, 2, 64, 8),   # old steps see few rows
+    _wl("re-drop-one", 1, 2, 64, KV_F16, 40, 30, 24, 1, 5, 1),
+]
+
+
+@pytest.mark.parametrize("wl", RECOMPUTE, ids=lambda w: w.name)
+@pytest.mark.parametrize("thresh", [B.SC_THRESH_INV_POS, B.SC_THRESH_INV_LEN], ids=["inv-t", "inv-n"])
+def test_recomputed_record_matches_oracle(wl, thresh):
+    """Alg. 2 as printed: no counting during the steps; at every compression the last w
+    queries are replayed over the resident rows.  Steps are compared as always; at each
+    compression the replayed probabilities are compared and the evicted slots must agree."""
+    run = ParityRun(wl, thresh=thresh, record_mode=B.SC_RECORD_RECOMPUTE)
+    st = run.run()
+    assert st["steps"] == wl.total and st["compressions"] >= 3
+
+
+def test_recomputed_record_after_dense_prefill():
+    """The queries of a prompt that went through sc_prefill are kept too: the compressions
+    during the decode steps that follow replay them."""
+    wl = _wl("re-prefill", 1, 4, 128, KV_F16, 90, 120, 100, 8, 64, 32, 0.05)  # prompt ends before the trigger
+    run = ParityRun(wl, record_mode=B.SC_RECORD_RECOMPUTE)
+    run.prefill(wl.prompt)
+    st = run.run()
+    assert st["compressions"] >= 3
+
+
 def test_error_codes_leave_state_untouched():
     wl = _wl("errors", 1, 2, 64, KV_F32, 0, 0, 8, 2, 4, 4)
     cfg = B.make_config(1, 2, 64, KV_F32, 8, 2, 4, 4)

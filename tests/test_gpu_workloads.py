@@ -61,3 +61,14 @@ def test_dense_prefill_at_full_size(idx, extra, decode):
     st = run.run(check_rows_every=2)
     print(st, flush=True)
     assert st["steps"] == wl.total
+
+
+def test_recomputed_record_at_full_size():
+    """Alg. 2 as printed on the headline shape: records rebuilt at compression time from the
+    last 256 queries (dense prefill of the prompt, then 300 decode steps, three compressions)."""
+    wl = CONFIGS[1].scaled(decode=300)
+    run = ParityRun(wl, sel=_sample(wl, 8), record_mode=B.SC_RECORD_RECOMPUTE)
+    run.prefill(wl.prompt)
+    st = run.run(check_rows_every=2)
+    print(st, flush=True)
+    assert st["compressions"] == 3

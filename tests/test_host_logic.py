@@ -202,3 +202,22 @@ def test_prefill_plan_rejects_bad_arguments():
     with pytest.raises(B.ScError) as e:
         B.sc_prefill_plan(cfg, 10, 7)
     assert e.value.status == B.SC_ERR_INVALID_ARG
+
+
+def test_recomputed_record_configuration():
+    """Record rebuilt at compression time: one 16-bit count per slot, a ring of w queries in the
+    workspace, any w (no bucket constraint), fp16 storage only."""
+    cfg = _cfg(record_mode=B.SC_RECORD_RECOMPUTE, history=37)
+    n_trig, cap, E, W32 = B.sc_config_sizes(cfg)
+    assert (E, W32) == (1, 0)
+    online = _cfg(history=32)  # E = 2
+    extra = B.sc_workspace_bytes(cfg) - B.sc_workspace_bytes(online)
+    U = 8
+    assert abs(extra - (U * 37 * 128 * 2 - U * cap * 2)) <= 4 * 256
+    for kv in (B.SC_KV_F32, B.SC_KV_I4G64):
+        with pytest.raises(B.ScError) as e:
+            B.sc_config_sizes(_cfg(record_mode=B.SC_RECORD_RECOMPUTE, kv_dtype=kv))
+        assert e.value.status == B.SC_ERR_UNSUPPORTED
+    with pytest.raises(B.ScError) as e:
+        B.sc_config_sizes(_cfg(record_mode=3))
+    assert e.value.status == B.SC_ERR_INVALID_ARG
