@@ -30,23 +30,6 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Copy the run's key/value rows into slots n0.. of every unit and record their positions.
-// grid (U, pieces/256): one 16-byte piece of a K row and of a V row per thread.
-__global__ void __launch_bounds__(256)
-append_rows_kernel(const char* __restrict__ k, const char* __restrict__ v, long unit_stride_bytes,
-                   char* __restrict__ K, char* __restrict__ V, int32_t* __restrict__ pos, int C,
-                   int row16, int n0, int c, int t0) {
-    const int u = blockIdx.x;
-    const int e = blockIdx.y * 256 + threadIdx.x;
-    if (e >= c * row16) return;
-    const int row = e / row16;
-    const size_t src = (size_t)u * unit_stride_bytes + (size_t)e * 16;
-    const size_t dst = ((size_t)u * C + n0) * row16 * 16 + (size_t)e * 16;
-    *reinterpret_cast<uint4*>(K + dst) = *reinterpret_cast<const uint4*>(k + src);
-    *reinterpret_cast<uint4*>(V + dst) = *reinterpret_cast<const uint4*>(v + src);
-    if (e - row * row16 == 0) pos[(size_t)u * C + n0 + row] = t0 + row;
-}
-
 // grid (U, pieces/256): one 16-byte piece of a query row per thread; step t0+1+row goes to
 // ring slot (t0 + row) mod w.  count <= w, so no two rows share a slot.
 __global__ void __launch_bounds__(256)
@@ -83,6 +66,12 @@ struct PrefillArgs {
     const int32_t* pos;
     int n_rows;
     int ring_w;
+    // Prompt run with the row copy fused in (fp16): the run's key/value rows as handed in
+    // (unit 0; units are unit_stride elements apart) and where their positions go; null
+    // when the rows are already in their slots.
+    const _Float16* k_run;
+    const _Float16* v_run;
+    int32_t* pos_w;
 };
 
 // Matrix-instruction operand layout (16x16x32, fp16 in, fp32 out), lane l, i = l%16, g = l/16:
@@ -93,7 +82,7 @@ struct PrefillArgs {
 // out^T = V^T P^T, whose contraction index (lane group g, element e) stands for cache row
 // 4g + e of one 16-row block (e < 4) or of the next one (e >= 4).  V is staged transposed in
 // LDS so that its A operand is two 8-byte reads.
-// At least two waves per SIMD: the register budget that goes with it (256) also makes the
+// At least three waves per SIMD: the register budget that goes with it (168) also makes the
 // compiler keep the matrix accumulators in ordinary vector registers, where the running-softmax
 // rescale can reach them without copies.
 //
@@ -104,7 +93,7 @@ struct PrefillArgs {
 // rows' stream positions (rows are kept in order of position): the last one with
 // position <= i-1.
 template <int D, bool WITH_PV>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3)))
 prefill_chunk_kernel(PrefillArgs a) {
     constexpr int KB = 64;        // cache rows per tile
     constexpr int QB = 64;        // queries per workgroup (16 per wave)
@@ -121,8 +110,39 @@ prefill_chunk_kernel(PrefillArgs a) {
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int li = lane & 15, g = lane >> 4;
-    const int u = blockIdx.x / a.nqb;
-    const int q0 = (a.nqb - 1 - (int)(blockIdx.x % a.nqb)) * QB;  // longest query blocks first
+    // With the row copy fused in, the second half of the grid copies the run's rows into their
+    // slots, 64 rows per workgroup (Alg. 1 "model update"), while the first half attends; the
+    // attending workgroups read the run's rows from where the caller handed them in, so the
+    // two halves never depend on each other.  (Copiers dispatched last was the fastest order
+    // measured; interleaving them with the attending workgroups was 40% slower.)
+    const bool fused = a.k_run != nullptr;
+    unsigned blk = blockIdx.x;
+    if (fused) {
+        const bool copier = blk >= gridDim.x / 2;
+        if (copier) blk -= gridDim.x / 2;
+        if (copier) {
+            const int cu = blk / a.nqb, slab = (int)(blk % a.nqb) * QB;
+            const size_t src = (size_t)cu * a.unit_stride + (size_t)slab * D;
+            const size_t dst = ((size_t)cu * a.C + a.n0 + slab) * D;
+            _Float16* Kw = const_cast<_Float16*>(static_cast<const _Float16*>(a.K));
+            _Float16* Vw = const_cast<_Float16*>(static_cast<const _Float16*>(a.V));
+#pragma unroll
+            for (int x = 0; x < PIECES; ++x) {
+                const int idx = tid + 256 * x;
+                const int row = idx / (D / 8);
+                if (slab + row < a.c) {
+                    *reinterpret_cast<uint4*>(Kw + dst + (size_t)idx * 8) =
+                        *reinterpret_cast<const uint4*>(a.k_run + src + (size_t)idx * 8);
+                    *reinterpret_cast<uint4*>(Vw + dst + (size_t)idx * 8) =
+                        *reinterpret_cast<const uint4*>(a.v_run + src + (size_t)idx * 8);
+                    if (idx % (D / 8) == 0) a.pos_w[(size_t)cu * a.C + a.n0 + slab + row] = (int)a.t0 + slab + row;
+                }
+            }
+            return;
+        }
+    }
+    const int u = blk / a.nqb;
+    const int q0 = (a.nqb - 1 - (int)(blk % a.nqb)) * QB;  // longest query blocks first
     const int qi = q0 + 16 * w + li;                 // this lane's query (position in the run)
     const int qc = qi < a.c ? qi : a.c - 1;          // clamped: padding lanes shadow the last query
     const int q_last = (q0 + QB < a.c ? q0 + QB : a.c) - 1;
@@ -157,6 +177,9 @@ prefill_chunk_kernel(PrefillArgs a) {
 
     const _Float16* Kb = static_cast<const _Float16*>(a.K) + (size_t)u * a.C * D;
     const _Float16* Vb = static_cast<const _Float16*>(a.V) + (size_t)u * a.C * D;
+    // rows n0.. of a fused run are read from the caller's arrays
+    const _Float16* Krun = fused ? a.k_run + (size_t)u * a.unit_stride : nullptr;
+    const _Float16* Vrun = fused ? a.v_run + (size_t)u * a.unit_stride : nullptr;
 
     half8_t qB[KS];
     {
@@ -179,9 +202,13 @@ prefill_chunk_kernel(PrefillArgs a) {
     const uint32_t koff = (uint32_t)(prow_k * D + pcb8 * 8) * 2u;       // bytes inside a tile
     const uint32_t voff = (uint32_t)(2 * prow_k * D + pcb8 * 8) * 2u;
     auto fetch = [&](int kt, bool with_v) {
-        const char* kt_base = reinterpret_cast<const char*>(Kb) + (size_t)kt * KB * D * 2;
-        const char* vt_base = reinterpret_cast<const char*>(Vb) + (size_t)kt * KB * D * 2;
-        if (kt * KB + KB <= hi) {  // whole tile holds data
+        const int r0 = kt * KB;
+        const bool in_cache = !fused || r0 + KB <= a.n0, in_run = fused && r0 >= a.n0;
+        if (r0 + KB <= hi && (in_cache || in_run)) {  // a whole tile of data from one array
+            const char* kt_base = in_cache ? reinterpret_cast<const char*>(Kb) + (size_t)r0 * D * 2
+                                           : reinterpret_cast<const char*>(Krun) + (size_t)(r0 - a.n0) * D * 2;
+            const char* vt_base = in_cache ? reinterpret_cast<const char*>(Vb) + (size_t)r0 * D * 2
+                                           : reinterpret_cast<const char*>(Vrun) + (size_t)(r0 - a.n0) * D * 2;
 #pragma unroll
             for (int x = 0; x < PIECES; ++x)
                 kreg[x] = *reinterpret_cast<const u32x4_t*>(kt_base + koff + (uint32_t)(x * RPP * D * 2));
@@ -193,23 +220,24 @@ prefill_chunk_kernel(PrefillArgs a) {
                         vreg[2 * x + h] = *reinterpret_cast<const half8_t*>(
                             vt_base + voff + (uint32_t)((2 * x * RPP + h) * D * 2));
             }
-        } else {  // last tile: rows past the data are read from the last row that holds some
-            const int last = hi - 1 - kt * KB;
+        } else {
+            // Last tile (rows past the data are read from the last row that holds some) or a
+            // tile that straddles the boundary between resident rows and the run's own.
+            auto row_of = [&](const _Float16* cache, const _Float16* run, int row) {
+                int grow = r0 + row;
+                grow = grow < hi ? grow : hi - 1;
+                return (!fused || grow < a.n0) ? cache + (size_t)grow * D : run + (size_t)(grow - a.n0) * D;
+            };
 #pragma unroll
-            for (int x = 0; x < PIECES; ++x) {
-                const int row = prow_k + x * RPP;
-                kreg[x] = *reinterpret_cast<const u32x4_t*>(
-                    kt_base + (uint32_t)(((row < last ? row : last) * D + pcb8 * 8) * 2));
-            }
+            for (int x = 0; x < PIECES; ++x)
+                kreg[x] = *reinterpret_cast<const u32x4_t*>(row_of(Kb, Krun, prow_k + x * RPP) + pcb8 * 8);
             if (with_v) {
 #pragma unroll
                 for (int x = 0; x < PIECES / 2; ++x)
 #pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const int row = 2 * (prow_k + x * RPP) + h;
+                    for (int h = 0; h < 2; ++h)
                         vreg[2 * x + h] = *reinterpret_cast<const half8_t*>(
-                            vt_base + (uint32_t)(((row < last ? row : last) * D + pcb8 * 8) * 2));
-                    }
+                            row_of(Vb, Vrun, 2 * (prow_k + x * RPP) + h) + pcb8 * 8);
             }
         }
     };
@@ -741,12 +769,6 @@ hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t
             static_cast<unsigned char*>(L.K), static_cast<unsigned char*>(L.V),
             static_cast<uint32_t*>(L.K_meta), static_cast<uint32_t*>(L.V_meta), L.pos, L.C, c.n0, c.c,
             (int)c.t0);
-    } else {
-        const int row16 = L.d * 2 / 16;
-        const dim3 grid_a(L.U, (c.c * row16 + 255) / 256);
-        append_rows_kernel<<<grid_a, 256, 0, stream>>>(
-            static_cast<const char*>(c.k), static_cast<const char*>(c.v), c.unit_stride * 2,
-            static_cast<char*>(L.K), static_cast<char*>(L.V), L.pos, L.C, row16, c.n0, c.c, (int)c.t0);
     }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
@@ -774,14 +796,18 @@ hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t
     a.pos = nullptr;
     a.n_rows = 0;
     a.ring_w = 0;
+    // fp16: the copy of the run's rows into their slots rides in the same launch
+    a.k_run = i4 ? nullptr : static_cast<const _Float16*>(c.k);
+    a.v_run = i4 ? nullptr : static_cast<const _Float16*>(c.v);
+    a.pos_w = L.pos;
     const size_t lds = (size_t)L.C * sizeof(int);
     const unsigned grid = (unsigned)L.U * (unsigned)a.nqb;
     if (i4)
         prefill_chunk_i4_kernel<<<grid, 256, lds, stream>>>(a);
     else if (L.d == 64)
-        prefill_chunk_kernel<64, true><<<grid, 256, lds, stream>>>(a);
+        prefill_chunk_kernel<64, true><<<2 * grid, 256, lds, stream>>>(a);
     else
-        prefill_chunk_kernel<128, true><<<grid, 256, lds, stream>>>(a);
+        prefill_chunk_kernel<128, true><<<2 * grid, 256, lds, stream>>>(a);
     return hipGetLastError();
 }
 
@@ -828,6 +854,9 @@ hipError_t launch_recompute_record(const Layout& L, const ReplayArgs& r, hipStre
     a.pos = L.pos;
     a.n_rows = r.n;
     a.ring_w = L.w;
+    a.k_run = nullptr;
+    a.v_run = nullptr;
+    a.pos_w = nullptr;
     const size_t lds = (size_t)L.C * sizeof(int);
     const unsigned grid = (unsigned)L.U * (unsigned)a.nqb;
     if (L.d == 64)
