@@ -4,13 +4,17 @@
 A "step" is one pass of the whole hot path over one batch: sc_decode_step (append + budgeted
 attention + importance-record update, one kernel) followed by sc_compress whenever the cache
 has reached its trigger size.  The workload is the OPT-6.7B-shaped single layer (batch 16,
-32 heads, head_dim 128, fp16, 1024-token prompt streamed through the cache, then decoding
+32 heads, head_dim 128, fp16, 1024-token prompt put through sc_prefill, then decoding
 under budget 1024).  Because one layer's cache (269 MB) is about the size of the chip's
 last-level cache and is re-read every step, R independent cache instances are stepped
 round-robin (as the layers of a model would be), so every step finds its cache cold in HBM.
 tokens/s = batch * steps / wall time, a step being one layer-instance step.
 
-Prints ONE JSON line (see the design doc for the field definitions).
+Prints ONE JSON line: metric / value / unit (whole-job decode tokens/s, inputs resident in
+HBM), ms_per_step, config (the workload), roofline (algorithmic bytes per decode-attention
+launch / its average duration from HIP events on the launch stream, against the 8 TB/s HBM
+peak; traffic = HBM bytes per launch from rocprofv3 counters where measured) and cpu_baseline
+(the CPU oracle timed on the host cores on the same decode phase).
 """
 from __future__ import annotations
 

@@ -21,8 +21,7 @@
  *             largest I are dropped (equal I: the lowest slot goes first), survivors
  *             keep their order, n <- n-m.
  *
- * Readings taken where the paper is silent or inconsistent (each is listed in the
- * design document of this repository):
+ * Readings taken where the paper is silent or inconsistent:
  *   - score = scale * <q, k_j>, q/k/v handed in by the caller, scale defaults to
  *     1/sqrt(head_dim); the sum runs over every resident row including the row
  *     appended at this step (Sec. 4.1 sums i = 1..t).
