@@ -263,6 +263,58 @@ def test_recomputed_record_after_dense_prefill():
     assert st["compressions"] >= 3
 
 
+@pytest.mark.parametrize("kv", [KV_F16, KV_I4G64], ids=["f16", "i4"])
+def test_dense_prefill_production_path_and_reset(kv):
+    """The dumps are optional: a call without `out` and `probs_out` (the second pass then only
+    counts), a call on strided inputs, and a call on a cache that was used and reset must all
+    leave exactly the state of the fully instrumented call."""
+    wl = _wl("pf-prod", 2, 3, 128, kv, 300, 0, 100, 8, 64, 32, 0.05)
+    T, d, U = wl.total, wl.head_dim, wl.units
+    q, k, v = (torch.from_numpy(a).cuda() for a in streams(wl))
+    cfg = B.make_config(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.budget, wl.recent, wl.history,
+                        wl.drop)
+
+    def state(c):
+        n = c.n
+        K, V = c.kv_rows()
+        out = [c.pos()[:, :n].clone(), c.cnt().clone(), K[:, :n].clone(), V[:, :n].clone()]
+        if kv == KV_I4G64:
+            Km, Vm = c.kv_meta()
+            out += [Km[:, :n].clone(), Vm[:, :n].clone()]
+        return (n, c.t), out
+
+    full = B.BudgetCache(cfg)
+    out = torch.empty(U, T, d, dtype=torch.float16, device="cuda")
+    probs = torch.zeros(U, T, full.capacity, dtype=torch.float32, device="cuda")
+    full.prefill(q, k, v, T, 0, out, probs)
+    ref = state(full)
+
+    def same(c):
+        got = state(c)
+        return got[0] == ref[0] and all(torch.equal(a, b) for a, b in zip(got[1], ref[1]))
+
+    bare = B.BudgetCache(cfg)
+    bare.prefill(q, k, v, T)
+    assert same(bare)
+    pad = torch.zeros(U, 8, d, dtype=torch.float16, device="cuda")
+    qq, kk, vv = (torch.cat([x, pad], dim=1).contiguous() for x in (q, k, v))
+    strided = B.BudgetCache(cfg)
+    out2 = torch.empty_like(out)
+    strided.prefill(qq, kk, vv, T, (T + 8) * d, out2)
+    assert same(strided) and torch.equal(out2, out)
+    # a used cache, reset: counters, lengths and schedule start over
+    bare.reset()
+    assert (bare.n, bare.t) == (0, 0)
+    bare.prefill(q, k, v, T, 0, out2)
+    assert same(bare) and torch.equal(out2, out)
+    with pytest.raises(B.ScError) as e:
+        bare.prefill(q, k, v, T)  # not empty any more
+    assert e.value.status == B.SC_ERR_STATE
+    with pytest.raises(B.ScError) as e:
+        B.BudgetCache(cfg).prefill(q, k, v, T, mode=5)
+    assert e.value.status == B.SC_ERR_INVALID_ARG
+
+
 def test_error_codes_leave_state_untouched():
     wl = _wl("errors", 1, 2, 64, KV_F32, 0, 0, 8, 2, 4, 4)
     cfg = B.make_config(1, 2, 64, KV_F32, 8, 2, 4, 4)
