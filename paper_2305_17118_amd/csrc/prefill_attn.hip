@@ -92,11 +92,16 @@ struct PrefillArgs {
 // from a ring (step i in slot (i-1) mod w) and the last row step i may see is found from the
 // rows' stream positions (rows are kept in order of position): the last one with
 // position <= i-1.
-template <int D, bool WITH_PV>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3)))
+//
+// SB = blocks of 16 queries per wave.  With SB = 2 every K and V fragment read from LDS feeds
+// two matrix instructions (LDS operand traffic, the busiest resource of this kernel, is halved
+// per query) at the price of twice the accumulators, i.e. two instead of three waves per SIMD.
+template <int D, bool WITH_PV, int SB>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SB == 1 ? 3 : 2)))
 prefill_chunk_kernel(PrefillArgs a) {
     constexpr int KB = 64;        // cache rows per tile
-    constexpr int QB = 64;        // queries per workgroup (16 per wave)
+    constexpr int WQ = 16 * SB;   // queries per wave
+    constexpr int QB = 4 * WQ;    // queries per workgroup
     constexpr int LDK = D + 8;    // halfs per staged K row (padding keeps 16-byte reads conflict-free)
     constexpr int LDV = KB + 4;   // halfs per channel of the transposed V tile
     constexpr int KS = D / 32;    // matrix instructions per 16 scores
@@ -110,41 +115,21 @@ prefill_chunk_kernel(PrefillArgs a) {
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int li = lane & 15, g = lane >> 4;
-    // With the row copy fused in, the second half of the grid copies the run's rows into their
-    // slots, 64 rows per workgroup (Alg. 1 "model update"), while the first half attends; the
-    // attending workgroups read the run's rows from where the caller handed them in, so the
-    // two halves never depend on each other.  (Copiers dispatched last was the fastest order
-    // measured; interleaving them with the attending workgroups was 40% slower.)
+    // A prompt run handed in with its rows still in the caller's arrays (k_run): every
+    // workgroup reads the run's rows from there, and the workgroup of the last query block,
+    // which sees all of them, also writes them into their slots as they pass through its
+    // registers (Alg. 1 "model update"): no separate copy pass, no second read.
     const bool fused = a.k_run != nullptr;
-    unsigned blk = blockIdx.x;
-    if (fused) {
-        const bool copier = blk >= gridDim.x / 2;
-        if (copier) blk -= gridDim.x / 2;
-        if (copier) {
-            const int cu = blk / a.nqb, slab = (int)(blk % a.nqb) * QB;
-            const size_t src = (size_t)cu * a.unit_stride + (size_t)slab * D;
-            const size_t dst = ((size_t)cu * a.C + a.n0 + slab) * D;
-            _Float16* Kw = const_cast<_Float16*>(static_cast<const _Float16*>(a.K));
-            _Float16* Vw = const_cast<_Float16*>(static_cast<const _Float16*>(a.V));
-#pragma unroll
-            for (int x = 0; x < PIECES; ++x) {
-                const int idx = tid + 256 * x;
-                const int row = idx / (D / 8);
-                if (slab + row < a.c) {
-                    *reinterpret_cast<uint4*>(Kw + dst + (size_t)idx * 8) =
-                        *reinterpret_cast<const uint4*>(a.k_run + src + (size_t)idx * 8);
-                    *reinterpret_cast<uint4*>(Vw + dst + (size_t)idx * 8) =
-                        *reinterpret_cast<const uint4*>(a.v_run + src + (size_t)idx * 8);
-                    if (idx % (D / 8) == 0) a.pos_w[(size_t)cu * a.C + a.n0 + slab + row] = (int)a.t0 + slab + row;
-                }
-            }
-            return;
-        }
-    }
+    const unsigned blk = blockIdx.x;
     const int u = blk / a.nqb;
     const int q0 = (a.nqb - 1 - (int)(blk % a.nqb)) * QB;  // longest query blocks first
-    const int qi = q0 + 16 * w + li;                 // this lane's query (position in the run)
-    const int qc = qi < a.c ? qi : a.c - 1;          // clamped: padding lanes shadow the last query
+    const bool writer = fused && blk % a.nqb == 0;
+    int qi[SB], qc[SB];  // this lane's queries (positions in the run); padding lanes shadow the last one
+#pragma unroll
+    for (int sb = 0; sb < SB; ++sb) {
+        qi[sb] = q0 + WQ * w + 16 * sb + li;
+        qc[sb] = qi[sb] < a.c ? qi[sb] : a.c - 1;
+    }
     const int q_last = (q0 + QB < a.c ? q0 + QB : a.c) - 1;
     // Last cache row each of the workgroup's queries sees.  Prompt run: n0 + query index.
     // Replay: rows with position <= t0 + query index (binary search over the positions, staged
@@ -167,13 +152,19 @@ prefill_chunk_kernel(PrefillArgs a) {
         stat_lim[tid] = a.n0 + (q0 + tid < a.c ? q0 + tid : a.c - 1);
     }
     __syncthreads();
-    const int lim_raw = stat_lim[16 * w + li];
-    const bool valid = qi < a.c && lim_raw >= 0;     // a real query that sees at least one row
-    const int lim = lim_raw > 0 ? lim_raw : 0;       // (a query that sees nothing shadows row 0, never stored)
+    bool valid[SB];  // a real query that sees at least one row
+    int lim[SB];     // last row it sees (a query that sees nothing shadows row 0, never stored)
+    int sub_first_lim[SB];  // last row ALL queries of the 16-block see
+#pragma unroll
+    for (int sb = 0; sb < SB; ++sb) {
+        const int lim_raw = stat_lim[WQ * w + 16 * sb + li];
+        valid[sb] = qi[sb] < a.c && lim_raw >= 0;
+        lim[sb] = lim_raw > 0 ? lim_raw : 0;
+        sub_first_lim[sb] = stat_lim[WQ * w + 16 * sb] > 0 ? stat_lim[WQ * w + 16 * sb] : 0;
+    }
     const int hi = (stat_lim[q_last - q0] > 0 ? stat_lim[q_last - q0] : 0) + 1;  // rows visible to this workgroup
     const int ntiles = (hi + KB - 1) / KB;
-    const int wave_lim = stat_lim[16 * w + 15] > 0 ? stat_lim[16 * w + 15] : 0;  // last row any query of the wave sees
-    const int wave_first_lim = stat_lim[16 * w] > 0 ? stat_lim[16 * w] : 0;      // last row ALL of them see
+    const int wave_lim = stat_lim[WQ * w + WQ - 1] > 0 ? stat_lim[WQ * w + WQ - 1] : 0;  // last row any query of the wave sees
 
     const _Float16* Kb = static_cast<const _Float16*>(a.K) + (size_t)u * a.C * D;
     const _Float16* Vb = static_cast<const _Float16*>(a.V) + (size_t)u * a.C * D;
@@ -181,12 +172,13 @@ prefill_chunk_kernel(PrefillArgs a) {
     const _Float16* Krun = fused ? a.k_run + (size_t)u * a.unit_stride : nullptr;
     const _Float16* Vrun = fused ? a.v_run + (size_t)u * a.unit_stride : nullptr;
 
-    half8_t qB[KS];
-    {
-        const long qslot = a.ring_w ? (a.t0 + qc) % a.ring_w : qc;
+    half8_t qB[SB][KS];
+#pragma unroll
+    for (int sb = 0; sb < SB; ++sb) {
+        const long qslot = a.ring_w ? (a.t0 + qc[sb]) % a.ring_w : qc[sb];
         const _Float16* qrow = a.q + (size_t)u * a.unit_stride + (size_t)qslot * D + 8 * g;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qB[ks] = *reinterpret_cast<const half8_t*>(qrow + 32 * ks);
+        for (int ks = 0; ks < KS; ++ks) qB[sb][ks] = *reinterpret_cast<const half8_t*>(qrow + 32 * ks);
     }
 
     // A tile travels global -> registers -> LDS; the loads of tile kt+1 are issued before
@@ -241,13 +233,30 @@ prefill_chunk_kernel(PrefillArgs a) {
             }
         }
     };
-    auto stage = [&](bool with_v) {
+    _Float16* Kw = const_cast<_Float16*>(Kb);
+    _Float16* Vw = const_cast<_Float16*>(Vb);
+    auto stage = [&](bool with_v, int kt) {
+        const int r0 = kt * KB;
+        // the writer keeps the run's rows (slots n0 .. n0+c-1) as they come by, in pass 1
+        const bool keep = writer && with_v && r0 + KB > a.n0;
 #pragma unroll
-        for (int x = 0; x < PIECES; ++x)
+        for (int x = 0; x < PIECES; ++x) {
             *reinterpret_cast<u32x4_t*>(&Ks[(prow_k + x * RPP) * LDK + pcb8 * 8]) = kreg[x];
+            const int grow = r0 + prow_k + x * RPP;
+            if (keep && grow >= a.n0 && grow < hi) {
+                *reinterpret_cast<u32x4_t*>(Kw + (size_t)grow * D + pcb8 * 8) = kreg[x];
+                if (pcb8 == 0) a.pos_w[(size_t)u * a.C + grow] = (int)a.t0 + grow - a.n0;
+            }
+        }
         if (with_v) {
 #pragma unroll
             for (int x = 0; x < PIECES / 2; ++x) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int grow = r0 + 2 * (prow_k + x * RPP) + h;
+                    if (keep && grow >= a.n0 && grow < hi)
+                        *reinterpret_cast<half8_t*>(Vw + (size_t)grow * D + pcb8 * 8) = vreg[2 * x + h];
+                }
                 const int col = (2 * (prow_k + x * RPP)) ^ (8 * (pcb8 >> 2));
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
@@ -257,24 +266,31 @@ prefill_chunk_kernel(PrefillArgs a) {
             }
         }
     };
-    // Raw dot products of a 64-row tile with the wave's 16 queries.
-    // TRANSPOSED: d[rb][r] = <k_j, q_i> for cache row j = 64*kt + 16*rb + 4*g + r and query i = li
-    //             (a lane holds one query: what the running softmax and P.V want);
-    // otherwise:  d[rb][r] = <k_j, q_i> for cache row j = 64*kt + 16*rb + li and query i = 4*g + r
-    //             (a lane holds one cache row: what the per-row counts want).
-    auto scores = [&](auto transposed, float4_t (&d)[4]) {
+    // Raw dot products of a 64-row tile with the wave's SB blocks of 16 queries.
+    // TRANSPOSED: d[sb][rb][r] = <k_j, q_i> for cache row j = 64*kt + 16*rb + 4*g + r and query
+    //             i = li of block sb (a lane holds one query per block: what the running
+    //             softmax and P.V want);
+    // otherwise:  d[sb][rb][r] = <k_j, q_i> for cache row j = 64*kt + 16*rb + li and query
+    //             i = 4*g + r of block sb (a lane holds one cache row: what the counts want).
+    // Every K fragment is read from LDS once and used for all SB blocks.
+    auto scores = [&](auto transposed, float4_t (&d)[SB][4]) {
         constexpr bool TRANSPOSED = decltype(transposed)::value;
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb) d[rb] = float4_t{0.f, 0.f, 0.f, 0.f};
+        for (int sb = 0; sb < SB; ++sb)
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) d[sb][rb] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int rb = 0; rb < 4; ++rb) {
                 const half8_t kf = *reinterpret_cast<const half8_t*>(&Ks[(16 * rb + li) * LDK + 32 * ks + 8 * g]);
-                if constexpr (TRANSPOSED)
-                    d[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qB[ks], d[rb], 0, 0, 0);
-                else
-                    d[rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qB[ks], kf, d[rb], 0, 0, 0);
+#pragma unroll
+                for (int sb = 0; sb < SB; ++sb) {
+                    if constexpr (TRANSPOSED)
+                        d[sb][rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qB[sb][ks], d[sb][rb], 0, 0, 0);
+                    else
+                        d[sb][rb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qB[sb][ks], kf, d[sb][rb], 0, 0, 0);
+                }
             }
     };
     using Transposed = std::integral_constant<bool, true>;
@@ -284,136 +300,167 @@ prefill_chunk_kernel(PrefillArgs a) {
     // m is kept in the scaled (log2) domain; the scale is positive, so the maximum can be
     // taken over the raw dot products and scaled once.
     const float c2 = a.qk_log2;
-    float m = -INFINITY, lsum = 0.f;
-    float4_t acc[CB];
+    float m[SB], lsum[SB];
+    float4_t acc[SB][CB];
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb) acc[cb] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int sb = 0; sb < SB; ++sb) {
+        m[sb] = -INFINITY;
+        lsum[sb] = 0.f;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) acc[sb][cb] = float4_t{0.f, 0.f, 0.f, 0.f};
+    }
     fetch(0, WITH_PV);
     for (int kt = 0; kt < ntiles; ++kt) {
         __syncthreads();
-        stage(WITH_PV);
+        stage(WITH_PV, kt);
         __syncthreads();
         if (kt + 1 < ntiles) fetch(kt + 1, WITH_PV);
         if (kt * KB > wave_lim) continue;  // nothing in this tile is visible to this wave
-        float4_t d[4];
+        float4_t d[SB][4];
         scores(Transposed{}, d);
-        if (kt * KB + KB - 1 > wave_first_lim) {  // the causal boundary crosses this tile
-            const int rel = lim - (kt * KB + 4 * g);  // rows 16*rb + r <= rel are visible
+        half4_t ph[SB][4];
 #pragma unroll
-            for (int rb = 0; rb < 4; ++rb)
+        for (int sb = 0; sb < SB; ++sb) {
+            if (kt * KB + KB - 1 > sub_first_lim[sb]) {  // the causal boundary crosses this tile
+                const int rel = lim[sb] - (kt * KB + 4 * g);  // rows 16*rb + r <= rel are visible
 #pragma unroll
-                for (int r = 0; r < 4; ++r) d[rb][r] = (16 * rb + r <= rel) ? d[rb][r] : -INFINITY;
-        }
-        float tmax = fmaxf(fmaxf(d[0][0], d[0][1]), fmaxf(d[0][2], d[0][3]));
+                for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
-        for (int rb = 1; rb < 4; ++rb)
-            tmax = fmaxf(tmax, fmaxf(fmaxf(d[rb][0], d[rb][1]), fmaxf(d[rb][2], d[rb][3])));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float m_new = fmaxf(m, tmax * c2);  // finite: row 0 of tile 0 is visible to every query
-        if (__builtin_amdgcn_ballot_w64(m_new != m) != 0ull) {
-            const float alpha = fast_exp2(m - m_new);
-            lsum *= alpha;
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb) acc[cb] *= alpha;
-            m = m_new;
-        }
-        half4_t ph[4];
-#pragma unroll
-        for (int rb = 0; rb < 4; ++rb) {
-            float4_t p;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                p[r] = fast_exp2(fmaf(d[rb][r], c2, -m));
-                lsum += p[r];
+                    for (int r = 0; r < 4; ++r) d[sb][rb][r] = (16 * rb + r <= rel) ? d[sb][rb][r] : -INFINITY;
             }
-            ph[rb] = __builtin_convertvector(p, half4_t);
+            float tmax = fmaxf(fmaxf(d[sb][0][0], d[sb][0][1]), fmaxf(d[sb][0][2], d[sb][0][3]));
+#pragma unroll
+            for (int rb = 1; rb < 4; ++rb)
+                tmax = fmaxf(tmax, fmaxf(fmaxf(d[sb][rb][0], d[sb][rb][1]), fmaxf(d[sb][rb][2], d[sb][rb][3])));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+            // finite from tile 0 on: row 0 is visible to every query
+            const float m_new = fmaxf(m[sb], tmax * c2);
+            if (__builtin_amdgcn_ballot_w64(m_new != m[sb]) != 0ull) {
+                const float alpha = fast_exp2(m[sb] - m_new);
+                lsum[sb] *= alpha;
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) acc[sb][cb] *= alpha;
+                m[sb] = m_new;
+            }
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) {
+                float4_t p;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    p[r] = fast_exp2(fmaf(d[sb][rb][r], c2, -m[sb]));
+                    lsum[sb] += p[r];
+                }
+                ph[sb][rb] = __builtin_convertvector(p, half4_t);
+            }
         }
         if constexpr (WITH_PV) {
 #pragma unroll
-        for (int kp = 0; kp < 2; ++kp) {
-            // The swizzle of the transposed tile decides which of the two 4-row groups of a
-            // lane sits at the lower LDS address; the probabilities are ordered to match, so
-            // that the operand is one two-address read with no register shuffling.
-            const half8_t B01 = __builtin_shufflevector(ph[2 * kp], ph[2 * kp + 1], 0, 1, 2, 3, 4, 5, 6, 7);
-            const half8_t B10 = __builtin_shufflevector(ph[2 * kp + 1], ph[2 * kp], 0, 1, 2, 3, 4, 5, 6, 7);
+            for (int kp = 0; kp < 2; ++kp) {
+                // The swizzle of the transposed tile decides which of the two 4-row groups of a
+                // lane sits at the lower LDS address; the probabilities are ordered to match,
+                // so that the operand is one two-address read with no register shuffling.
+                half8_t B01[SB], B10[SB];
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) {
-                const int swz = 8 * (cb >> 1);  // channel/32 == cb/2
-                const _Float16* vrow = &Vt[(16 * cb + li) * LDV + (((32 * kp + 4 * g) ^ swz) & ~16)];
-                const half4_t a0 = *reinterpret_cast<const half4_t*>(vrow);
-                const half4_t a1 = *reinterpret_cast<const half4_t*>(vrow + 16);
-                const half8_t A = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
-                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, (swz & 16) ? B10 : B01, acc[cb], 0, 0, 0);
+                for (int sb = 0; sb < SB; ++sb) {
+                    B01[sb] = __builtin_shufflevector(ph[sb][2 * kp], ph[sb][2 * kp + 1], 0, 1, 2, 3, 4, 5, 6, 7);
+                    B10[sb] = __builtin_shufflevector(ph[sb][2 * kp + 1], ph[sb][2 * kp], 0, 1, 2, 3, 4, 5, 6, 7);
+                }
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+                    const int swz = 8 * (cb >> 1);  // channel/32 == cb/2
+                    const _Float16* vrow = &Vt[(16 * cb + li) * LDV + (((32 * kp + 4 * g) ^ swz) & ~16)];
+                    const half4_t a0 = *reinterpret_cast<const half4_t*>(vrow);
+                    const half4_t a1 = *reinterpret_cast<const half4_t*>(vrow + 16);
+                    const half8_t A = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+                    for (int sb = 0; sb < SB; ++sb)
+                        acc[sb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, (swz & 16) ? B10[sb] : B01[sb],
+                                                                              acc[sb][cb], 0, 0, 0);
+                }
             }
-        }
         }
     }
     const bool pass2 = a.counted || a.probs;
     if (pass2) fetch(0, false);  // in flight while the outputs are written
-    lsum += __shfl_xor(lsum, 16);
-    lsum += __shfl_xor(lsum, 32);
-    const float invL = 1.0f / lsum;
-    if (WITH_PV && a.out && valid) {
-        _Float16* orow = a.out + (size_t)u * a.out_unit_stride + (size_t)qi * D + 4 * g;
+    float invL[SB];
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-            *reinterpret_cast<half4_t*>(orow + 16 * cb) = __builtin_convertvector(acc[cb] * invL, half4_t);
+    for (int sb = 0; sb < SB; ++sb) {
+        lsum[sb] += __shfl_xor(lsum[sb], 16);
+        lsum[sb] += __shfl_xor(lsum[sb], 32);
+        invL[sb] = 1.0f / lsum[sb];
+        if (WITH_PV && a.out && valid[sb]) {
+            _Float16* orow = a.out + (size_t)u * a.out_unit_stride + (size_t)qi[sb] * D + 4 * g;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+                *reinterpret_cast<half4_t*>(orow + 16 * cb) = __builtin_convertvector(acc[sb][cb] * invL[sb], half4_t);
+        }
     }
     if (!pass2) return;
 
     // ---- pass 2: the probabilities themselves, thresholds, counts ---------------------------
-    // Scores are recomputed untransposed, so a lane holds ONE cache row and four queries
-    // (4*g + r of its wave): the per-row count is a sum inside the lane plus one LDS atomic.
-    // Each query's maximum and 1/sum come from the lane that owned it in pass 1, through LDS.
+    // Scores are recomputed untransposed, so a lane holds ONE cache row and four queries per
+    // block (4*g + r): the per-row count is a sum inside the lane plus one LDS atomic.  Each
+    // query's maximum and 1/sum come from the lane that owned it in pass 1, through LDS.
     if (g == 0) {
-        stat_m[16 * w + li] = m;
-        stat_inv[16 * w + li] = invL;
+#pragma unroll
+        for (int sb = 0; sb < SB; ++sb) {
+            stat_m[WQ * w + 16 * sb + li] = m[sb];
+            stat_inv[WQ * w + 16 * sb + li] = invL[sb];
+        }
     }
     for (int i = tid; i < ntiles * KB; i += 256) cnt_lds[i] = 0;
     __syncthreads();
-    float qm[4], qinv[4], qtau[4];
-    int qlim[4];
-    const int qbase = q0 + 16 * w + 4 * g;  // this lane's first query
+    float qm[SB][4], qinv[SB][4], qtau[SB][4];
+    int qlim[SB][4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        qm[r] = stat_m[16 * w + 4 * g + r];
-        qinv[r] = stat_inv[16 * w + 4 * g + r];
-        qlim[r] = stat_lim[16 * w + 4 * g + r];
-        // threshold 1/t (tokens seen at that step) or 1/(rows it sees)
-        const long tq = a.thresh_len ? (long)qlim[r] + 1 : a.t0 + qbase + r + 1;
-        // a padding query (past the end of the run) or one that sees no row never counts: no
-        // probability is below -1
-        qtau[r] = (qbase + r < a.c && qlim[r] >= 0) ? __fdiv_rn(1.0f, (float)tq) : -1.0f;
+    for (int sb = 0; sb < SB; ++sb) {
+        const int qbase = q0 + WQ * w + 16 * sb + 4 * g;  // this lane's first query of the block
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int si = WQ * w + 16 * sb + 4 * g + r;
+            qm[sb][r] = stat_m[si];
+            qinv[sb][r] = stat_inv[si];
+            qlim[sb][r] = stat_lim[si];
+            // threshold 1/t (tokens seen at that step) or 1/(rows it sees)
+            const long tq = a.thresh_len ? (long)qlim[sb][r] + 1 : a.t0 + qbase + r + 1;
+            // a padding query (past the end of the run) or one that sees no row never counts: no
+            // probability is below -1
+            qtau[sb][r] = (qbase + r < a.c && qlim[sb][r] >= 0) ? __fdiv_rn(1.0f, (float)tq) : -1.0f;
+        }
     }
-    float* pbase = a.probs ? a.probs + (size_t)u * a.probs_unit_stride + (size_t)qbase * a.C : nullptr;
     for (int kt = 0; kt < ntiles; ++kt) {
         __syncthreads();
-        stage(false);
+        stage(false, kt);
         __syncthreads();
         if (kt + 1 < ntiles) fetch(kt + 1, false);
         if (kt * KB > wave_lim) continue;
-        float4_t d[4];
+        float4_t d[SB][4];
         scores(Plain{}, d);
-        const bool diag = kt * KB + KB - 1 > wave_first_lim;
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) {
             const int j = kt * KB + 16 * rb + li;
-            float4_t p;
             int cnt = 0;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                p[r] = fast_exp2(fmaf(d[rb][r], c2, -qm[r])) * qinv[r];
-                bool low = p[r] < qtau[r];
-                if (diag) low = low && j <= qlim[r];
-                cnt += low ? 1 : 0;
+            for (int sb = 0; sb < SB; ++sb) {
+                const bool diag = kt * KB + KB - 1 > sub_first_lim[sb];
+                const int qbase = q0 + WQ * w + 16 * sb + 4 * g;
+                float4_t p;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    p[r] = fast_exp2(fmaf(d[sb][rb][r], c2, -qm[sb][r])) * qinv[sb][r];
+                    bool low = p[r] < qtau[sb][r];
+                    if (diag) low = low && j <= qlim[sb][r];
+                    cnt += low ? 1 : 0;
+                }
+                if (a.probs) {
+                    float* pbase = a.probs + (size_t)u * a.probs_unit_stride + (size_t)qbase * a.C;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (qbase + r < a.c && j <= qlim[sb][r]) pbase[(size_t)r * a.C + j] = p[r];
+                }
             }
             if (cnt) atomicAdd(&cnt_lds[j], cnt);
-            if (pbase) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (qbase + r < a.c && j <= qlim[r]) pbase[(size_t)r * a.C + j] = p[r];
-            }
         }
     }
     __syncthreads();
@@ -788,7 +835,8 @@ hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t
     a.C = L.C;
     a.n0 = c.n0;
     a.c = c.c;
-    a.nqb = (c.c + 63) / 64;
+    const bool wide = !i4 && c.c > 64;  // two blocks of 16 queries per wave
+    a.nqb = wide ? (c.c + 127) / 128 : (c.c + 63) / 64;
     a.t0 = c.t0;
     a.counted = c.counted;
     a.thresh_len = c.thresh_len;
@@ -796,7 +844,7 @@ hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t
     a.pos = nullptr;
     a.n_rows = 0;
     a.ring_w = 0;
-    // fp16: the copy of the run's rows into their slots rides in the same launch
+    // fp16: the run's rows are written into their slots by the attention kernel itself
     a.k_run = i4 ? nullptr : static_cast<const _Float16*>(c.k);
     a.v_run = i4 ? nullptr : static_cast<const _Float16*>(c.v);
     a.pos_w = L.pos;
@@ -804,10 +852,14 @@ hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t
     const unsigned grid = (unsigned)L.U * (unsigned)a.nqb;
     if (i4)
         prefill_chunk_i4_kernel<<<grid, 256, lds, stream>>>(a);
+    else if (L.d == 64 && wide)
+        prefill_chunk_kernel<64, true, 2><<<grid, 256, lds, stream>>>(a);
     else if (L.d == 64)
-        prefill_chunk_kernel<64, true><<<2 * grid, 256, lds, stream>>>(a);
+        prefill_chunk_kernel<64, true, 1><<<grid, 256, lds, stream>>>(a);
+    else if (wide)
+        prefill_chunk_kernel<128, true, 2><<<grid, 256, lds, stream>>>(a);
     else
-        prefill_chunk_kernel<128, true><<<2 * grid, 256, lds, stream>>>(a);
+        prefill_chunk_kernel<128, true, 1><<<grid, 256, lds, stream>>>(a);
     return hipGetLastError();
 }
 
@@ -846,7 +898,8 @@ hipError_t launch_recompute_record(const Layout& L, const ReplayArgs& r, hipStre
     a.C = L.C;
     a.n0 = 0;
     a.c = W;
-    a.nqb = (W + 63) / 64;
+    const bool wide = W > 64;
+    a.nqb = wide ? (W + 127) / 128 : (W + 63) / 64;
     a.t0 = r.t - W;
     a.counted = 1;
     a.thresh_len = r.thresh_len;
@@ -859,10 +912,14 @@ hipError_t launch_recompute_record(const Layout& L, const ReplayArgs& r, hipStre
     a.pos_w = nullptr;
     const size_t lds = (size_t)L.C * sizeof(int);
     const unsigned grid = (unsigned)L.U * (unsigned)a.nqb;
-    if (L.d == 64)
-        prefill_chunk_kernel<64, false><<<grid, 256, lds, stream>>>(a);
+    if (L.d == 64 && wide)
+        prefill_chunk_kernel<64, false, 2><<<grid, 256, lds, stream>>>(a);
+    else if (L.d == 64)
+        prefill_chunk_kernel<64, false, 1><<<grid, 256, lds, stream>>>(a);
+    else if (wide)
+        prefill_chunk_kernel<128, false, 2><<<grid, 256, lds, stream>>>(a);
     else
-        prefill_chunk_kernel<128, false><<<grid, 256, lds, stream>>>(a);
+        prefill_chunk_kernel<128, false, 1><<<grid, 256, lds, stream>>>(a);
     return hipGetLastError();
 }
 

@@ -109,7 +109,7 @@ Run next_run(const sc_config& cfg, const Sizes& z, int32_t mode, int64_t t, int6
     const int64_t units = (int64_t)cfg.batch * cfg.heads;
     r.dense = mode == SC_PREFILL_AUTO && r.len >= kMinDenseRun &&
               sc::prefill_chunk_supported(cfg.kv_dtype, cfg.head_dim, z.E, z.C) &&
-              units * ((r.len + 63) / 64) < (1ll << 30);  // the launch uses two workgroups per query block
+              units * ((r.len + 63) / 64) < (1ll << 31);
     return r;
 }
 
