@@ -88,18 +88,40 @@ def cpu_baseline(wl, sample_units: int, sample_steps: int) -> dict:
     }
 
 
-def prefill_flops(wl) -> float:
-    """Algorithmic flops of one prompt pass: position i attends over the n_i rows resident at
-    that step (its own included), 2*d multiply-adds for the score and 2*d for P.V per row.
-    The recomputation of the scores in the counting pass is not counted."""
-    n_trig = wl.budget + 1
-    n, total = 0, 0
-    for _ in range(wl.prompt):
-        n += 1
-        total += n
+def prefill_work(wl):
+    """Algorithmic work of one prompt pass -> (flops, bytes).  The prompt is cut into runs that
+    end at the steps t = n_trig + k*m (after which a compression is due); a run of c positions
+    that finds n0 rows resident costs, per unit,
+      flops: position i attends over n0 + i + 1 rows, 2*d multiply-adds for the score and 2*d
+             for P.V per row (the recomputation of the scores in the counting pass is not
+             counted);
+      bytes: the n0 + c visible K and V rows read once, the c new K and V rows written, c query
+             rows read and c output rows written, a 16-bit counter read and written per visible
+             row when the run counts (4-bit storage: plus the run's fp16 rows read to be
+             quantised).
+    The traffic of the compressions between runs is not counted (it depends on which rows go)."""
+    from paper_2305_17118_amd.workloads import KV_F16
+    d = wl.head_dim
+    row = d * 2 if wl.kv_dtype == KV_F16 else d // 2 + (d // 64) * 4
+    n_trig, m, E = wl.budget + 1, wl.drop, wl.history // wl.drop
+    t = n = 0
+    rows_attended = 0
+    nbytes = 0
+    while t < wl.prompt:
+        a = t + 1 - n_trig
+        epoch = (a + m - 1) // m if a >= 0 else -((-a) // m)
+        c = min(wl.prompt - t, n_trig + epoch * m - t)
+        rows_attended += c * n + c * (c + 1) // 2
+        nbytes += (n + c) * 2 * row + c * 2 * row + c * d * 2 * 2
+        if wl.kv_dtype != KV_F16:
+            nbytes += c * 2 * d * 2  # the run's fp16 rows are read once more, to be quantised
+        if epoch > -E:
+            nbytes += (n + c) * 4
+        t += c
+        n += c
         if n == n_trig:
-            n -= wl.drop
-    return 4.0 * wl.head_dim * total * wl.units
+            n -= m
+    return 4.0 * d * rows_attended * wl.units, float(nbytes) * wl.units
 
 
 def bench_prefill(args, wl, dev) -> int:
@@ -137,8 +159,13 @@ def bench_prefill(args, wl, dev) -> int:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     dev_ms = e0.elapsed_time(e1) / K
-    flops = prefill_flops(wl)
-    achieved = flops / (dev_ms * 1e-3) / 1e12
+    flops, nbytes = prefill_work(wl)
+    # which roofline binds: a run offers only m queries per K/V row read, so with per-unit caches
+    # the prompt phase is bound by HBM unless m is large
+    t_mfma, t_hbm = flops / (MFMA_F16_PEAK_TFLOPS * 1e12), nbytes / (HBM_PEAK_GBS * 1e9)
+    hbm_bound = t_hbm >= t_mfma
+    tflops = flops / (dev_ms * 1e-3) / 1e12
+    gbs = nbytes / (dev_ms * 1e-3) / 1e9
     res = {
         "metric": "prompt tokens/s into a budgeted KV cache", "value": wl.batch * P * K / wall,
         "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": wall / K * 1e3,
@@ -147,13 +174,20 @@ def bench_prefill(args, wl, dev) -> int:
         "config": {"workload": wl.name, "phase": "prefill", "batch": wl.batch, "heads": wl.heads,
                    "head_dim": d, "prompt": P, "budget": wl.budget, "recent": wl.recent,
                    "history": wl.history, "drop": wl.drop, "trigger": "hard_cap"},
-        # every launch of the call (append, attention, select, compact) is inside the timed
-        # span, so this is a lower bound on the attention kernel's own rate
-        "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None,
+        # every launch of the call (attention, select, compact) is inside the timed span, so
+        # this is a lower bound on the attention kernel's own rate
+        "roofline": {"bound": "hbm" if hbm_bound else "mfma",
+                     "achieved": gbs if hbm_bound else tflops,
+                     "peak": HBM_PEAK_GBS if hbm_bound else MFMA_F16_PEAK_TFLOPS,
+                     "unit": "GB/s" if hbm_bound else "TFLOP/s",
+                     "frac": gbs / HBM_PEAK_GBS if hbm_bound else tflops / MFMA_F16_PEAK_TFLOPS,
+                     "traffic": None,
                      "kernel": ("prefill_chunk_kernel" if wl.kv_dtype == KV_F16 else "prefill_chunk_i4_kernel")
                      + " (whole sc_prefill call timed)",
-                     "call_ms_avg": dev_ms, "algorithmic_flops_per_call": flops},
+                     "call_ms_avg": dev_ms, "algorithmic_flops_per_call": flops,
+                     "algorithmic_bytes_per_call": nbytes, "tflops": tflops,
+                     "mfma_frac": tflops / MFMA_F16_PEAK_TFLOPS, "gbs": gbs,
+                     "hbm_frac": gbs / HBM_PEAK_GBS},
     }
     print(json.dumps(res))
     return 0
