@@ -263,6 +263,42 @@ def test_recomputed_record_after_dense_prefill():
     assert st["compressions"] >= 3
 
 
+@pytest.mark.parametrize("kv,d,window,record", [
+    (KV_F16, 128, B.SC_WINDOW_AUTO, B.SC_RECORD_ONLINE), (KV_F32, 64, B.SC_WINDOW_AUTO, B.SC_RECORD_ONLINE),
+    (KV_I4G64, 128, B.SC_WINDOW_AUTO, B.SC_RECORD_ONLINE), (KV_I4G64, 64, B.SC_WINDOW_AUTO, B.SC_RECORD_ONLINE),
+    (KV_F16, 128, B.SC_WINDOW_RING, B.SC_RECORD_ONLINE), (KV_F16, 128, B.SC_WINDOW_AUTO, B.SC_RECORD_RECOMPUTE)],
+    ids=["f16", "f32", "i4-d128", "i4-d64", "f16-ring", "f16-recompute"])
+def test_decode_without_dumps_leaves_the_same_state(kv, d, window, record):
+    """The benchmark's path: no `probs_out`, no `evicted_out`.  Outputs, records, positions and
+    stored rows must be exactly those of the instrumented calls the parity tests compare."""
+    wl = _wl("prod", 2, 3, d, kv, 0, 150, 64, 8, 32, 16, 0.05)
+    T, U = wl.total, wl.units
+    q, k, v = (torch.from_numpy(a).cuda() for a in streams(wl))
+    cfg = B.make_config(wl.batch, wl.heads, d, kv, wl.budget, wl.recent, wl.history, wl.drop,
+                        window_mode=window, record_mode=record)
+    a, b = B.BudgetCache(cfg), B.BudgetCache(cfg)
+    out_a = torch.empty(U, d, dtype=a.io_dtype, device="cuda")
+    out_b = torch.empty_like(out_a)
+    probs = torch.zeros(U, a.capacity, dtype=torch.float32, device="cuda")
+    ev = torch.empty(U, wl.drop, dtype=torch.int32, device="cuda")
+    re_probs = torch.zeros(U, wl.history, a.capacity, dtype=torch.float32, device="cuda")
+    compressions = 0
+    for s in range(T):
+        due_a = a.decode_step(q[:, s], k[:, s], v[:, s], out_a, probs, in_stride=T * d)
+        due_b = b.decode_step(q[:, s], k[:, s], v[:, s], out_b, None, in_stride=T * d)
+        assert due_a == due_b and torch.equal(out_a, out_b), "step %d" % s
+        if due_a:
+            a.compress(ev, re_probs if record == B.SC_RECORD_RECOMPUTE else None)
+            b.compress()
+            compressions += 1
+    assert compressions >= 5 and (a.n, a.t) == (b.n, b.t)
+    n = a.n
+    planes_a, planes_b = (c.ring() if c.ring_words else c.cnt() for c in (a, b))
+    assert torch.equal(planes_a, planes_b) and torch.equal(a.pos()[:, :n], b.pos()[:, :n])
+    for xa, xb in zip(a.kv_rows(), b.kv_rows()):
+        assert torch.equal(xa[:, :n], xb[:, :n])
+
+
 @pytest.mark.parametrize("kv", [KV_F16, KV_I4G64], ids=["f16", "i4"])
 def test_dense_prefill_production_path_and_reset(kv):
     """The dumps are optional: a call without `out` and `probs_out` (the second pass then only
