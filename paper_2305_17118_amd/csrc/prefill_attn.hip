@@ -474,8 +474,8 @@ prefill_chunk_kernel(PrefillArgs a) {
 
 
 // ---------------------------------------------------------------------------------------
-// 4-bit storage (head size 128).  The run's rows are quantised into their slots first (one
-// wave per row, the same single-operation fp32 arithmetic as the decode kernel, so the
+// 4-bit storage (head size 128).  The run's rows are quantised into their slots first (16
+// lanes per row, the same single-operation fp32 arithmetic as the decode kernel, so the
 // codes are identical to what stepping would have stored).  The attention kernel has the
 // structure of prefill_chunk_kernel; what differs is how a tile is staged and how a score
 // is finished:
@@ -488,22 +488,79 @@ prefill_chunk_kernel(PrefillArgs a) {
 // (3,7); the staged K tile keeps that order inside every 8 channels and the query operand is
 // permuted once to match.
 // ---------------------------------------------------------------------------------------
+// Quantise 8 consecutive channels held by one lane; the 8 lanes that share a group of 64
+// channels are adjacent (half a DPP row).  Same single-operation fp32 arithmetic as
+// quantise_row, so the codes and meta words are identical; returns the 8 codes packed into one
+// word (channel e in nibble e) and the group's meta word.
+__device__ __forceinline__ uint32_t quantise_octet(const half8_t x, uint32_t& meta_word) {
+    float f[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] = (float)x[e];
+    float mn = fminf(fminf(fminf(f[0], f[1]), fminf(f[2], f[3])), fminf(fminf(f[4], f[5]), fminf(f[6], f[7])));
+    float mx = fmaxf(fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])), fmaxf(fmaxf(f[4], f[5]), fmaxf(f[6], f[7])));
+    auto dpp = [](float v, auto ctrl) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v),
+                                                                     decltype(ctrl)::value, 0xF, 0xF, true));
+    };
+    using X1 = std::integral_constant<int, 0xB1>;   // quad_perm [1,0,3,2]
+    using X2 = std::integral_constant<int, 0x4E>;   // quad_perm [2,3,0,1]
+    using HM = std::integral_constant<int, 0x141>;  // row_half_mirror: the other quad of these 8 lanes
+    mn = fminf(mn, dpp(mn, X1{}));
+    mx = fmaxf(mx, dpp(mx, X1{}));
+    mn = fminf(mn, dpp(mn, X2{}));
+    mx = fmaxf(mx, dpp(mx, X2{}));
+    mn = fminf(mn, dpp(mn, HM{}));
+    mx = fmaxf(mx, dpp(mx, HM{}));
+    const float range = __fsub_rn(mx, mn);
+    _Float16 sh = (_Float16)__fdiv_rn(range, 15.0f);
+    float sc = (float)sh;
+    if (sc == 0.0f) {
+        sc = 1.0f;
+        sh = (_Float16)1.0f;
+    }
+    const _Float16 zh = (_Float16)mn;
+    const float z = (float)zh;
+    uint32_t word = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float c = rintf(__fdiv_rn(__fsub_rn(f[e], z), sc));
+        c = fminf(fmaxf(c, 0.f), 15.f);
+        word |= (uint32_t)c << (4 * e);
+    }
+    MetaWord mw;
+    mw.h[0] = sh;
+    mw.h[1] = zh;
+    meta_word = mw.u32;
+    return word;
+}
+
+// Quantise the run's rows into slots n0.. : 16 lanes per row (8 channels each), 16 rows per
+// workgroup; grid (U, rows/16).
 __global__ void __launch_bounds__(256)
 append_rows_i4_kernel(const _Float16* __restrict__ k, const _Float16* __restrict__ v, long unit_stride,
                       unsigned char* __restrict__ K, unsigned char* __restrict__ V,
                       uint32_t* __restrict__ Km, uint32_t* __restrict__ Vm, int32_t* __restrict__ pos,
                       int C, int n0, int c, int t0) {
     constexpr int D = 128;
-    const int u = blockIdx.x, lane = threadIdx.x & 63;
-    const int row = blockIdx.y * 4 + (threadIdx.x >> 6);
-    if (row >= c) return;
-    const size_t src = (size_t)u * unit_stride + (size_t)row * D + 2 * lane;
+    const int u = blockIdx.x, l8 = threadIdx.x & 15;
+    int row = blockIdx.y * 16 + (threadIdx.x >> 4);
+    const bool live = row < c;
+    row = live ? row : c - 1;  // idle lanes shadow the last row (the reductions need every lane)
+    const size_t src = (size_t)u * unit_stride + (size_t)row * D + 8 * l8;
     const size_t slot = (size_t)u * C + n0 + row;
-    const half2_t kk = *reinterpret_cast<const half2_t*>(k + src);
-    const half2_t vv = *reinterpret_cast<const half2_t*>(v + src);
-    quantise_row<D>((float)kk[0], (float)kk[1], K + slot * (D / 2), Km + slot * (D / 64), nullptr, nullptr, lane);
-    quantise_row<D>((float)vv[0], (float)vv[1], V + slot * (D / 2), Vm + slot * (D / 64), nullptr, nullptr, lane);
-    if (lane == 0) pos[slot] = t0 + row;
+    const half8_t kk = *reinterpret_cast<const half8_t*>(k + src);
+    const half8_t vv = *reinterpret_cast<const half8_t*>(v + src);
+    uint32_t kmw, vmw;
+    const uint32_t kc = quantise_octet(kk, kmw);
+    const uint32_t vc = quantise_octet(vv, vmw);
+    if (!live) return;
+    reinterpret_cast<uint32_t*>(K + slot * (D / 2))[l8] = kc;
+    reinterpret_cast<uint32_t*>(V + slot * (D / 2))[l8] = vc;
+    if ((l8 & 7) == 0) {
+        Km[slot * (D / 64) + (l8 >> 3)] = kmw;
+        Vm[slot * (D / 64) + (l8 >> 3)] = vmw;
+    }
+    if (l8 == 0) pos[slot] = t0 + row;
 }
 
 // The eight codes of word w as fp16 integers, in the order (n0,n4) (n1,n5) (n2,n6) (n3,n7).
@@ -810,7 +867,7 @@ prefill_chunk_i4_kernel(PrefillArgs a) {
 hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t stream) {
     const bool i4 = L.kv_dtype == KV_I4G64;
     if (i4) {
-        const dim3 grid_a(L.U, (c.c + 3) / 4);
+        const dim3 grid_a(L.U, (c.c + 15) / 16);
         append_rows_i4_kernel<<<grid_a, 256, 0, stream>>>(
             static_cast<const _Float16*>(c.k), static_cast<const _Float16*>(c.v), c.unit_stride,
             static_cast<unsigned char*>(L.K), static_cast<unsigned char*>(L.V),
