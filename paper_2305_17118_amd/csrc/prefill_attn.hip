@@ -583,7 +583,7 @@ prefill_chunk_i4_kernel(PrefillArgs a) {
     constexpr uint32_t ROWB = D / 2;  // bytes of codes per row
     __shared__ __align__(16) _Float16 Ks[KB * LDK];
     __shared__ __align__(16) _Float16 Vt[D * LDV];
-    __shared__ __align__(16) uint32_t Kmeta[KB * 2];
+    __shared__ __align__(16) float Kmeta[KB * 4];  // per row: scale, zero of group 0; scale, zero of group 1
     __shared__ float stat_m[QB], stat_inv[QB], stat_q0[QB], stat_q1[QB];
     extern __shared__ int cnt_lds[];
 
@@ -653,35 +653,45 @@ prefill_chunk_i4_kernel(PrefillArgs a) {
             *reinterpret_cast<half8_t*>(&Ks[srow * LDK + 32 * sp + 8 * i]) =
                 __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
         }
-        if ((sp & 1) == 0) Kmeta[srow * 2 + (sp >> 1)] = kmreg;
+        if ((sp & 1) == 0) {
+            MetaWord kw;
+            kw.u32 = kmreg;
+            *reinterpret_cast<float2*>(&Kmeta[srow * 4 + (sp >> 1) * 2]) = make_float2((float)kw.h[0], (float)kw.h[1]);
+        }
         if (with_v) {
             MetaWord mw;
             mw.u32 = vmreg;
-            const float sc = (float)mw.h[0], zr = (float)mw.h[1];
-            // x[c] = value of channel 32*sp + c of this thread's row, c = 0..31, as fp16
-            _Float16 x[32];
+            const half2_t sc2 = {mw.h[0], mw.h[0]}, zr2 = {mw.h[1], mw.h[1]};
+            // P[i][k] = values of channels 32*sp + 8*i + k and + 4 of this thread's row as fp16:
+            // code*scale + zero in one fused fp16 operation (the codes are exact integers, so
+            // this is the real value rounded once)
+            half2_t P[4][4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 4; ++i) {
+                half2_t h[4];
+                codes_to_half(vreg[i], h);
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    x[8 * i + e] = (_Float16)fmaf((float)((vreg[i] >> (4 * e)) & 15u), sc, zr);
+                for (int k = 0; k < 4; ++k) P[i][k] = __builtin_elementwise_fma(h[k], sc2, zr2);
+            }
             // Rows 2k and 2k+1 sit four lanes apart.  The even-row thread ends up with channels
             // 0..15 of both rows, the odd-row thread with channels 16..31, so that each writes
             // 32-bit words {row 2k, row 2k+1} of the transposed tile.
             const bool odd = srow & 1;
             const int col = (srow & ~1) ^ (8 * sp);  // swizzle: channel/32 == sp
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const half2_t lower = {x[2 * j], x[2 * j + 1]}, upper = {x[16 + 2 * j], x[17 + 2 * j]};
-                const uint32_t send = __builtin_bit_cast(uint32_t, odd ? lower : upper);
-                const half2_t got = __builtin_bit_cast(half2_t, (uint32_t)__shfl_xor((int)send, 4));
-                const half2_t mine = odd ? upper : lower;
-                const half2_t r0 = odd ? got : mine, r1 = odd ? mine : got;  // rows 2k, 2k+1
-                const int ch = 32 * sp + (odd ? 16 : 0) + 2 * j;
-                const half2_t w0 = {r0[0], r1[0]}, w1 = {r0[1], r1[1]};
-                *reinterpret_cast<half2_t*>(&Vt[ch * LDV + col]) = w0;
-                *reinterpret_cast<half2_t*>(&Vt[(ch + 1) * LDV + col]) = w1;
-            }
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const half2_t lower = P[i][k], upper = P[2 + i][k];
+                    const uint32_t send = __builtin_bit_cast(uint32_t, odd ? lower : upper);
+                    const half2_t got = __builtin_bit_cast(half2_t, (uint32_t)__shfl_xor((int)send, 4));
+                    const half2_t mine = odd ? upper : lower;
+                    const half2_t r0 = odd ? got : mine, r1 = odd ? mine : got;  // rows 2k, 2k+1
+                    const int ch = 32 * sp + (odd ? 16 : 0) + 8 * i + k;
+                    const half2_t w0 = {r0[0], r1[0]}, w1 = {r0[1], r1[1]};
+                    *reinterpret_cast<half2_t*>(&Vt[ch * LDV + col]) = w0;
+                    *reinterpret_cast<half2_t*>(&Vt[(ch + 4) * LDV + col]) = w1;
+                }
         }
     };
     // Per group: sum_c q_c*code_c for a 64-row tile against the wave's 16 queries (see
@@ -703,14 +713,12 @@ prefill_chunk_i4_kernel(PrefillArgs a) {
             }
     };
     // <q, k> from the two code sums and the row's meta words.
-    auto finish_score = [](float s0, float s1, uint32_t m0, uint32_t m1, float q0s, float q1s) {
-        MetaWord a0, a1;
-        a0.u32 = m0;
-        a1.u32 = m1;
-        float s = (float)a0.h[1] * q0s;
-        s = fmaf((float)a1.h[1], q1s, s);
-        s = fmaf((float)a0.h[0], s0, s);
-        return fmaf((float)a1.h[0], s1, s);
+    // meta = (scale_0, zero_0, scale_1, zero_1) of the row
+    auto finish_score = [](float s0, float s1, float4_t meta, float q0s, float q1s) {
+        float s = meta[1] * q0s;
+        s = fmaf(meta[3], q1s, s);
+        s = fmaf(meta[0], s0, s);
+        return fmaf(meta[2], s1, s);
     };
     using Transposed = std::integral_constant<bool, true>;
     using Plain = std::integral_constant<bool, false>;
@@ -732,13 +740,11 @@ prefill_chunk_i4_kernel(PrefillArgs a) {
         code_dots(Transposed{}, d, d1);
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) {
-            // meta words of rows 16*rb + 4*g + r, r = 0..3: eight consecutive words
-            const u32x4_t ma = *reinterpret_cast<const u32x4_t*>(&Kmeta[(16 * rb + 4 * g) * 2]);
-            const u32x4_t mb = *reinterpret_cast<const u32x4_t*>(&Kmeta[(16 * rb + 4 * g) * 2 + 4]);
-            d[rb][0] = finish_score(d[rb][0], d1[rb][0], ma[0], ma[1], qsum0, qsum1);
-            d[rb][1] = finish_score(d[rb][1], d1[rb][1], ma[2], ma[3], qsum0, qsum1);
-            d[rb][2] = finish_score(d[rb][2], d1[rb][2], mb[0], mb[1], qsum0, qsum1);
-            d[rb][3] = finish_score(d[rb][3], d1[rb][3], mb[2], mb[3], qsum0, qsum1);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float4_t meta = *reinterpret_cast<const float4_t*>(&Kmeta[(16 * rb + 4 * g + r) * 4]);
+                d[rb][r] = finish_score(d[rb][r], d1[rb][r], meta, qsum0, qsum1);
+            }
         }
         if (kt * KB + KB - 1 > wave_first_lim) {
             const int rel = lim - (kt * KB + 4 * g);
@@ -834,12 +840,12 @@ prefill_chunk_i4_kernel(PrefillArgs a) {
         for (int rb = 0; rb < 4; ++rb) {
             const int j = kt * KB + 16 * rb + li;
             const int rel = j - a.n0 - qbase;
-            const uint2 mw = *reinterpret_cast<const uint2*>(&Kmeta[(16 * rb + li) * 2]);
+            const float4_t meta = *reinterpret_cast<const float4_t*>(&Kmeta[(16 * rb + li) * 4]);
             float4_t p;
             int cnt = 0;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float s = finish_score(d[rb][r], d1[rb][r], mw.x, mw.y, qs0[r], qs1[r]);
+                const float s = finish_score(d[rb][r], d1[rb][r], meta, qs0[r], qs1[r]);
                 p[r] = fast_exp2(fmaf(s, c2, -qm[r])) * qinv[r];
                 bool low = p[r] < qtau[r];
                 if (diag) low = low && rel <= r;
