@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes per decode-attention launch measured with rocprofv3 counters (FETCH_SIZE x 2.000 +
 # WRITE_SIZE x 1.000, factors from a copy of known size) for the headline workload in this
 # launch configuration; see profiles/attn_rows_fp16_cfg2_hbm_traffic.md.  Other workloads: null.
-MEASURED_TRAFFIC_BYTES = {"cfg2-opt6.7b-fp16": 253.56e6}
+MEASURED_TRAFFIC_BYTES = {"cfg2-opt6.7b-fp16": 253.59e6}
 
 
 def algorithmic_bytes(wl, n: int) -> int:
