@@ -540,3 +540,74 @@ def test_recompute_forced_probabilities_drive_only_the_record():
     assert np.all(rec[:, 5] == w) and rec.sum() == U * w
     assert np.array_equal(ev, np.array([[0, 1, 5]] * U))  # the largest record, then ties by age
     assert np.all(np.abs(probs.sum(axis=2) - 1.0) < 1e-12)  # the oracle's own probabilities are untouched
+
+
+# --------------------------------------------------------------------------------------
+# Diagnostics the paper plots (oracle/diag.py): persistence ratio (Sec. 3.1) and the
+# attention-score change ratio (Sec. 5), pinned on closed forms produced by the oracle cache.
+# --------------------------------------------------------------------------------------
+def _full_attention_rows(q, k):
+    """Probabilities of every position of one unit from a cache that never evicts."""
+    T, d = q.shape
+    o = Oracle(_cfg(heads=1, head_dim=d, budget=T, recent=1, history=1, drop=1))
+    rows = []
+    for s in range(T):
+        _, p, _ = o.step(q[None, s], k[None, s], np.zeros((1, d), np.float32))
+        rows.append(p[0, : s + 1].copy())
+    return rows
+
+
+def test_persistence_counts_on_closed_forms():
+    from oracle import diag
+    rng = np.random.default_rng(31)
+    T, d, split = 24, 8, 12
+    e0 = np.zeros(d, np.float32)
+    e0[0] = 1.0
+    # (a) one dominant token: every position gives token 0 far more than the average share, every
+    # other token far less -> both pivotal sets are {0}, ratio 1
+    k = rng.standard_normal((T, d)).astype(np.float32) * 0.01
+    k[0] += 40.0 * e0
+    q = np.tile(8.0 * e0, (T, 1)).astype(np.float32)
+    assert diag.persistence_counts(_full_attention_rows(q, k), split) == (1, 1, 1)
+    # (b) every position attends to itself only: S_first is every token but the very first
+    # (alone in its row it holds exactly 1/t = 1, not more), and nothing persists
+    eye = 30.0 * np.eye(T, d * 3, dtype=np.float32)
+    rows = _full_attention_rows(eye, eye)
+    assert diag.persistence_counts(rows, split) == (split - 1, 0, 0)
+    # (c) identical keys: every score is exactly the average, never above it
+    one = np.ones((T, d), np.float32)
+    assert diag.persistence_counts(_full_attention_rows(one, one), split) == (0, 0, 0)
+    # (d) the sets only ever hold tokens below the split, and S_first only needs the first rows
+    q, k = (rng.standard_normal((T, d)).astype(np.float32) * 2 for _ in range(2))
+    rows = _full_attention_rows(q, k)
+    first, later = diag.pivotal_sets(rows, split)
+    assert all(j < split for j in first | later)
+    assert first == diag.pivotal_sets(rows[:split], split)[0]
+
+
+def test_change_ratio_of_survivors_is_one_over_kept_mass_minus_one():
+    """Sec. 5 defines the change ratio (a_s - a_o)/a_o; with the restricted-softmax identity of
+    Lemma A.4 it is the same number for every surviving token of a step, 1/mass - 1 with
+    mass the full attention the survivors hold, and -1 for every evicted token."""
+    from oracle import diag
+    rng = np.random.default_rng(32)
+    U, d, B, r, w, m = 2, 16, 12, 3, 6, 4
+    T = 50
+    q, k, v = _rand(rng, U, T, d)
+    q *= 2.0
+    o = Oracle(_cfg(heads=U, head_dim=d, budget=B, recent=r, history=w, drop=m))
+    full = Oracle(_cfg(heads=U, head_dim=d, budget=T, recent=r, history=w, drop=m))
+    for s in range(T):
+        _, ps, due = o.step(q[:, s], k[:, s], v[:, s])
+        _, pf, _ = full.step(q[:, s], k[:, s], v[:, s])
+        pos = o.positions()
+        n = o.n
+        for u in range(U):
+            mass = diag.kept_mass(pos[u], pf[u])
+            assert 0.0 < mass <= 1.0 + 1e-12
+            ratio = diag.change_ratio(ps[u, :n], pf[u][pos[u]])
+            np.testing.assert_allclose(ratio, 1.0 / mass - 1.0, rtol=1e-8, atol=1e-10)
+            gone = np.setdiff1d(np.arange(s + 1), pos[u])
+            assert np.all(diag.change_ratio(np.zeros(len(gone)), pf[u][gone]) == -1.0)
+        if due:
+            o.compress()
