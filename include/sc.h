@@ -222,6 +222,32 @@ sc_status sc_cache_view(const sc_cache *c, const void **K, const void **V, const
                         const void **V_meta, const int32_t **pos, const uint16_t **cnt,
                         int32_t *capacity, int32_t *buckets);
 
+/* Diagnostic of Sec. 3.1 ("Verification"): the pivotal-token sets behind the persistence
+ * ratio, from full-attention probabilities (e.g. sc_prefill's probs_out of a cache whose budget
+ * is at least the length, so that slot j holds token j).  A token j is pivotal for position i
+ * (0-based; t = i+1 tokens seen) when probs[i][j] > 1/t.  With S_first the tokens j < split
+ * pivotal for some position i < split and S_later those pivotal for some i >= split,
+ *   counts_out[u] = { |S_first|, |S_later|, |S_first ^ S_later| },
+ * so the persistence ratio is counts[2]/counts[1] and |S_first|/split the size the paper
+ * reports beside it (the paper uses split = length/2).
+ *   probs      : device fp32; row i of unit u starts at probs + u*unit_stride + i*row_stride
+ *                and holds at least i+1 probabilities
+ *   counts_out : device int32 [units][3] */
+sc_status sc_diag_persistence(const float *probs, int32_t units, int32_t length, int64_t row_stride,
+                              int64_t unit_stride, int32_t split, int32_t *counts_out, void *stream);
+
+/* Diagnostic behind the attention-score change ratio of Sec. 5: the share of one step's
+ * full attention that falls on the rows the budgeted cache still holds,
+ *   mass_out[u] = sum over resident slots j of probs_full[u][pos[u][j]].
+ * By the restricted-softmax identity (proof of Lemma A.4) every surviving token's budgeted
+ * score is its full score divided by this mass, so the change ratio (a_s - a_o)/a_o is
+ * 1/mass - 1 for every survivor and -1 for every evicted token.
+ *   probs_full : device fp32, unit u's full-attention probabilities by stream position start
+ *                at probs_full + u*unit_stride (at least t entries)
+ *   mass_out   : device fp32 [U] */
+sc_status sc_diag_kept_mass(const sc_cache *c, const float *probs_full, int64_t unit_stride,
+                            float *mass_out, void *stream);
+
 /* Static description of a status code. */
 const char *sc_status_str(sc_status s);
 

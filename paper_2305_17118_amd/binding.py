@@ -25,6 +25,7 @@ EXPORTS = (
     "sc_config_sizes", "sc_workspace_bytes", "sc_schedule", "sc_cache_create", "sc_cache_reset",
     "sc_cache_destroy",
     "sc_decode_step", "sc_compress", "sc_prefill", "sc_prefill_plan", "sc_cache_len", "sc_cache_view", "sc_status_str",
+    "sc_diag_persistence", "sc_diag_kept_mass",
 )
 
 
@@ -69,6 +70,8 @@ def lib():
     l.sc_prefill_plan.argtypes = [cfgp, C.c_int32, C.c_int32, C.c_int32, i32p, i32p, i32p, i32p]
     l.sc_cache_len.argtypes = [vp, i32p, i64p]
     l.sc_cache_view.argtypes = [vp] + [C.POINTER(vp)] * 6 + [i32p, i32p]
+    l.sc_diag_persistence.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int32, vp, vp]
+    l.sc_diag_kept_mass.argtypes = [vp, vp, C.c_int64, vp, vp]
     l.sc_status_str.argtypes = [C.c_int]
     l.sc_status_str.restype = C.c_char_p
     for name in EXPORTS:
@@ -178,6 +181,16 @@ def sc_cache_view(handle):
     return d
 
 
+def sc_diag_persistence(probs_ptr, units, length, row_stride, unit_stride, split, counts_ptr, stream=0) -> None:
+    _check(lib().sc_diag_persistence(probs_ptr, units, length, int(row_stride), int(unit_stride), split,
+                                     counts_ptr, stream), "sc_diag_persistence")
+
+
+def sc_diag_kept_mass(handle, probs_full_ptr, unit_stride, mass_ptr, stream=0) -> None:
+    _check(lib().sc_diag_kept_mass(handle, probs_full_ptr, int(unit_stride), mass_ptr, stream),
+           "sc_diag_kept_mass")
+
+
 # ---- a small holder that keeps the torch workspace alive next to the handle ----------------
 
 class BudgetCache:
@@ -200,6 +213,7 @@ class BudgetCache:
         self._ws_ptr = (base + 255) // 256 * 256
         self.io_dtype = torch.float32 if cfg.kv_dtype == SC_KV_F32 else torch.float16
         self.handle = sc_cache_create(cfg, self._ws_ptr, nbytes, self._stream())
+        self._destroy = lib().sc_cache_destroy  # kept here: module globals may be gone at interpreter exit
         self._view = sc_cache_view(self.handle)
 
     def _stream(self) -> int:
@@ -210,7 +224,7 @@ class BudgetCache:
 
     def close(self):
         if getattr(self, "handle", None):
-            sc_cache_destroy(self.handle)
+            self._destroy(self.handle)
             self.handle = None
 
     __del__ = close

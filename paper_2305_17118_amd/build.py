@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsc.so")
-SOURCES = ("sc_host.cpp", "decode_attn.hip", "prefill_attn.hip", "compress.hip")
+SOURCES = ("sc_host.cpp", "decode_attn.hip", "prefill_attn.hip", "compress.hip", "diag.hip")
 
 # -packed-fp32-ops is switched off on purpose: the compiler then emits scalar fp32 VALU
 # instructions only (the host pass warns that it does not know the feature; harmless).

@@ -416,6 +416,25 @@ sc_status sc_cache_view(const sc_cache* c, const void** K, const void** V, const
     return SC_OK;
 }
 
+sc_status sc_diag_persistence(const float* probs, int32_t units, int32_t length, int64_t row_stride,
+                              int64_t unit_stride, int32_t split, int32_t* counts_out, void* stream) {
+    if (!probs || !counts_out || units < 1 || length < 1 || split < 0 || split > length) return SC_ERR_INVALID_ARG;
+    if (row_stride < length || unit_stride < (int64_t)(length - 1) * row_stride + length) return SC_ERR_INVALID_ARG;
+    if (sc::launch_persistence(probs, units, length, (long)row_stride, (long)unit_stride, split, counts_out,
+                               static_cast<hipStream_t>(stream)) != hipSuccess)
+        return SC_ERR_DEVICE;
+    return SC_OK;
+}
+
+sc_status sc_diag_kept_mass(const sc_cache* c, const float* probs_full, int64_t unit_stride, float* mass_out,
+                            void* stream) {
+    if (!c || !probs_full || !mass_out || unit_stride < c->t) return SC_ERR_INVALID_ARG;
+    if (sc::launch_kept_mass(c->L, c->n, probs_full, (long)unit_stride, mass_out,
+                             static_cast<hipStream_t>(stream)) != hipSuccess)
+        return SC_ERR_DEVICE;
+    return SC_OK;
+}
+
 const char* sc_status_str(sc_status s) {
     switch (s) {
         case SC_OK: return "ok";

@@ -107,6 +107,13 @@ struct ReplayArgs {
 };
 hipError_t launch_recompute_record(const Layout& L, const ReplayArgs& a, hipStream_t stream);
 
+// Diagnostics (diag.hip): pivotal-token counts behind the persistence ratio of Sec. 3.1, and the
+// full-attention mass held by the resident rows.
+hipError_t launch_persistence(const float* probs, int units, int length, long row_stride, long unit_stride,
+                              int split, int32_t* counts, hipStream_t stream);
+hipError_t launch_kept_mass(const Layout& L, int n, const float* full, long unit_stride, float* mass,
+                            hipStream_t stream);
+
 // Zero all counters (cache creation).
 hipError_t launch_clear_counters(const Layout& L, hipStream_t stream);
 

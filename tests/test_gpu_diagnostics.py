@@ -1,0 +1,80 @@
+"""Device diagnostics (persistence counts of Sec. 3.1, attention mass kept by the budgeted
+cache behind the change ratio of Sec. 5) against ``oracle/diag.py``.
+
+The counts are integers decided in fp32 on the probabilities the GPU itself dumped, so they
+must agree exactly with the reference evaluated on those same dumped values; the mass is a
+sum of fp32 numbers and agrees to rounding.  The dumped probabilities themselves are compared
+with the oracle cache by the parity tests."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import diag
+from paper_2305_17118_amd import binding as B
+from paper_2305_17118_amd.workloads import KV_F16, Workload, streams
+
+pytestmark = pytest.mark.gpu
+
+
+def _full_probs(wl, q, k, v):
+    """Full attention of every prompt position: a cache whose budget is the whole length."""
+    cfg = B.make_config(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.total, 1, wl.drop, wl.drop)
+    c = B.BudgetCache(cfg)
+    probs = torch.zeros(wl.units, wl.total, c.capacity, dtype=torch.float32, device="cuda")
+    c.prefill(q, k, v, wl.total, 0, None, probs)
+    return c, probs
+
+
+@pytest.mark.parametrize("heavy,split", [(0.0, 100), (0.1, 100), (0.1, 37), (0.1, 0), (0.1, 200)])
+def test_persistence_counts_match_reference(heavy, split):
+    wl = Workload("diag", 880, 1, 6, 128, KV_F16, 200, 0, 64, 8, 32, 32, heavy)
+    q, k, v = (torch.from_numpy(a).cuda() for a in streams(wl))
+    c, probs = _full_probs(wl, q, k, v)
+    T, C = wl.total, c.capacity
+    counts = torch.full((wl.units, 3), -1, dtype=torch.int32, device="cuda")
+    B.sc_diag_persistence(probs.data_ptr(), wl.units, T, C, T * C, split, counts.data_ptr(),
+                          int(torch.cuda.current_stream().cuda_stream))
+    got = counts.cpu().numpy()
+    host = probs.cpu().numpy()
+    for u in range(wl.units):
+        rows = [host[u, i, : i + 1] for i in range(T)]
+        assert tuple(got[u]) == diag.persistence_counts(rows, split), "unit %d" % u
+    assert np.all(got[:, 2] <= got[:, 1]) and np.all(got[:, 2] <= got[:, 0]) and np.all(got[:, 0] <= split)
+
+
+def test_kept_mass_matches_reference_and_explains_the_budgeted_scores():
+    wl = Workload("diag-mass", 881, 1, 5, 128, KV_F16, 0, 260, 96, 8, 64, 32, 0.1)
+    T, d, U = wl.total, wl.head_dim, wl.units
+    q, k, v = (torch.from_numpy(a).cuda() for a in streams(wl))
+    cfg_b = B.make_config(wl.batch, wl.heads, d, wl.kv_dtype, wl.budget, wl.recent, wl.history, wl.drop)
+    cfg_f = B.make_config(wl.batch, wl.heads, d, wl.kv_dtype, T, 1, wl.drop, wl.drop)
+    bud, full = B.BudgetCache(cfg_b), B.BudgetCache(cfg_f)
+    out = torch.empty(U, d, dtype=torch.float16, device="cuda")
+    pb = torch.zeros(U, bud.capacity, dtype=torch.float32, device="cuda")
+    pf = torch.zeros(U, full.capacity, dtype=torch.float32, device="cuda")
+    mass = torch.empty(U, dtype=torch.float32, device="cuda")
+    checked = 0
+    for s in range(T):
+        due = bud.decode_step(q[:, s], k[:, s], v[:, s], out, pb, in_stride=T * d)
+        full.decode_step(q[:, s], k[:, s], v[:, s], out, pf, in_stride=T * d)
+        if s % 7 == 0 or due:
+            B.sc_diag_kept_mass(bud.handle, pf.data_ptr(), full.capacity, mass.data_ptr(),
+                                int(torch.cuda.current_stream().cuda_stream))
+            n = bud.n
+            pos = bud.pos()[:, :n].cpu().numpy()
+            pf_h, pb_h, m_h = pf.cpu().numpy(), pb.cpu().numpy(), mass.cpu().numpy()
+            for u in range(U):
+                ref = diag.kept_mass(pos[u], pf_h[u])
+                assert abs(m_h[u] - ref) <= 2e-6 * max(ref, 1e-3)
+                # the budgeted scores are the full ones divided by the kept mass (Lemma A.4)
+                np.testing.assert_allclose(pb_h[u, :n] * ref, pf_h[u][pos[u]], rtol=2e-3, atol=1e-7)
+            checked += 1
+        if due:
+            bud.compress()
+    assert checked > 40 and bud.n < T
+    with pytest.raises(B.ScError) as e:
+        B.sc_diag_kept_mass(bud.handle, pf.data_ptr(), 5, mass.data_ptr())
+    assert e.value.status == B.SC_ERR_INVALID_ARG
+    with pytest.raises(B.ScError) as e:
+        B.sc_diag_persistence(pf.data_ptr(), U, 10, 4, 100, 5, mass.data_ptr())
+    assert e.value.status == B.SC_ERR_INVALID_ARG
