@@ -72,7 +72,39 @@ struct PrefillArgs {
     const _Float16* k_run;
     const _Float16* v_run;
     int32_t* pos_w;
+    // Exact one-bit-per-step record instead of counters: uint32 [U][ring_words][C], step i owns
+    // bit i mod ring_bits of every row; null with bucket counters.
+    uint32_t* ring;
+    int ring_words, ring_bits;
 };
+
+// Write the low/not-low flags of 16 consecutive steps into one row's ring.  `first_bit` is the
+// bit the first of them owns; bit k of `touch` says step k saw the row (its bit is rewritten:
+// set where `set` has it, cleared otherwise), steps that did not see it leave their bit alone.
+// The run of bits is cut at word ends and where the ring wraps.  Other waves update other bits
+// of the same words at the same time, hence the atomics.
+__device__ __forceinline__ void ring_write16(uint32_t* row_ring, int C, int first_bit, int ring_bits,
+                                             uint32_t set, uint32_t touch) {
+    int b = first_bit, left = 16;
+    while (left > 0) {
+        const int off = b & 31;
+        int take = 32 - off;
+        if (take > ring_bits - b) take = ring_bits - b;
+        if (take > left) take = left;
+        const uint32_t m = take == 32 ? 0xFFFFFFFFu : ((1u << take) - 1u);
+        const uint32_t t = (touch & m) << off, v = (set & m) << off;
+        if (t) {
+            uint32_t* word = row_ring + (size_t)(b >> 5) * C;
+            if (t & ~v) atomicAnd(word, ~(t & ~v));
+            if (v) atomicOr(word, v);
+        }
+        set >>= take;
+        touch >>= take;
+        left -= take;
+        b += take;
+        if (b == ring_bits) b = 0;
+    }
+}
 
 // Matrix-instruction operand layout (16x16x32, fp16 in, fp32 out), lane l, i = l%16, g = l/16:
 //   A: lane holds A[i][8g .. 8g+7]      B: lane holds B[8g .. 8g+7][i]      D: lane holds D[4g + r][i]
@@ -413,12 +445,20 @@ prefill_chunk_kernel(PrefillArgs a) {
     __syncthreads();
     float qm[SB][4], qinv[SB][4], qtau[SB][4];
     int qlim[SB][4];
+    // ring record: which of this lane's queries write their bit (real, see a row, and among the
+    // last ring_bits steps of the run: an earlier step's bit is overwritten within the run)
+    // and the bit the first query of each 16-block owns
+    uint32_t qwrites[SB];
+    int blk_bit[SB];
 #pragma unroll
     for (int sb = 0; sb < SB; ++sb) {
         const int qbase = q0 + WQ * w + 16 * sb + 4 * g;  // this lane's first query of the block
+        qwrites[sb] = 0;
+        blk_bit[sb] = a.ring ? (int)((a.t0 + q0 + WQ * w + 16 * sb + 1) % a.ring_bits) : 0;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int si = WQ * w + 16 * sb + 4 * g + r;
+            if (qbase + r < a.c && stat_lim[si] >= 0 && qbase + r >= a.c - a.ring_bits) qwrites[sb] |= 1u << r;
             qm[sb][r] = stat_m[si];
             qinv[sb][r] = stat_inv[si];
             qlim[sb][r] = stat_lim[si];
@@ -446,12 +486,25 @@ prefill_chunk_kernel(PrefillArgs a) {
                 const bool diag = kt * KB + KB - 1 > sub_first_lim[sb];
                 const int qbase = q0 + WQ * w + 16 * sb + 4 * g;
                 float4_t p;
+                uint32_t setn = 0, seen = 0;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     p[r] = fast_exp2(fmaf(d[sb][rb][r], c2, -qm[sb][r])) * qinv[sb][r];
                     bool low = p[r] < qtau[sb][r];
-                    if (diag) low = low && j <= qlim[sb][r];
+                    const bool sees = !diag || j <= qlim[sb][r];
+                    low = low && sees;
                     cnt += low ? 1 : 0;
+                    setn |= (low ? 1u : 0u) << r;
+                    seen |= (sees ? 1u : 0u) << r;
+                }
+                if (a.ring) {
+                    // the 16 queries of the block: this lane's four sit at bits 4g .. 4g+3
+                    uint32_t both = ((setn & qwrites[sb]) << (4 * g)) | ((seen & qwrites[sb]) << (4 * g + 16));
+                    both |= (uint32_t)__shfl_xor((int)both, 16);
+                    both |= (uint32_t)__shfl_xor((int)both, 32);
+                    if (g == 0 && (both >> 16))
+                        ring_write16(a.ring + (size_t)u * a.ring_words * a.C + j, a.C, blk_bit[sb], a.ring_bits,
+                                     both & 0xFFFFu, both >> 16);
                 }
                 if (a.probs) {
                     float* pbase = a.probs + (size_t)u * a.probs_unit_stride + (size_t)qbase * a.C;
@@ -460,11 +513,11 @@ prefill_chunk_kernel(PrefillArgs a) {
                         if (qbase + r < a.c && j <= qlim[sb][r]) pbase[(size_t)r * a.C + j] = p[r];
                 }
             }
-            if (cnt) atomicAdd(&cnt_lds[j], cnt);
+            if (cnt && !a.ring) atomicAdd(&cnt_lds[j], cnt);
         }
     }
     __syncthreads();
-    if (!a.counted) return;
+    if (!a.counted || a.ring) return;
     uint32_t* cw = reinterpret_cast<uint32_t*>(a.cnt + (size_t)u * a.cnt_unit_stride);
     for (int i = tid; 2 * i < hi; i += 256) {
         const uint32_t word = (uint32_t)cnt_lds[2 * i] | ((uint32_t)cnt_lds[2 * i + 1] << 16);
@@ -911,6 +964,9 @@ hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t
     a.k_run = i4 ? nullptr : static_cast<const _Float16*>(c.k);
     a.v_run = i4 ? nullptr : static_cast<const _Float16*>(c.v);
     a.pos_w = L.pos;
+    a.ring = L.W32 ? reinterpret_cast<uint32_t*>(L.cnt) : nullptr;
+    a.ring_words = L.W32;
+    a.ring_bits = L.W32 ? L.w : (1 << 30);
     const size_t lds = (size_t)L.C * sizeof(int);
     const unsigned grid = (unsigned)L.U * (unsigned)a.nqb;
     if (i4)
@@ -973,6 +1029,9 @@ hipError_t launch_recompute_record(const Layout& L, const ReplayArgs& r, hipStre
     a.k_run = nullptr;
     a.v_run = nullptr;
     a.pos_w = nullptr;
+    a.ring = nullptr;
+    a.ring_words = 0;
+    a.ring_bits = 1 << 30;
     const size_t lds = (size_t)L.C * sizeof(int);
     const unsigned grid = (unsigned)L.U * (unsigned)a.nqb;
     if (L.d == 64 && wide)

@@ -108,7 +108,7 @@ Run next_run(const sc_config& cfg, const Sizes& z, int32_t mode, int64_t t, int6
     r.len = std::min<int64_t>(remaining, z.n_trig + r.epoch * cfg.drop - t);
     const int64_t units = (int64_t)cfg.batch * cfg.heads;
     r.dense = mode == SC_PREFILL_AUTO && r.len >= kMinDenseRun &&
-              sc::prefill_chunk_supported(cfg.kv_dtype, cfg.head_dim, z.E, z.C) &&
+              sc::prefill_chunk_supported(cfg.kv_dtype, cfg.head_dim, z.E, z.W32, z.C) &&
               units * ((r.len + 63) / 64) < (1ll << 31);
     return r;
 }
@@ -338,8 +338,9 @@ sc_status sc_prefill(sc_cache* c, const void* q, const void* k, const void* v, i
             a.n0 = c->n;
             a.c = (int)run;
             a.t0 = (long)c->t;
-            a.bucket = bucket_of(ep, c->L.E);
-            a.counted = !c->L.Qh && ep > -(int64_t)c->L.E;
+            a.bucket = c->L.E ? bucket_of(ep, c->L.E) : 0;
+            // the ring records every step; counters skip steps older than every window
+            a.counted = c->L.W32 ? 1 : (!c->L.Qh && ep > -(int64_t)c->L.E);
             a.thresh_len = c->cfg.thresh_mode == SC_THRESH_INV_LEN;
             a.qk_log2 = c->qk_log2;
             if (sc::launch_prefill_chunk(c->L, a, s) != hipSuccess) return SC_ERR_DEVICE;

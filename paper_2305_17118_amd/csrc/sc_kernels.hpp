@@ -80,11 +80,13 @@ struct ChunkArgs {
     float qk_log2;
 };
 
-// Whether launch_prefill_chunk handles such a cache: fp16 rows (either head size) or 4-bit rows
-// of 128 channels, bucket counters, and a per-slot LDS array that fits beside the tiles.
-inline bool prefill_chunk_supported(int kv_dtype, int d, int E, int C) {
-    if (E == 0 || C > 6144) return false;
-    return kv_dtype == KV_F16 || (kv_dtype == KV_I4G64 && d == 128);
+// Whether launch_prefill_chunk handles such a cache: fp16 rows (either head size; bucket
+// counters or the one-bit-per-step ring) or 4-bit rows of 128 channels (bucket counters), and a
+// per-slot LDS array that fits beside the tiles.
+inline bool prefill_chunk_supported(int kv_dtype, int d, int E, int W32, int C) {
+    if (C > 6144) return false;
+    if (kv_dtype == KV_F16) return E > 0 || W32 > 0;
+    return kv_dtype == KV_I4G64 && d == 128 && E > 0;
 }
 
 // Two launches on `stream`: append the run's rows, then attention + counting.

@@ -205,6 +205,28 @@ def test_dense_prefill_matches_oracle(wl, trigger):
     assert st["steps"] == wl.total and st["compressions"] >= 2
 
 
+RING_PREFILL = [
+    # name, batch, heads, d, kv, prompt, decode, B, r, w, m, heavy  (w no multiple of m: ring record)
+    _wl("pf-ring-d128", 1, 4, 128, KV_F16, 400, 70, 150, 8, 100, 48, 0.05),
+    _wl("pf-ring-d64", 2, 2, 64, KV_F16, 333, 50, 100, 6, 45, 32, 0.05),
+    _wl("pf-ring-paper", 1, 3, 128, KV_F16, 700, 300, 400, 10, 400, 200, 0.05),   # r = 10, w = 400, m = B/2
+    _wl("pf-ring-short-window", 1, 2, 128, KV_F16, 300, 60, 100, 8, 5, 48),        # w far below a query block
+    _wl("pf-ring-window-33", 1, 3, 128, KV_F16, 350, 80, 120, 8, 33, 64, 0.1),    # w < run length, odd word split
+    _wl("pf-ring-long-window", 1, 2, 64, KV_F16, 260, 90, 77, 7, 1000, 17, 0.1),  # w beyond everything seen
+]
+
+
+@pytest.mark.parametrize("wl", RING_PREFILL, ids=lambda w: w.name)
+def test_dense_prefill_with_ring_record_matches_oracle(wl):
+    """Dense prompt runs writing the one-bit-per-step record: every position compared, then the
+    decode steps' compressions check the rings the prompt left behind bit for bit."""
+    run = ParityRun(wl, window_mode=B.SC_WINDOW_RING)
+    assert any(dense for _, dense, _ in B.sc_prefill_plan(run.cfg, wl.prompt))
+    run.prefill(wl.prompt)
+    st = run.run()
+    assert st["steps"] == wl.total and st["compressions"] >= 2
+
+
 def test_dense_prefill_inverse_length_threshold():
     wl = _wl("pf-inv-len", 1, 3, 128, KV_F16, 300, 80, 120, 8, 64, 32, 0.05)
     run = ParityRun(wl, thresh=B.SC_THRESH_INV_LEN, scale=0.2)

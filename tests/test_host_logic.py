@@ -163,7 +163,8 @@ def test_compression_ratio_of_the_workloads():
     (dict(budget=60, recent=4, history=16, drop=4), 150),                 # runs too short for a dense block
     (dict(kv_dtype=B.SC_KV_I4G64), 200),
     (dict(kv_dtype=B.SC_KV_F32, head_dim=64), 200),                       # no dense kernel for fp32 rows
-    (dict(history=40), 200),                                              # ring record: streamed
+    (dict(history=40), 200),                                              # ring record, fp16: dense too
+    (dict(history=40, kv_dtype=B.SC_KV_I4G64), 200),                      # ring record, 4-bit: streamed
 ])
 def test_prefill_plan_follows_the_schedule(kw, prompt):
     """The runs sc_prefill cuts a prompt into, against a position-by-position simulation of
@@ -174,8 +175,8 @@ def test_prefill_plan_follows_the_schedule(kw, prompt):
     n_trig, cap, E, W32 = B.sc_config_sizes(cfg)
     plan = B.sc_prefill_plan(cfg, prompt)
     assert sum(r[0] for r in plan) == prompt and all(r[0] >= 1 for r in plan)
-    dense_capable = E > 0 and (cfg.kv_dtype == B.SC_KV_F16 or
-                               (cfg.kv_dtype == B.SC_KV_I4G64 and cfg.head_dim == 128))
+    dense_capable = (cfg.kv_dtype == B.SC_KV_F16 and (E > 0 or W32 > 0)) or \
+                    (cfg.kv_dtype == B.SC_KV_I4G64 and cfg.head_dim == 128 and E > 0)
     t = n = 0
     for length, dense, compress in plan:
         epochs = {B.sc_schedule(cfg, t + 1 + i)[0] for i in range(length)}
