@@ -182,8 +182,7 @@ def bench_prefill(args, wl, dev) -> int:
                      "unit": "GB/s" if hbm_bound else "TFLOP/s",
                      "frac": gbs / HBM_PEAK_GBS if hbm_bound else tflops / MFMA_F16_PEAK_TFLOPS,
                      "traffic": None,
-                     "kernel": ("prefill_chunk_kernel" if wl.kv_dtype == KV_F16 else "prefill_chunk_i4_kernel")
-                     + " (whole sc_prefill call timed)",
+                     "kernel": "prefill_chunk_kernel (whole sc_prefill call timed)",
                      "call_ms_avg": dev_ms, "algorithmic_flops_per_call": flops,
                      "algorithmic_bytes_per_call": nbytes, "tflops": tflops,
                      "mfma_frac": tflops / MFMA_F16_PEAK_TFLOPS, "gbs": gbs,

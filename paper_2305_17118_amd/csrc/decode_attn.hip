@@ -430,6 +430,8 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
         for (int w = 0; w < 4; ++w) {
             Frag<_Float16, 8> qr;
             qr.raw = *reinterpret_cast<const uint4*>(qu + w * 8);
+            if (a.q_keep && wv == 0 && g == 0)  // kept for the replay at the next compressions
+                *reinterpret_cast<uint4*>((_Float16*)a.q_keep + (size_t)u * a.q_keep_stride + c * 32 + w * 8) = qr.raw;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 qh[w * 4 + k] = half2_t{qr.e[k], qr.e[k + 4]};
@@ -677,6 +679,11 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_mfma_kernel(AttnArgs a) {
         const _Float16* qu = (const _Float16*)a.q + (size_t)u * a.in_stride + kb * 32;
 #pragma unroll
         for (int t = 0; t < 4; ++t) qraw[t].raw = *reinterpret_cast<const uint4*>(qu + t * 8);
+        if (a.q_keep && wv == 0 && r == 0) {  // kept for the replay at the next compressions
+            _Float16* qk = (_Float16*)a.q_keep + (size_t)u * a.q_keep_stride + kb * 32;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) *reinterpret_cast<uint4*>(qk + t * 8) = qraw[t].raw;
+        }
     }
     uint32_t cpre[cnt_pf(NW * 64)];
     prefetch_counters<NW * 64>(a, u, cpre);

@@ -106,6 +106,109 @@ __device__ __forceinline__ void ring_write16(uint32_t* row_ring, int C, int firs
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// 4-bit storage (head size 128).  The run's rows are quantised into their slots first (16
+// lanes per row, the same single-operation fp32 arithmetic as the decode kernel, so the
+// codes are identical to what stepping would have stored).  prefill_chunk_kernel<128, ., ., true>
+// then differs from the fp16 instantiation in how a tile is staged and how a score is finished:
+//  * keys stay codes: the staged K tile holds the codes as fp16 integers (exact), the matrix
+//    instructions accumulate sum_c q_c*code_c per group of 64 channels, and the score is
+//    scale_0*S_0 + scale_1*S_1 + zero_0*sum(q over group 0) + zero_1*sum(q over group 1)
+//    in fp32, i.e. <q, code*scale + zero> without ever rounding a dequantised key;
+//  * values are dequantised while they are transposed into LDS: fp16(code*scale + zero).
+// Unpacking a word of eight codes with two masks gives the channel pairs (0,4) (1,5) (2,6)
+// (3,7); the staged K tile keeps that order inside every 8 channels and the query operand is
+// permuted once to match.
+// ---------------------------------------------------------------------------------------
+// Quantise 8 consecutive channels held by one lane; the 8 lanes that share a group of 64
+// channels are adjacent (half a DPP row).  Same single-operation fp32 arithmetic as
+// quantise_row, so the codes and meta words are identical; returns the 8 codes packed into one
+// word (channel e in nibble e) and the group's meta word.
+__device__ __forceinline__ uint32_t quantise_octet(const half8_t x, uint32_t& meta_word) {
+    float f[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] = (float)x[e];
+    float mn = fminf(fminf(fminf(f[0], f[1]), fminf(f[2], f[3])), fminf(fminf(f[4], f[5]), fminf(f[6], f[7])));
+    float mx = fmaxf(fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])), fmaxf(fmaxf(f[4], f[5]), fmaxf(f[6], f[7])));
+    auto dpp = [](float v, auto ctrl) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v),
+                                                                     decltype(ctrl)::value, 0xF, 0xF, true));
+    };
+    using X1 = std::integral_constant<int, 0xB1>;   // quad_perm [1,0,3,2]
+    using X2 = std::integral_constant<int, 0x4E>;   // quad_perm [2,3,0,1]
+    using HM = std::integral_constant<int, 0x141>;  // row_half_mirror: the other quad of these 8 lanes
+    mn = fminf(mn, dpp(mn, X1{}));
+    mx = fmaxf(mx, dpp(mx, X1{}));
+    mn = fminf(mn, dpp(mn, X2{}));
+    mx = fmaxf(mx, dpp(mx, X2{}));
+    mn = fminf(mn, dpp(mn, HM{}));
+    mx = fmaxf(mx, dpp(mx, HM{}));
+    const float range = __fsub_rn(mx, mn);
+    _Float16 sh = (_Float16)__fdiv_rn(range, 15.0f);
+    float sc = (float)sh;
+    if (sc == 0.0f) {
+        sc = 1.0f;
+        sh = (_Float16)1.0f;
+    }
+    const _Float16 zh = (_Float16)mn;
+    const float z = (float)zh;
+    uint32_t word = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float c = rintf(__fdiv_rn(__fsub_rn(f[e], z), sc));
+        c = fminf(fmaxf(c, 0.f), 15.f);
+        word |= (uint32_t)c << (4 * e);
+    }
+    MetaWord mw;
+    mw.h[0] = sh;
+    mw.h[1] = zh;
+    meta_word = mw.u32;
+    return word;
+}
+
+// Quantise the run's rows into slots n0.. : 16 lanes per row (8 channels each), 16 rows per
+// workgroup; grid (U, rows/16).
+__global__ void __launch_bounds__(256)
+append_rows_i4_kernel(const _Float16* __restrict__ k, const _Float16* __restrict__ v, long unit_stride,
+                      unsigned char* __restrict__ K, unsigned char* __restrict__ V,
+                      uint32_t* __restrict__ Km, uint32_t* __restrict__ Vm, int32_t* __restrict__ pos,
+                      int C, int n0, int c, int t0) {
+    constexpr int D = 128;
+    const int u = blockIdx.x, l8 = threadIdx.x & 15;
+    int row = blockIdx.y * 16 + (threadIdx.x >> 4);
+    const bool live = row < c;
+    row = live ? row : c - 1;  // idle lanes shadow the last row (the reductions need every lane)
+    const size_t src = (size_t)u * unit_stride + (size_t)row * D + 8 * l8;
+    const size_t slot = (size_t)u * C + n0 + row;
+    const half8_t kk = *reinterpret_cast<const half8_t*>(k + src);
+    const half8_t vv = *reinterpret_cast<const half8_t*>(v + src);
+    uint32_t kmw, vmw;
+    const uint32_t kc = quantise_octet(kk, kmw);
+    const uint32_t vc = quantise_octet(vv, vmw);
+    if (!live) return;
+    reinterpret_cast<uint32_t*>(K + slot * (D / 2))[l8] = kc;
+    reinterpret_cast<uint32_t*>(V + slot * (D / 2))[l8] = vc;
+    if ((l8 & 7) == 0) {
+        Km[slot * (D / 64) + (l8 >> 3)] = kmw;
+        Vm[slot * (D / 64) + (l8 >> 3)] = vmw;
+    }
+    if (l8 == 0) pos[slot] = t0 + row;
+}
+
+// The eight codes of word w as fp16 integers, in the order (n0,n4) (n1,n5) (n2,n6) (n3,n7).
+__device__ __forceinline__ void codes_to_half(uint32_t w, half2_t (&h)[4]) {
+    const uint32_t t = w >> 8;
+    const half2_t k1024 = {(_Float16)1024.f, (_Float16)1024.f};
+    const half2_t k64 = {(_Float16)64.f, (_Float16)64.f};
+    const half2_t sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
+    // (w & mask) | 0x6400 per half is the fp16 number 1024 + code (low nibble) or 1024 + 16*code
+    h[0] = __builtin_bit_cast(half2_t, (w & 0x000F000Fu) | 0x64006400u) - k1024;
+    h[1] = __builtin_bit_cast(half2_t, (w & 0x00F000F0u) | 0x64006400u) * sixteenth - k64;
+    h[2] = __builtin_bit_cast(half2_t, (t & 0x000F000Fu) | 0x64006400u) - k1024;
+    h[3] = __builtin_bit_cast(half2_t, (t & 0x00F000F0u) | 0x64006400u) * sixteenth - k64;
+}
+
+
 // Matrix-instruction operand layout (16x16x32, fp16 in, fp32 out), lane l, i = l%16, g = l/16:
 //   A: lane holds A[i][8g .. 8g+7]      B: lane holds B[8g .. 8g+7][i]      D: lane holds D[4g + r][i]
 // Scores are computed transposed, S^T = K Q^T (A = 16 cache rows, B = 16 queries), so a lane
@@ -128,9 +231,13 @@ __device__ __forceinline__ void ring_write16(uint32_t* row_ring, int C, int firs
 // SB = blocks of 16 queries per wave.  With SB = 2 every K and V fragment read from LDS feeds
 // two matrix instructions (LDS operand traffic, the busiest resource of this kernel, is halved
 // per query) at the price of twice the accumulators, i.e. two instead of three waves per SIMD.
-template <int D, bool WITH_PV, int SB>
+//
+// I4 = true: 4-bit rows (see above); the rows are already in their slots (quantised by
+// append_rows_i4_kernel), so nothing is read from the caller's arrays or written here.
+template <int D, bool WITH_PV, int SB, bool I4>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SB == 1 ? 3 : 2)))
 prefill_chunk_kernel(PrefillArgs a) {
+    static_assert(!I4 || D == 128, "4-bit rows: two groups of 64 channels");
     constexpr int KB = 64;        // cache rows per tile
     constexpr int WQ = 16 * SB;   // queries per wave
     constexpr int QB = 4 * WQ;    // queries per workgroup
@@ -142,6 +249,8 @@ prefill_chunk_kernel(PrefillArgs a) {
     __shared__ __align__(16) _Float16 Ks[KB * LDK];
     __shared__ __align__(16) _Float16 Vt[D * LDV];
     __shared__ float stat_m[QB], stat_inv[QB];  // per query: final maximum, 1/sum (pass 1 -> pass 2)
+    __shared__ __align__(16) float Kmeta[I4 ? KB * 4 : 4];  // 4-bit: per tile row scale, zero of group 0; of group 1
+    __shared__ float stat_q0[I4 ? QB : 1], stat_q1[I4 ? QB : 1];  // 4-bit: per query, sum of q over each group
     __shared__ int stat_lim[QB];                // per query: last row it sees (-1: none)
     extern __shared__ int cnt_lds[];  // [tiles * 64] low-score counts of this workgroup's queries
 
@@ -152,7 +261,14 @@ prefill_chunk_kernel(PrefillArgs a) {
     // which sees all of them, also writes them into their slots as they pass through its
     // registers (Alg. 1 "model update"): no separate copy pass, no second read.
     const bool fused = a.k_run != nullptr;
-    const unsigned blk = blockIdx.x;
+    // Workgroups are handed to the 8 XCDs round-robin by their index; each XCD has its own L2.
+    // Renumber them so that an XCD receives consecutive numbers: the query blocks of one unit,
+    // which read the same K/V rows, then run on one XCD at about the same time and share its L2.
+    unsigned blk;
+    {
+        const unsigned per = gridDim.x / 8, rem = gridDim.x % 8, xcd = blockIdx.x % 8, idx = blockIdx.x / 8;
+        blk = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
+    }
     const int u = blk / a.nqb;
     const int q0 = (a.nqb - 1 - (int)(blk % a.nqb)) * QB;  // longest query blocks first
     const bool writer = fused && blk % a.nqb == 0;
@@ -204,13 +320,40 @@ prefill_chunk_kernel(PrefillArgs a) {
     const _Float16* Krun = fused ? a.k_run + (size_t)u * a.unit_stride : nullptr;
     const _Float16* Vrun = fused ? a.v_run + (size_t)u * a.unit_stride : nullptr;
 
+    // 4-bit rows: codes, and one meta word per row and group
+    const unsigned char* Kc = static_cast<const unsigned char*>(a.K) + (size_t)u * a.C * (D / 2);
+    const unsigned char* Vc = static_cast<const unsigned char*>(a.V) + (size_t)u * a.C * (D / 2);
+    const uint32_t* Kmb = I4 ? a.K_meta + (size_t)u * a.C * 2 : nullptr;
+    const uint32_t* Vmb = I4 ? a.V_meta + (size_t)u * a.C * 2 : nullptr;
+
+    // Query operand.  4-bit: channels 32*ks + 8*g + {0,4,1,5,2,6,3,7} (the order the codes are
+    // unpacked in), plus the sums of q over the two groups for the zero points.
     half8_t qB[SB][KS];
+    float qsum0[SB], qsum1[SB];
 #pragma unroll
     for (int sb = 0; sb < SB; ++sb) {
         const long qslot = a.ring_w ? (a.t0 + qc[sb]) % a.ring_w : qc[sb];
         const _Float16* qrow = a.q + (size_t)u * a.unit_stride + (size_t)qslot * D + 8 * g;
+        float part[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qB[sb][ks] = *reinterpret_cast<const half8_t*>(qrow + 32 * ks);
+        for (int ks = 0; ks < KS; ++ks) {
+            const half8_t x = *reinterpret_cast<const half8_t*>(qrow + 32 * ks);
+            qB[sb][ks] = I4 ? __builtin_shufflevector(x, x, 0, 4, 1, 5, 2, 6, 3, 7) : x;
+            float acc = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc += (float)x[e];
+            part[ks] = acc;
+        }
+        qsum0[sb] = qsum1[sb] = 0.f;
+        if constexpr (I4) {
+            float s0 = part[0] + part[1], s1 = part[KS - 2] + part[KS - 1];
+            s0 += __shfl_xor(s0, 16);
+            s0 += __shfl_xor(s0, 32);
+            s1 += __shfl_xor(s1, 16);
+            s1 += __shfl_xor(s1, 32);
+            qsum0[sb] = s0;
+            qsum1[sb] = s1;
+        }
     }
 
     // A tile travels global -> registers -> LDS; the loads of tile kt+1 are issued before
@@ -225,8 +368,23 @@ prefill_chunk_kernel(PrefillArgs a) {
     const int prow_k = tid / (D / 8), pcb8 = tid % (D / 8);
     const uint32_t koff = (uint32_t)(prow_k * D + pcb8 * 8) * 2u;       // bytes inside a tile
     const uint32_t voff = (uint32_t)(2 * prow_k * D + pcb8 * 8) * 2u;
+    // 4-bit staging: thread = (tile row tid/4, 32 channels starting at 32*(tid%4))
+    const int srow = tid >> 2, sp = tid & 3;
+    u32x4_t kcodes, vcodes;
+    uint32_t kmreg = 0, vmreg = 0;
     auto fetch = [&](int kt, bool with_v) {
         const int r0 = kt * KB;
+        if constexpr (I4) {
+            int grow = r0 + srow;
+            grow = grow < hi ? grow : hi - 1;  // stay inside rows that hold data
+            kcodes = *reinterpret_cast<const u32x4_t*>(Kc + (size_t)grow * (D / 2) + sp * 16);
+            kmreg = Kmb[(size_t)grow * 2 + (sp >> 1)];
+            if (with_v) {
+                vcodes = *reinterpret_cast<const u32x4_t*>(Vc + (size_t)grow * (D / 2) + sp * 16);
+                vmreg = Vmb[(size_t)grow * 2 + (sp >> 1)];
+            }
+            return;
+        }
         const bool in_cache = !fused || r0 + KB <= a.n0, in_run = fused && r0 >= a.n0;
         if (r0 + KB <= hi && (in_cache || in_run)) {  // a whole tile of data from one array
             const char* kt_base = in_cache ? reinterpret_cast<const char*>(Kb) + (size_t)r0 * D * 2
@@ -269,6 +427,58 @@ prefill_chunk_kernel(PrefillArgs a) {
     _Float16* Vw = const_cast<_Float16*>(Vb);
     auto stage = [&](bool with_v, int kt) {
         const int r0 = kt * KB;
+        if constexpr (I4) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                half2_t h[4];
+                codes_to_half(kcodes[i], h);
+                const half4_t lo = __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3);
+                const half4_t hi4 = __builtin_shufflevector(h[2], h[3], 0, 1, 2, 3);
+                *reinterpret_cast<half8_t*>(&Ks[srow * LDK + 32 * sp + 8 * i]) =
+                    __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+            if ((sp & 1) == 0) {
+                MetaWord kw;
+                kw.u32 = kmreg;
+                *reinterpret_cast<float2*>(&Kmeta[srow * 4 + (sp >> 1) * 2]) = make_float2((float)kw.h[0], (float)kw.h[1]);
+            }
+            if (with_v) {
+                MetaWord mw;
+                mw.u32 = vmreg;
+                const half2_t sc2 = {mw.h[0], mw.h[0]}, zr2 = {mw.h[1], mw.h[1]};
+                // P[i][k] = values of channels 32*sp + 8*i + k and + 4 of this thread's row as fp16:
+                // code*scale + zero in one fused fp16 operation (the codes are exact integers, so
+                // this is the real value rounded once)
+                half2_t P[4][4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    half2_t h[4];
+                    codes_to_half(vcodes[i], h);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) P[i][k] = __builtin_elementwise_fma(h[k], sc2, zr2);
+                }
+                // Rows 2k and 2k+1 sit four lanes apart.  The even-row thread ends up with channels
+                // 0..15 of both rows, the odd-row thread with channels 16..31, so that each writes
+                // 32-bit words {row 2k, row 2k+1} of the transposed tile.
+                const bool odd = srow & 1;
+                const int col = (srow & ~1) ^ (8 * sp);  // swizzle: channel/32 == sp
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const half2_t lower = P[i][k], upper = P[2 + i][k];
+                        const uint32_t send = __builtin_bit_cast(uint32_t, odd ? lower : upper);
+                        const half2_t got = __builtin_bit_cast(half2_t, (uint32_t)__shfl_xor((int)send, 4));
+                        const half2_t mine = odd ? upper : lower;
+                        const half2_t r0h = odd ? got : mine, r1h = odd ? mine : got;  // rows 2k, 2k+1
+                        const int ch = 32 * sp + (odd ? 16 : 0) + 8 * i + k;
+                        const half2_t w0 = {r0h[0], r1h[0]}, w1 = {r0h[1], r1h[1]};
+                        *reinterpret_cast<half2_t*>(&Vt[ch * LDV + col]) = w0;
+                        *reinterpret_cast<half2_t*>(&Vt[(ch + 4) * LDV + col]) = w1;
+                    }
+            }
+            return;
+        }
         // the writer keeps the run's rows (slots n0 .. n0+c-1) as they come by, in pass 1
         const bool keep = writer && with_v && r0 + KB > a.n0;
 #pragma unroll
@@ -305,8 +515,53 @@ prefill_chunk_kernel(PrefillArgs a) {
     // otherwise:  d[sb][rb][r] = <k_j, q_i> for cache row j = 64*kt + 16*rb + li and query
     //             i = 4*g + r of block sb (a lane holds one cache row: what the counts want).
     // Every K fragment is read from LDS once and used for all SB blocks.
+    // 4-bit: the matrix instructions give sum_c q_c*code_c per group of 64 channels; the score is
+    // scale_0*S_0 + scale_1*S_1 + zero_0*sum(q over group 0) + zero_1*sum(q over group 1) in fp32.
+    float qs0p[SB][4], qs1p[SB][4];  // pass 2: group sums of this lane's four queries per block
+    auto finish_score = [](float s0, float s1, float4_t meta, float q0s, float q1s) {
+        float s = meta[1] * q0s;
+        s = fmaf(meta[3], q1s, s);
+        s = fmaf(meta[0], s0, s);
+        return fmaf(meta[2], s1, s);
+    };
     auto scores = [&](auto transposed, float4_t (&d)[SB][4]) {
         constexpr bool TRANSPOSED = decltype(transposed)::value;
+        if constexpr (I4) {
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) {
+                half8_t kf[4];
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    kf[ks] = *reinterpret_cast<const half8_t*>(&Ks[(16 * rb + li) * LDK + 32 * ks + 8 * g]);
+                float4_t meta[4];  // transposed: rows 4g + r of the block; plain: row li (entry 0)
+                if constexpr (TRANSPOSED) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        meta[r] = *reinterpret_cast<const float4_t*>(&Kmeta[(16 * rb + 4 * g + r) * 4]);
+                } else {
+                    meta[0] = *reinterpret_cast<const float4_t*>(&Kmeta[(16 * rb + li) * 4]);
+                }
+#pragma unroll
+                for (int sb = 0; sb < SB; ++sb) {
+                    float4_t g0 = {0.f, 0.f, 0.f, 0.f}, g1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        if constexpr (TRANSPOSED) {
+                            g0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[ks], qB[sb][ks], g0, 0, 0, 0);
+                            g1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[2 + ks], qB[sb][2 + ks], g1, 0, 0, 0);
+                        } else {
+                            g0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(qB[sb][ks], kf[ks], g0, 0, 0, 0);
+                            g1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(qB[sb][2 + ks], kf[2 + ks], g1, 0, 0, 0);
+                        }
+                    }
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        d[sb][rb][r] = TRANSPOSED ? finish_score(g0[r], g1[r], meta[r], qsum0[sb], qsum1[sb])
+                                                  : finish_score(g0[r], g1[r], meta[0], qs0p[sb][r], qs1p[sb][r]);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int sb = 0; sb < SB; ++sb)
 #pragma unroll
@@ -439,6 +694,10 @@ prefill_chunk_kernel(PrefillArgs a) {
         for (int sb = 0; sb < SB; ++sb) {
             stat_m[WQ * w + 16 * sb + li] = m[sb];
             stat_inv[WQ * w + 16 * sb + li] = invL[sb];
+            if constexpr (I4) {
+                stat_q0[WQ * w + 16 * sb + li] = qsum0[sb];
+                stat_q1[WQ * w + 16 * sb + li] = qsum1[sb];
+            }
         }
     }
     for (int i = tid; i < ntiles * KB; i += 256) cnt_lds[i] = 0;
@@ -461,6 +720,8 @@ prefill_chunk_kernel(PrefillArgs a) {
             if (qbase + r < a.c && stat_lim[si] >= 0 && qbase + r >= a.c - a.ring_bits) qwrites[sb] |= 1u << r;
             qm[sb][r] = stat_m[si];
             qinv[sb][r] = stat_inv[si];
+            qs0p[sb][r] = I4 ? stat_q0[si] : 0.f;
+            qs1p[sb][r] = I4 ? stat_q1[si] : 0.f;
             qlim[sb][r] = stat_lim[si];
             // threshold 1/t (tokens seen at that step) or 1/(rows it sees)
             const long tq = a.thresh_len ? (long)qlim[sb][r] + 1 : a.t0 + qbase + r + 1;
@@ -526,401 +787,6 @@ prefill_chunk_kernel(PrefillArgs a) {
 }
 
 
-// ---------------------------------------------------------------------------------------
-// 4-bit storage (head size 128).  The run's rows are quantised into their slots first (16
-// lanes per row, the same single-operation fp32 arithmetic as the decode kernel, so the
-// codes are identical to what stepping would have stored).  The attention kernel has the
-// structure of prefill_chunk_kernel; what differs is how a tile is staged and how a score
-// is finished:
-//  * keys stay codes: the staged K tile holds the codes as fp16 integers (exact), the matrix
-//    instructions accumulate sum_c q_c*code_c per group of 64 channels, and the score is
-//    scale_0*S_0 + scale_1*S_1 + zero_0*sum(q over group 0) + zero_1*sum(q over group 1)
-//    in fp32, i.e. <q, code*scale + zero> without ever rounding a dequantised key;
-//  * values are dequantised while they are transposed into LDS: fp16(code*scale + zero).
-// Unpacking a word of eight codes with two masks gives the channel pairs (0,4) (1,5) (2,6)
-// (3,7); the staged K tile keeps that order inside every 8 channels and the query operand is
-// permuted once to match.
-// ---------------------------------------------------------------------------------------
-// Quantise 8 consecutive channels held by one lane; the 8 lanes that share a group of 64
-// channels are adjacent (half a DPP row).  Same single-operation fp32 arithmetic as
-// quantise_row, so the codes and meta words are identical; returns the 8 codes packed into one
-// word (channel e in nibble e) and the group's meta word.
-__device__ __forceinline__ uint32_t quantise_octet(const half8_t x, uint32_t& meta_word) {
-    float f[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) f[e] = (float)x[e];
-    float mn = fminf(fminf(fminf(f[0], f[1]), fminf(f[2], f[3])), fminf(fminf(f[4], f[5]), fminf(f[6], f[7])));
-    float mx = fmaxf(fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])), fmaxf(fmaxf(f[4], f[5]), fmaxf(f[6], f[7])));
-    auto dpp = [](float v, auto ctrl) {
-        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v),
-                                                                     decltype(ctrl)::value, 0xF, 0xF, true));
-    };
-    using X1 = std::integral_constant<int, 0xB1>;   // quad_perm [1,0,3,2]
-    using X2 = std::integral_constant<int, 0x4E>;   // quad_perm [2,3,0,1]
-    using HM = std::integral_constant<int, 0x141>;  // row_half_mirror: the other quad of these 8 lanes
-    mn = fminf(mn, dpp(mn, X1{}));
-    mx = fmaxf(mx, dpp(mx, X1{}));
-    mn = fminf(mn, dpp(mn, X2{}));
-    mx = fmaxf(mx, dpp(mx, X2{}));
-    mn = fminf(mn, dpp(mn, HM{}));
-    mx = fmaxf(mx, dpp(mx, HM{}));
-    const float range = __fsub_rn(mx, mn);
-    _Float16 sh = (_Float16)__fdiv_rn(range, 15.0f);
-    float sc = (float)sh;
-    if (sc == 0.0f) {
-        sc = 1.0f;
-        sh = (_Float16)1.0f;
-    }
-    const _Float16 zh = (_Float16)mn;
-    const float z = (float)zh;
-    uint32_t word = 0;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        float c = rintf(__fdiv_rn(__fsub_rn(f[e], z), sc));
-        c = fminf(fmaxf(c, 0.f), 15.f);
-        word |= (uint32_t)c << (4 * e);
-    }
-    MetaWord mw;
-    mw.h[0] = sh;
-    mw.h[1] = zh;
-    meta_word = mw.u32;
-    return word;
-}
-
-// Quantise the run's rows into slots n0.. : 16 lanes per row (8 channels each), 16 rows per
-// workgroup; grid (U, rows/16).
-__global__ void __launch_bounds__(256)
-append_rows_i4_kernel(const _Float16* __restrict__ k, const _Float16* __restrict__ v, long unit_stride,
-                      unsigned char* __restrict__ K, unsigned char* __restrict__ V,
-                      uint32_t* __restrict__ Km, uint32_t* __restrict__ Vm, int32_t* __restrict__ pos,
-                      int C, int n0, int c, int t0) {
-    constexpr int D = 128;
-    const int u = blockIdx.x, l8 = threadIdx.x & 15;
-    int row = blockIdx.y * 16 + (threadIdx.x >> 4);
-    const bool live = row < c;
-    row = live ? row : c - 1;  // idle lanes shadow the last row (the reductions need every lane)
-    const size_t src = (size_t)u * unit_stride + (size_t)row * D + 8 * l8;
-    const size_t slot = (size_t)u * C + n0 + row;
-    const half8_t kk = *reinterpret_cast<const half8_t*>(k + src);
-    const half8_t vv = *reinterpret_cast<const half8_t*>(v + src);
-    uint32_t kmw, vmw;
-    const uint32_t kc = quantise_octet(kk, kmw);
-    const uint32_t vc = quantise_octet(vv, vmw);
-    if (!live) return;
-    reinterpret_cast<uint32_t*>(K + slot * (D / 2))[l8] = kc;
-    reinterpret_cast<uint32_t*>(V + slot * (D / 2))[l8] = vc;
-    if ((l8 & 7) == 0) {
-        Km[slot * (D / 64) + (l8 >> 3)] = kmw;
-        Vm[slot * (D / 64) + (l8 >> 3)] = vmw;
-    }
-    if (l8 == 0) pos[slot] = t0 + row;
-}
-
-// The eight codes of word w as fp16 integers, in the order (n0,n4) (n1,n5) (n2,n6) (n3,n7).
-__device__ __forceinline__ void codes_to_half(uint32_t w, half2_t (&h)[4]) {
-    const uint32_t t = w >> 8;
-    const half2_t k1024 = {(_Float16)1024.f, (_Float16)1024.f};
-    const half2_t k64 = {(_Float16)64.f, (_Float16)64.f};
-    const half2_t sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
-    // (w & mask) | 0x6400 per half is the fp16 number 1024 + code (low nibble) or 1024 + 16*code
-    h[0] = __builtin_bit_cast(half2_t, (w & 0x000F000Fu) | 0x64006400u) - k1024;
-    h[1] = __builtin_bit_cast(half2_t, (w & 0x00F000F0u) | 0x64006400u) * sixteenth - k64;
-    h[2] = __builtin_bit_cast(half2_t, (t & 0x000F000Fu) | 0x64006400u) - k1024;
-    h[3] = __builtin_bit_cast(half2_t, (t & 0x00F000F0u) | 0x64006400u) * sixteenth - k64;
-}
-
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
-prefill_chunk_i4_kernel(PrefillArgs a) {
-    constexpr int D = 128, KB = 64, QB = 64;
-    constexpr int LDK = D + 8, LDV = KB + 4, CB = D / 16;
-    constexpr uint32_t ROWB = D / 2;  // bytes of codes per row
-    __shared__ __align__(16) _Float16 Ks[KB * LDK];
-    __shared__ __align__(16) _Float16 Vt[D * LDV];
-    __shared__ __align__(16) float Kmeta[KB * 4];  // per row: scale, zero of group 0; scale, zero of group 1
-    __shared__ float stat_m[QB], stat_inv[QB], stat_q0[QB], stat_q1[QB];
-    extern __shared__ int cnt_lds[];
-
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int li = lane & 15, g = lane >> 4;
-    const int u = blockIdx.x / a.nqb;
-    const int q0 = (a.nqb - 1 - (int)(blockIdx.x % a.nqb)) * QB;
-    const int qi = q0 + 16 * w + li;
-    const int qc = qi < a.c ? qi : a.c - 1;
-    const int lim = a.n0 + qc;
-    const int q_last = (q0 + QB < a.c ? q0 + QB : a.c) - 1;
-    const int hi = a.n0 + q_last + 1;
-    const int ntiles = (hi + KB - 1) / KB;
-    const int wave_lim = a.n0 + (q0 + 16 * w + 15 < a.c ? q0 + 16 * w + 15 : a.c - 1);
-    const int wave_first_lim = a.n0 + (q0 + 16 * w < a.c ? q0 + 16 * w : a.c - 1);
-
-    const unsigned char* Kb = static_cast<const unsigned char*>(a.K) + (size_t)u * a.C * ROWB;
-    const unsigned char* Vb = static_cast<const unsigned char*>(a.V) + (size_t)u * a.C * ROWB;
-    const uint32_t* Kmb = a.K_meta + (size_t)u * a.C * 2;
-    const uint32_t* Vmb = a.V_meta + (size_t)u * a.C * 2;
-
-    // Query operand: channels 32*ks + 8*g + {0,4,1,5,2,6,3,7}; sums of q over the two groups.
-    half8_t qB[4];
-    float qsum0, qsum1;
-    {
-        const _Float16* qrow = a.q + (size_t)u * a.unit_stride + (size_t)qc * D + 8 * g;
-        float part[4];
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const half8_t x = *reinterpret_cast<const half8_t*>(qrow + 32 * ks);
-            qB[ks] = __builtin_shufflevector(x, x, 0, 4, 1, 5, 2, 6, 3, 7);
-            float acc = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc += (float)x[e];
-            part[ks] = acc;
-        }
-        float s0 = part[0] + part[1], s1 = part[2] + part[3];
-        s0 += __shfl_xor(s0, 16);
-        s0 += __shfl_xor(s0, 32);
-        s1 += __shfl_xor(s1, 16);
-        s1 += __shfl_xor(s1, 32);
-        qsum0 = s0;
-        qsum1 = s1;
-    }
-
-    // Tile staging: thread = (row tid/4, 32 channels starting at 32*(tid%4)).
-    const int srow = tid >> 2, sp = tid & 3;
-    u32x4_t kreg, vreg;
-    uint32_t kmreg, vmreg;
-    auto fetch = [&](int kt, bool with_v) {
-        int grow = kt * KB + srow;
-        grow = grow < hi ? grow : hi - 1;  // stay inside rows that hold data
-        kreg = *reinterpret_cast<const u32x4_t*>(Kb + (size_t)grow * ROWB + sp * 16);
-        kmreg = Kmb[(size_t)grow * 2 + (sp >> 1)];
-        if (with_v) {
-            vreg = *reinterpret_cast<const u32x4_t*>(Vb + (size_t)grow * ROWB + sp * 16);
-            vmreg = Vmb[(size_t)grow * 2 + (sp >> 1)];
-        }
-    };
-    auto stage = [&](bool with_v) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            half2_t h[4];
-            codes_to_half(kreg[i], h);
-            const half4_t lo = __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3);
-            const half4_t hi4 = __builtin_shufflevector(h[2], h[3], 0, 1, 2, 3);
-            *reinterpret_cast<half8_t*>(&Ks[srow * LDK + 32 * sp + 8 * i]) =
-                __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-        }
-        if ((sp & 1) == 0) {
-            MetaWord kw;
-            kw.u32 = kmreg;
-            *reinterpret_cast<float2*>(&Kmeta[srow * 4 + (sp >> 1) * 2]) = make_float2((float)kw.h[0], (float)kw.h[1]);
-        }
-        if (with_v) {
-            MetaWord mw;
-            mw.u32 = vmreg;
-            const half2_t sc2 = {mw.h[0], mw.h[0]}, zr2 = {mw.h[1], mw.h[1]};
-            // P[i][k] = values of channels 32*sp + 8*i + k and + 4 of this thread's row as fp16:
-            // code*scale + zero in one fused fp16 operation (the codes are exact integers, so
-            // this is the real value rounded once)
-            half2_t P[4][4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                half2_t h[4];
-                codes_to_half(vreg[i], h);
-#pragma unroll
-                for (int k = 0; k < 4; ++k) P[i][k] = __builtin_elementwise_fma(h[k], sc2, zr2);
-            }
-            // Rows 2k and 2k+1 sit four lanes apart.  The even-row thread ends up with channels
-            // 0..15 of both rows, the odd-row thread with channels 16..31, so that each writes
-            // 32-bit words {row 2k, row 2k+1} of the transposed tile.
-            const bool odd = srow & 1;
-            const int col = (srow & ~1) ^ (8 * sp);  // swizzle: channel/32 == sp
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const half2_t lower = P[i][k], upper = P[2 + i][k];
-                    const uint32_t send = __builtin_bit_cast(uint32_t, odd ? lower : upper);
-                    const half2_t got = __builtin_bit_cast(half2_t, (uint32_t)__shfl_xor((int)send, 4));
-                    const half2_t mine = odd ? upper : lower;
-                    const half2_t r0 = odd ? got : mine, r1 = odd ? mine : got;  // rows 2k, 2k+1
-                    const int ch = 32 * sp + (odd ? 16 : 0) + 8 * i + k;
-                    const half2_t w0 = {r0[0], r1[0]}, w1 = {r0[1], r1[1]};
-                    *reinterpret_cast<half2_t*>(&Vt[ch * LDV + col]) = w0;
-                    *reinterpret_cast<half2_t*>(&Vt[(ch + 4) * LDV + col]) = w1;
-                }
-        }
-    };
-    // Per group: sum_c q_c*code_c for a 64-row tile against the wave's 16 queries (see
-    // prefill_chunk_kernel for the two orientations).
-    auto code_dots = [&](auto transposed, float4_t (&d0)[4], float4_t (&d1)[4]) {
-        constexpr bool TRANSPOSED = decltype(transposed)::value;
-#pragma unroll
-        for (int rb = 0; rb < 4; ++rb) d0[rb] = d1[rb] = float4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int rb = 0; rb < 4; ++rb) {
-                const half8_t kf = *reinterpret_cast<const half8_t*>(&Ks[(16 * rb + li) * LDK + 32 * ks + 8 * g]);
-                float4_t& d = ks < 2 ? d0[rb] : d1[rb];
-                if constexpr (TRANSPOSED)
-                    d = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qB[ks], d, 0, 0, 0);
-                else
-                    d = __builtin_amdgcn_mfma_f32_16x16x32_f16(qB[ks], kf, d, 0, 0, 0);
-            }
-    };
-    // <q, k> from the two code sums and the row's meta words.
-    // meta = (scale_0, zero_0, scale_1, zero_1) of the row
-    auto finish_score = [](float s0, float s1, float4_t meta, float q0s, float q1s) {
-        float s = meta[1] * q0s;
-        s = fmaf(meta[3], q1s, s);
-        s = fmaf(meta[0], s0, s);
-        return fmaf(meta[2], s1, s);
-    };
-    using Transposed = std::integral_constant<bool, true>;
-    using Plain = std::integral_constant<bool, false>;
-
-    // ---- pass 1 ----------------------------------------------------------------------------
-    const float c2 = a.qk_log2;
-    float m = -INFINITY, lsum = 0.f;
-    float4_t acc[CB];
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb) acc[cb] = float4_t{0.f, 0.f, 0.f, 0.f};
-    fetch(0, true);
-    for (int kt = 0; kt < ntiles; ++kt) {
-        __syncthreads();
-        stage(true);
-        __syncthreads();
-        if (kt + 1 < ntiles) fetch(kt + 1, true);
-        if (kt * KB > wave_lim) continue;
-        float4_t d[4], d1[4];
-        code_dots(Transposed{}, d, d1);
-#pragma unroll
-        for (int rb = 0; rb < 4; ++rb) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float4_t meta = *reinterpret_cast<const float4_t*>(&Kmeta[(16 * rb + 4 * g + r) * 4]);
-                d[rb][r] = finish_score(d[rb][r], d1[rb][r], meta, qsum0, qsum1);
-            }
-        }
-        if (kt * KB + KB - 1 > wave_first_lim) {
-            const int rel = lim - (kt * KB + 4 * g);
-#pragma unroll
-            for (int rb = 0; rb < 4; ++rb)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) d[rb][r] = (16 * rb + r <= rel) ? d[rb][r] : -INFINITY;
-        }
-        float tmax = fmaxf(fmaxf(d[0][0], d[0][1]), fmaxf(d[0][2], d[0][3]));
-#pragma unroll
-        for (int rb = 1; rb < 4; ++rb)
-            tmax = fmaxf(tmax, fmaxf(fmaxf(d[rb][0], d[rb][1]), fmaxf(d[rb][2], d[rb][3])));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float m_new = fmaxf(m, tmax * c2);
-        if (__builtin_amdgcn_ballot_w64(m_new != m) != 0ull) {
-            const float alpha = fast_exp2(m - m_new);
-            lsum *= alpha;
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb) acc[cb] *= alpha;
-            m = m_new;
-        }
-        half4_t ph[4];
-#pragma unroll
-        for (int rb = 0; rb < 4; ++rb) {
-            float4_t p;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                p[r] = fast_exp2(fmaf(d[rb][r], c2, -m));
-                lsum += p[r];
-            }
-            ph[rb] = __builtin_convertvector(p, half4_t);
-        }
-#pragma unroll
-        for (int kp = 0; kp < 2; ++kp) {
-            const half8_t B01 = __builtin_shufflevector(ph[2 * kp], ph[2 * kp + 1], 0, 1, 2, 3, 4, 5, 6, 7);
-            const half8_t B10 = __builtin_shufflevector(ph[2 * kp + 1], ph[2 * kp], 0, 1, 2, 3, 4, 5, 6, 7);
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb) {
-                const int swz = 8 * (cb >> 1);
-                const _Float16* vrow = &Vt[(16 * cb + li) * LDV + (((32 * kp + 4 * g) ^ swz) & ~16)];
-                const half4_t a0 = *reinterpret_cast<const half4_t*>(vrow);
-                const half4_t a1 = *reinterpret_cast<const half4_t*>(vrow + 16);
-                const half8_t A = __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7);
-                acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(A, (swz & 16) ? B10 : B01, acc[cb], 0, 0, 0);
-            }
-        }
-    }
-    const bool pass2 = a.counted || a.probs;
-    if (pass2) fetch(0, false);
-    lsum += __shfl_xor(lsum, 16);
-    lsum += __shfl_xor(lsum, 32);
-    const float invL = 1.0f / lsum;
-    if (a.out && qi < a.c) {
-        _Float16* orow = a.out + (size_t)u * a.out_unit_stride + (size_t)qi * D + 4 * g;
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-            *reinterpret_cast<half4_t*>(orow + 16 * cb) = __builtin_convertvector(acc[cb] * invL, half4_t);
-    }
-    if (!pass2) return;
-
-    // ---- pass 2 ----------------------------------------------------------------------------
-    if (g == 0) {
-        stat_m[16 * w + li] = m;
-        stat_inv[16 * w + li] = invL;
-        stat_q0[16 * w + li] = qsum0;
-        stat_q1[16 * w + li] = qsum1;
-    }
-    for (int i = tid; i < ntiles * KB; i += 256) cnt_lds[i] = 0;
-    __syncthreads();
-    float qm[4], qinv[4], qtau[4], qs0[4], qs1[4];
-    const int qbase = q0 + 16 * w + 4 * g;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        qm[r] = stat_m[16 * w + 4 * g + r];
-        qinv[r] = stat_inv[16 * w + 4 * g + r];
-        qs0[r] = stat_q0[16 * w + 4 * g + r];
-        qs1[r] = stat_q1[16 * w + 4 * g + r];
-        const long tq = a.thresh_len ? (long)a.n0 + qbase + r + 1 : a.t0 + qbase + r + 1;
-        qtau[r] = qbase + r < a.c ? __fdiv_rn(1.0f, (float)tq) : -1.0f;
-    }
-    float* pbase = a.probs ? a.probs + (size_t)u * a.probs_unit_stride + (size_t)qbase * a.C : nullptr;
-    for (int kt = 0; kt < ntiles; ++kt) {
-        __syncthreads();
-        stage(false);
-        __syncthreads();
-        if (kt + 1 < ntiles) fetch(kt + 1, false);
-        if (kt * KB > wave_lim) continue;
-        float4_t d[4], d1[4];
-        code_dots(Plain{}, d, d1);
-        const bool diag = kt * KB + KB - 1 > wave_first_lim;
-#pragma unroll
-        for (int rb = 0; rb < 4; ++rb) {
-            const int j = kt * KB + 16 * rb + li;
-            const int rel = j - a.n0 - qbase;
-            const float4_t meta = *reinterpret_cast<const float4_t*>(&Kmeta[(16 * rb + li) * 4]);
-            float4_t p;
-            int cnt = 0;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float s = finish_score(d[rb][r], d1[rb][r], meta, qs0[r], qs1[r]);
-                p[r] = fast_exp2(fmaf(s, c2, -qm[r])) * qinv[r];
-                bool low = p[r] < qtau[r];
-                if (diag) low = low && rel <= r;
-                cnt += low ? 1 : 0;
-            }
-            if (cnt) atomicAdd(&cnt_lds[j], cnt);
-            if (pbase) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (qbase + r < a.c && rel <= r) pbase[(size_t)r * a.C + j] = p[r];
-            }
-        }
-    }
-    __syncthreads();
-    if (!a.counted) return;
-    uint32_t* cw = reinterpret_cast<uint32_t*>(a.cnt + (size_t)u * a.cnt_unit_stride);
-    for (int i = tid; 2 * i < hi; i += 256) {
-        const uint32_t word = (uint32_t)cnt_lds[2 * i] | ((uint32_t)cnt_lds[2 * i + 1] << 16);
-        if (word) atomicAdd(&cw[i], word);
-    }
-}
-
 }  // namespace
 
 hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t stream) {
@@ -969,16 +835,18 @@ hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t
     a.ring_bits = L.W32 ? L.w : (1 << 30);
     const size_t lds = (size_t)L.C * sizeof(int);
     const unsigned grid = (unsigned)L.U * (unsigned)a.nqb;
-    if (i4)
-        prefill_chunk_i4_kernel<<<grid, 256, lds, stream>>>(a);
+    if (i4 && wide)
+        prefill_chunk_kernel<128, true, 2, true><<<grid, 256, lds, stream>>>(a);
+    else if (i4)
+        prefill_chunk_kernel<128, true, 1, true><<<grid, 256, lds, stream>>>(a);
     else if (L.d == 64 && wide)
-        prefill_chunk_kernel<64, true, 2><<<grid, 256, lds, stream>>>(a);
+        prefill_chunk_kernel<64, true, 2, false><<<grid, 256, lds, stream>>>(a);
     else if (L.d == 64)
-        prefill_chunk_kernel<64, true, 1><<<grid, 256, lds, stream>>>(a);
+        prefill_chunk_kernel<64, true, 1, false><<<grid, 256, lds, stream>>>(a);
     else if (wide)
-        prefill_chunk_kernel<128, true, 2><<<grid, 256, lds, stream>>>(a);
+        prefill_chunk_kernel<128, true, 2, false><<<grid, 256, lds, stream>>>(a);
     else
-        prefill_chunk_kernel<128, true, 1><<<grid, 256, lds, stream>>>(a);
+        prefill_chunk_kernel<128, true, 1, false><<<grid, 256, lds, stream>>>(a);
     return hipGetLastError();
 }
 
@@ -1006,8 +874,8 @@ hipError_t launch_recompute_record(const Layout& L, const ReplayArgs& r, hipStre
     a.unit_stride = (long)L.w * L.d;
     a.K = L.K;
     a.V = L.V;
-    a.K_meta = nullptr;
-    a.V_meta = nullptr;
+    a.K_meta = static_cast<const uint32_t*>(L.K_meta);
+    a.V_meta = static_cast<const uint32_t*>(L.V_meta);
     a.out = nullptr;
     a.out_unit_stride = 0;
     a.probs = r.probs;
@@ -1017,7 +885,7 @@ hipError_t launch_recompute_record(const Layout& L, const ReplayArgs& r, hipStre
     a.C = L.C;
     a.n0 = 0;
     a.c = W;
-    const bool wide = W > 64;
+    const bool wide = L.kv_dtype != KV_I4G64 && W > 64;
     a.nqb = wide ? (W + 127) / 128 : (W + 63) / 64;
     a.t0 = r.t - W;
     a.counted = 1;
@@ -1034,14 +902,16 @@ hipError_t launch_recompute_record(const Layout& L, const ReplayArgs& r, hipStre
     a.ring_bits = 1 << 30;
     const size_t lds = (size_t)L.C * sizeof(int);
     const unsigned grid = (unsigned)L.U * (unsigned)a.nqb;
-    if (L.d == 64 && wide)
-        prefill_chunk_kernel<64, false, 2><<<grid, 256, lds, stream>>>(a);
+    if (L.kv_dtype == KV_I4G64)
+        prefill_chunk_kernel<128, false, 1, true><<<grid, 256, lds, stream>>>(a);
+    else if (L.d == 64 && wide)
+        prefill_chunk_kernel<64, false, 2, false><<<grid, 256, lds, stream>>>(a);
     else if (L.d == 64)
-        prefill_chunk_kernel<64, false, 1><<<grid, 256, lds, stream>>>(a);
+        prefill_chunk_kernel<64, false, 1, false><<<grid, 256, lds, stream>>>(a);
     else if (wide)
-        prefill_chunk_kernel<128, false, 2><<<grid, 256, lds, stream>>>(a);
+        prefill_chunk_kernel<128, false, 2, false><<<grid, 256, lds, stream>>>(a);
     else
-        prefill_chunk_kernel<128, false, 1><<<grid, 256, lds, stream>>>(a);
+        prefill_chunk_kernel<128, false, 1, false><<<grid, 256, lds, stream>>>(a);
     return hipGetLastError();
 }
 

@@ -213,6 +213,9 @@ RING_PREFILL = [
     _wl("pf-ring-short-window", 1, 2, 128, KV_F16, 300, 60, 100, 8, 5, 48),        # w far below a query block
     _wl("pf-ring-window-33", 1, 3, 128, KV_F16, 350, 80, 120, 8, 33, 64, 0.1),    # w < run length, odd word split
     _wl("pf-ring-long-window", 1, 2, 64, KV_F16, 260, 90, 77, 7, 1000, 17, 0.1),  # w beyond everything seen
+    _wl("pf-ring-i4", 1, 4, 128, KV_I4G64, 400, 70, 150, 8, 100, 48, 0.05),        # 4-bit rows, ring record
+    _wl("pf-ring-i4-paper", 1, 2, 128, KV_I4G64, 700, 300, 400, 10, 400, 200, 0.05),
+    _wl("pf-ring-i4-window-33", 2, 2, 128, KV_I4G64, 350, 80, 120, 8, 33, 64, 0.1),
 ]
 
 
@@ -261,6 +264,9 @@ RECOMPUTE = [
     _wl("re-paper-params", 1, 3, 128, KV_F16, 300, 400, 200, 10, 400, 100, 0.05),  # w = 400: 7 query blocks
     _wl("re-window-longer-than-cache", 1, 2, 128, KV_F16, 90, 80, 20, 2, 64, 8),   # old steps see few rows
     _wl("re-drop-one", 1, 2, 64, KV_F16, 40, 30, 24, 1, 5, 1),
+    _wl("re-i4", 1, 4, 128, KV_I4G64, 150, 100, 100, 7, 32, 16, 0.05),             # 4-bit rows replayed from their codes
+    _wl("re-i4-paper-params", 1, 2, 128, KV_I4G64, 300, 400, 200, 10, 400, 100, 0.05),
+    _wl("re-i4-window-longer-than-cache", 2, 2, 128, KV_I4G64, 90, 80, 20, 2, 64, 8),
 ]
 
 
@@ -275,10 +281,11 @@ def test_recomputed_record_matches_oracle(wl, thresh):
     assert st["steps"] == wl.total and st["compressions"] >= 3
 
 
-def test_recomputed_record_after_dense_prefill():
+@pytest.mark.parametrize("kv", [KV_F16, KV_I4G64], ids=["f16", "i4"])
+def test_recomputed_record_after_dense_prefill(kv):
     """The queries of a prompt that went through sc_prefill are kept too: the compressions
     during the decode steps that follow replay them."""
-    wl = _wl("re-prefill", 1, 4, 128, KV_F16, 90, 120, 100, 8, 64, 32, 0.05)  # prompt ends before the trigger
+    wl = _wl("re-prefill", 1, 4, 128, kv, 90, 120, 100, 8, 64, 32, 0.05)  # prompt ends before the trigger
     run = ParityRun(wl, record_mode=B.SC_RECORD_RECOMPUTE)
     run.prefill(wl.prompt)
     st = run.run()
@@ -288,8 +295,9 @@ def test_recomputed_record_after_dense_prefill():
 @pytest.mark.parametrize("kv,d,window,record", [
     (KV_F16, 128, B.SC_WINDOW_AUTO, B.SC_RECORD_ONLINE), (KV_F32, 64, B.SC_WINDOW_AUTO, B.SC_RECORD_ONLINE),
     (KV_I4G64, 128, B.SC_WINDOW_AUTO, B.SC_RECORD_ONLINE), (KV_I4G64, 64, B.SC_WINDOW_AUTO, B.SC_RECORD_ONLINE),
-    (KV_F16, 128, B.SC_WINDOW_RING, B.SC_RECORD_ONLINE), (KV_F16, 128, B.SC_WINDOW_AUTO, B.SC_RECORD_RECOMPUTE)],
-    ids=["f16", "f32", "i4-d128", "i4-d64", "f16-ring", "f16-recompute"])
+    (KV_F16, 128, B.SC_WINDOW_RING, B.SC_RECORD_ONLINE), (KV_F16, 128, B.SC_WINDOW_AUTO, B.SC_RECORD_RECOMPUTE),
+    (KV_I4G64, 128, B.SC_WINDOW_AUTO, B.SC_RECORD_RECOMPUTE)],
+    ids=["f16", "f32", "i4-d128", "i4-d64", "f16-ring", "f16-recompute", "i4-recompute"])
 def test_decode_without_dumps_leaves_the_same_state(kv, d, window, record):
     """The benchmark's path: no `probs_out`, no `evicted_out`.  Outputs, records, positions and
     stored rows must be exactly those of the instrumented calls the parity tests compare."""

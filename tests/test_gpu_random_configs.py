@@ -96,3 +96,37 @@ def test_random_dense_prefill_matches_oracle(seed):
     run.prefill(wl.prompt)
     st = run.run()
     assert st["steps"] == wl.total
+
+
+def _draw_i4_variants(seed):
+    """4-bit rows of 128 channels with the records that are not bucket counters: the exact ring
+    (dense prompt runs write bits) or the record rebuilt at compression time."""
+    rng = np.random.default_rng(9000 + seed)
+    m = int(rng.integers(16, 160))
+    budget = int(rng.integers(2 * m, 2 * m + 300))
+    trigger = int(rng.choice([B.SC_TRIGGER_HARD_CAP, B.SC_TRIGGER_HIGH_WATER]))
+    n_trig = budget + 1 if trigger == B.SC_TRIGGER_HARD_CAP else budget + m
+    r = int(rng.integers(1, n_trig - m))
+    w = int(rng.integers(1, 300))
+    thresh = int(rng.choice([B.SC_THRESH_INV_POS, B.SC_THRESH_INV_LEN]))
+    if rng.integers(0, 2) == 0:
+        record, window = B.SC_RECORD_ONLINE, B.SC_WINDOW_RING
+        prompt = int(rng.integers(2 * m, n_trig + 4 * m))
+    else:
+        record, window = B.SC_RECORD_RECOMPUTE, B.SC_WINDOW_AUTO
+        prompt = int(rng.integers(2 * m, n_trig))
+    decode = int(rng.integers(m + 2, 2 * m + 30))
+    wl = Workload("i4var-%d" % seed, 900 + seed, int(rng.integers(1, 3)), int(rng.integers(1, 4)), 128,
+                  KV_I4G64, prompt, decode, budget, r, w, m, float(rng.choice([0.0, 0.05])))
+    return wl, trigger, thresh, window, record
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_random_4bit_ring_and_recompute_match_oracle(seed):
+    wl, trigger, thresh, window, record = _draw_i4_variants(seed)
+    print("\n", wl, "trigger", trigger, "thresh", thresh, "window", window, "record", record, flush=True)
+    run = ParityRun(wl, trigger=trigger, thresh=thresh, window_mode=window, record_mode=record)
+    assert any(dense for _, dense, _ in B.sc_prefill_plan(run.cfg, wl.prompt))
+    run.prefill(wl.prompt)
+    st = run.run()
+    assert st["steps"] == wl.total
