@@ -49,7 +49,25 @@ def algorithmic_bytes(wl, n: int) -> int:
         row, e_io = d * 2, 2
     else:
         row, e_io = d // 2 + (d // 64) * 4, 2
+    if isinstance(n, (list, tuple)):  # ragged batch: resident rows per sequence
+        return wl.heads * sum(nb * (2 * row + 4) + 4 * d * e_io for nb in n)
     return wl.units * (n * (2 * row + 4) + 4 * d * e_io)
+
+
+def ragged_prompt_lengths(wl):
+    """The length mix of the ragged variant: prompts spread evenly from a quarter of the
+    workload's prompt length up to all of it (sequence 0 the shortest), so that the sequences sit
+    at different points of the compression cycle and see different thresholds."""
+    lo, hi = wl.prompt // 4, wl.prompt
+    if wl.batch == 1:
+        return [hi]
+    return [lo + (hi - lo) * b // (wl.batch - 1) for b in range(wl.batch)]
+
+
+def rows_after_step(wl, t: int) -> int:
+    """Resident rows of a sequence right after its step t (hard-cap trigger)."""
+    n_trig, m = wl.budget + 1, wl.drop
+    return t if t <= n_trig else n_trig - m + (t - n_trig - 1) % m + 1
 
 
 def cpu_baseline(wl, sample_units: int, sample_steps: int) -> dict:
@@ -208,6 +226,9 @@ def main() -> int:
     ap.add_argument("--record", choices=("online", "recompute"), default="online",
                     help="importance record kept during the steps (headline) or rebuilt at each "
                          "compression by replaying the last w queries (fp16 workloads)")
+    ap.add_argument("--ragged", action="store_true",
+                    help="decode phase with prompts of different lengths (every sequence on its own "
+                         "clock: sc_prefill_ragged / sc_decode_step_ragged / sc_compress_ragged)")
     ap.add_argument("--no-events", action="store_true", help="skip the per-launch HIP events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=512)
@@ -245,8 +266,12 @@ def main() -> int:
     q, k, v = (torch.from_numpy(a).to(dev) for a in streams(wl, threads=16))
     caches = [B.BudgetCache(cfg, dev) for _ in range(R)]
     outs = [torch.empty(U, d, dtype=caches[0].io_dtype, device=dev) for _ in range(R)]
+    plens = ragged_prompt_lengths(wl) if args.ragged else None
     for c in caches:
-        c.prefill(q, k, v, wl.prompt, T * d, None)
+        if args.ragged:
+            c.prefill_ragged(q, k, v, plens, T * d, None)
+        else:
+            c.prefill(q, k, v, wl.prompt, T * d, None)
     torch.cuda.synchronize()
 
     cursor = [wl.prompt] * R
@@ -257,6 +282,12 @@ def main() -> int:
         s = cursor[r]
         cursor[r] = s + 1
         c = caches[r]
+        if args.ragged:  # all sequences take part, each at its own t_b and n_b
+            due = c.decode_step_ragged(q[:, s], k[:, s], v[:, s], outs[r], None, in_stride=T * d)
+            n_log.append([rows_after_step(wl, p + s - wl.prompt + 1) for p in plens])
+            if due:
+                c.compress_ragged()
+            return 1 if due else 0
         due = c.decode_step(q[:, s], k[:, s], v[:, s], outs[r], None, in_stride=T * d)
         n_log.append(c.n)
         if due:
@@ -322,16 +353,18 @@ def main() -> int:
             "prompt": wl.prompt, "decode": wl.decode, "budget": wl.budget, "recent": wl.recent,
             "history": wl.history, "drop": wl.drop, "trigger": "hard_cap", "window": args.window, "record": args.record,
             "cache_instances_round_robin": R, "compressions_in_timed_region": compress_events,
-            "resident_rows_avg": sum(n_log) / len(n_log),
+            "resident_rows_avg": (sum(sum(x) / len(x) for x in n_log) if args.ragged else sum(n_log)) / len(n_log),
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": None if achieved is None else achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if R == 3 else None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if R == 3 and not args.ragged else None,
             "kernel": kernel_name, "kernel_ms_avg": kern_ms, "algorithmic_bytes_per_launch": alg,
         },
     }
-    if not args.no_cpu_baseline:
+    if args.ragged:
+        res["config"]["ragged_prompt_lengths"] = plens
+    if not args.no_cpu_baseline and not args.ragged:
         res["cpu_baseline"] = cpu_baseline(wl, args.cpu_units, args.cpu_steps)
     print(json.dumps(res))
     return 0

@@ -11,9 +11,10 @@
  *     rows with the largest record are dropped; survivors are compacted, n <- n - m.
  *
  * General conventions
- *   Units.     A unit is one (sequence, head) pair; U = batch*heads.  All units advance in
- *              lock step, so the counters t (tokens seen) and n (resident rows) are host
- *              integers and no call ever reads device memory back.
+ *   Units.     A unit is one (sequence, head) pair; U = batch*heads.  By default all units
+ *              advance in lock step; with the *_ragged calls every sequence has its own
+ *              counters.  Either way the counters t (tokens seen) and n (resident rows) are
+ *              host integers and no call ever reads device memory back.
  *   Memory.    Every pointer marked "device" is device memory owned by the caller and must
  *              stay valid until the work enqueued by the call has run.  The library never
  *              allocates or frees device memory; the cache lives in a caller-provided
@@ -206,8 +207,61 @@ sc_status sc_prefill(sc_cache *c, const void *q, const void *k, const void *v, i
 sc_status sc_prefill_plan(const sc_config *cfg, int32_t prompt_len, int32_t mode, int32_t max_runs,
                           int32_t *run_len, int32_t *run_dense, int32_t *run_compress, int32_t *n_runs);
 
-/* Resident rows n and tokens seen t (either pointer may be NULL). */
+/* Resident rows n and tokens seen t (either pointer may be NULL).  SC_ERR_STATE once the handle
+ * keeps per-sequence counters (see sc_cache_len_seq). */
 sc_status sc_cache_len(const sc_cache *c, int32_t *n, int64_t *t);
+
+/* ---- Ragged batches -------------------------------------------------------------------------
+ * Alg. 1 keeps its counters per sequence: prompts of different lengths, or sequences that stop
+ * generating at different steps, give every sequence b its own t_b and n_b, hence its own
+ * threshold 1/t_b (Alg. 2), its own place in the history window and its own steps at which a
+ * compression is due.  The three calls below run the same kernels with those quantities taken
+ * per sequence (a device table of one integer per sequence, rewritten only when a sequence
+ * joins, leaves or is prefilled); all sequences of a call still share one launch.
+ * The first *_ragged call switches the handle to per-sequence counters (SC_ERR_FULL if a
+ * lock-step compression is still due); from then on the lock-step calls (sc_decode_step,
+ * sc_compress, sc_prefill, sc_cache_len, sc_diag_kept_mass) return SC_ERR_STATE until
+ * sc_cache_reset.  SC_RECORD_RECOMPUTE is not offered for ragged batches (SC_ERR_UNSUPPORTED). */
+
+/* Host only: the resident rows of a sequence right after its step t (t >= 1, counting the row
+ * that step appended, before the compression that may then be due) and whether a compression is
+ * due after it, given that every due compression was carried out (Alg. 1).  This closed form is
+ * what the kernels evaluate per sequence for ragged batches.  Either pointer may be NULL. */
+sc_status sc_schedule_rows(const sc_config *cfg, int64_t t, int32_t *rows, int32_t *due);
+
+/* Prompts of different lengths: sequence b streams its first prompt_len[b] positions through
+ * Alg. 1 exactly as sc_prefill does for a whole batch (consecutive sequences of equal length
+ * share their launches).  Sequences with prompt_len[b] == 0 are left alone; the others must be
+ * empty (SC_ERR_STATE).
+ *   prompt_len : host int32 [batch]
+ *   q, k, v    : device, [U][>= max prompt_len][head_dim], units `unit_stride` elements apart
+ *                (0 = max prompt_len * head_dim)
+ *   out        : device dense [U][max prompt_len][head_dim] or NULL; rows past a sequence's
+ *                prompt are untouched
+ *   probs_out  : device fp32 [U][max prompt_len][capacity] or NULL, rows as in sc_prefill */
+sc_status sc_prefill_ragged(sc_cache *c, const void *q, const void *k, const void *v,
+                            const int32_t *prompt_len, int64_t unit_stride, void *out, float *probs_out,
+                            int32_t mode, void *stream);
+
+/* One decode step of the sequences with active[b] != 0 (all when active is NULL; at least one),
+ * each at its own t_b and n_b; arguments as in sc_decode_step.  Units of idle sequences are
+ * neither read nor written (q/k_new/v_new/out/probs_out rows included).
+ *   active : host uint8 [batch] or NULL
+ *   n_due  : host int or NULL; receives the number of sequences whose cache has reached its
+ *            trigger size: when it is not 0 the caller must call sc_compress_ragged before the
+ *            next step
+ * SC_ERR_FULL if a compression is due for any sequence. */
+sc_status sc_decode_step_ragged(sc_cache *c, const void *q, const void *k_new, const void *v_new,
+                                int64_t in_stride, void *out, float *probs_out, const uint8_t *active,
+                                int32_t *n_due, void *stream);
+
+/* Alg. 2 on the units of every sequence that is due (one launch pair for all of them).
+ *   evicted_out : device int32 [U][m] or NULL; rows of sequences that were not due are untouched
+ * SC_ERR_STATE when no sequence is due. */
+sc_status sc_compress_ragged(sc_cache *c, int32_t *evicted_out, void *stream);
+
+/* Resident rows and tokens seen of sequence b (works for lock-step handles too). */
+sc_status sc_cache_len_seq(const sc_cache *c, int32_t b, int32_t *n, int64_t *t);
 
 /* Device pointers into the workspace, for inspection (any pointer may be NULL):
  *   K, V    : [U][capacity] rows; F32/F16: head_dim elements; I4G64: head_dim/2 bytes of

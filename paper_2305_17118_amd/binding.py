@@ -26,6 +26,8 @@ EXPORTS = (
     "sc_cache_destroy",
     "sc_decode_step", "sc_compress", "sc_prefill", "sc_prefill_plan", "sc_cache_len", "sc_cache_view", "sc_status_str",
     "sc_diag_persistence", "sc_diag_kept_mass",
+    "sc_prefill_ragged", "sc_decode_step_ragged", "sc_compress_ragged", "sc_cache_len_seq",
+    "sc_schedule_rows",
 )
 
 
@@ -72,6 +74,11 @@ def lib():
     l.sc_cache_view.argtypes = [vp] + [C.POINTER(vp)] * 6 + [i32p, i32p]
     l.sc_diag_persistence.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int32, vp, vp]
     l.sc_diag_kept_mass.argtypes = [vp, vp, C.c_int64, vp, vp]
+    l.sc_prefill_ragged.argtypes = [vp, vp, vp, vp, i32p, C.c_int64, vp, vp, C.c_int32, vp]
+    l.sc_decode_step_ragged.argtypes = [vp, vp, vp, vp, C.c_int64, vp, vp, C.POINTER(C.c_uint8), i32p, vp]
+    l.sc_compress_ragged.argtypes = [vp, vp, vp]
+    l.sc_cache_len_seq.argtypes = [vp, C.c_int32, i32p, i64p]
+    l.sc_schedule_rows.argtypes = [cfgp, C.c_int64, i32p, i32p]
     l.sc_status_str.argtypes = [C.c_int]
     l.sc_status_str.restype = C.c_char_p
     for name in EXPORTS:
@@ -169,6 +176,42 @@ def sc_cache_len(handle):
     return n.value, t.value
 
 
+def sc_schedule_rows(cfg: sc_config, t: int):
+    """-> (rows right after step t, compression due after it)"""
+    n, due = C.c_int32(), C.c_int32()
+    _check(lib().sc_schedule_rows(C.byref(cfg), int(t), C.byref(n), C.byref(due)), "sc_schedule_rows")
+    return n.value, bool(due.value)
+
+
+def sc_cache_len_seq(handle, b: int):
+    """-> (n_b, t_b)"""
+    n, t = C.c_int32(), C.c_int64()
+    _check(lib().sc_cache_len_seq(handle, int(b), C.byref(n), C.byref(t)), "sc_cache_len_seq")
+    return n.value, t.value
+
+
+def sc_prefill_ragged(handle, q_ptr, k_ptr, v_ptr, prompt_len, unit_stride, out_ptr=None, probs_ptr=None,
+                      mode=SC_PREFILL_AUTO, stream=0) -> None:
+    """prompt_len: one length per sequence (0 = leave the sequence alone)."""
+    arr = (C.c_int32 * len(prompt_len))(*[int(x) for x in prompt_len])
+    _check(lib().sc_prefill_ragged(handle, q_ptr, k_ptr, v_ptr, arr, int(unit_stride), out_ptr, probs_ptr,
+                                   int(mode), stream), "sc_prefill_ragged")
+
+
+def sc_decode_step_ragged(handle, q_ptr, k_ptr, v_ptr, in_stride, out_ptr, probs_ptr=None, active=None,
+                          stream=0) -> int:
+    """active: one flag per sequence or None (all).  -> number of sequences now due."""
+    arr = None if active is None else (C.c_uint8 * len(active))(*[1 if x else 0 for x in active])
+    due = C.c_int32(0)
+    _check(lib().sc_decode_step_ragged(handle, q_ptr, k_ptr, v_ptr, int(in_stride), out_ptr, probs_ptr, arr,
+                                       C.byref(due), stream), "sc_decode_step_ragged")
+    return due.value
+
+
+def sc_compress_ragged(handle, evicted_ptr=None, stream=0) -> None:
+    _check(lib().sc_compress_ragged(handle, evicted_ptr, stream), "sc_compress_ragged")
+
+
 def sc_cache_view(handle):
     """-> dict of raw device addresses plus capacity and buckets"""
     ptrs = [C.c_void_p() for _ in range(6)]
@@ -251,6 +294,25 @@ class BudgetCache:
         sc_prefill(self.handle, q.data_ptr(), k.data_ptr(), v.data_ptr(), prompt_len, unit_stride,
                    None if out is None else out.data_ptr(),
                    None if probs_out is None else probs_out.data_ptr(), mode, self._stream())
+
+    # -- ragged batches: every sequence on its own clock --
+    def len_seq(self, b: int):
+        return sc_cache_len_seq(self.handle, b)
+
+    def prefill_ragged(self, q, k, v, prompt_len, unit_stride=0, out=None, probs_out=None,
+                       mode=SC_PREFILL_AUTO) -> None:
+        sc_prefill_ragged(self.handle, q.data_ptr(), k.data_ptr(), v.data_ptr(), prompt_len, unit_stride,
+                          None if out is None else out.data_ptr(),
+                          None if probs_out is None else probs_out.data_ptr(), mode, self._stream())
+
+    def decode_step_ragged(self, q, k_new, v_new, out, probs_out=None, in_stride=0, active=None) -> int:
+        return sc_decode_step_ragged(self.handle, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(), in_stride,
+                                     out.data_ptr(), None if probs_out is None else probs_out.data_ptr(),
+                                     active, self._stream())
+
+    def compress_ragged(self, evicted_out=None) -> None:
+        sc_compress_ragged(self.handle, None if evicted_out is None else evicted_out.data_ptr(),
+                           self._stream())
 
     def _typed(self, key, dtype, shape):
         """A torch view (no copy) of one of the cache's arrays inside the workspace."""

@@ -51,13 +51,20 @@ __device__ __forceinline__ void find_cut_bin(const int* hist, int* scan, int nee
     __syncthreads();
 }
 
+// Ragged batches: whether the sequence of unit u stands at its trigger size after the latest step.
+__device__ __forceinline__ bool seq_due(const SeqSched& s, int u) {
+    const int off = s.off[u / s.heads];
+    return off != kSeqIdle && sched_due((long)off + s.step, s.n_trig, s.m);
+}
+
 // One workgroup per unit.  Writes srcmap[u][i] = source slot of the row that ends in slot i
 // (i < n-m), first[u] = first slot whose row moves, and optionally the ascending list of
 // evicted slots.
 __global__ void __launch_bounds__(SEL_THREADS)
 select_evict_kernel(const uint16_t* __restrict__ cnt, int32_t* __restrict__ srcmap,
                     int32_t* __restrict__ first, int32_t* __restrict__ evicted, int n, int C, int E,
-                    int W32, int r, int m) {
+                    int W32, int r, int m, SeqSched seq) {
+    if (seq.off && !seq_due(seq, blockIdx.x)) return;  // ragged batch: this unit's sequence is not due
     extern __shared__ int smem[];
     int* I = smem;            // [C] record of every slot
     int* hist = I + C;        // [256]
@@ -170,6 +177,7 @@ struct CompactArgs {
     int meta_words;    // 32-bit words of meta per row (0 when not 4-bit)
     int n_old, n_new;
     int zero_bucket;
+    SeqSched seq;
 };
 
 // grid (U, 3): part 0 moves K (+K_meta), part 1 moves V (+V_meta), part 2 moves positions and
@@ -177,6 +185,13 @@ struct CompactArgs {
 // epoch counts into.
 __global__ void __launch_bounds__(256) compact_kernel(CompactArgs a) {
     const int u = blockIdx.x, part = blockIdx.y;
+    if (a.seq.off) {  // ragged batch: only due sequences, each clearing the bucket its next epoch counts into
+        if (!seq_due(a.seq, u)) return;
+        if (a.E) {
+            const long ep = sched_epoch((long)a.seq.off[u / a.seq.heads] + a.seq.step, a.seq.n_trig, a.seq.m) + 1;
+            a.zero_bucket = (int)(((ep % a.E) + a.E) % a.E);
+        }
+    }
     const int32_t* map = a.srcmap + (size_t)u * a.C;
     const int first = a.first[u];
     if (part < 2) {
@@ -206,12 +221,33 @@ __global__ void __launch_bounds__(256) compact_kernel(CompactArgs a) {
     }
 }
 
+// The per-sequence table travels as kernel arguments (no host buffer has to outlive the call).
+struct SeqChunk {
+    int32_t v[256];
+};
+
+__global__ void __launch_bounds__(256) write_seq_table_kernel(int32_t* __restrict__ dst, SeqChunk c, int count) {
+    if ((int)threadIdx.x < count) dst[threadIdx.x] = c.v[threadIdx.x];
+}
+
 }  // namespace
+
+hipError_t launch_write_seq_table(int32_t* dst, const int32_t* host_values, int count, hipStream_t stream) {
+    for (int base = 0; base < count; base += 256) {
+        SeqChunk c;
+        const int k = count - base < 256 ? count - base : 256;
+        for (int i = 0; i < 256; ++i) c.v[i] = i < k ? host_values[base + i] : kSeqIdle;
+        write_seq_table_kernel<<<1, 256, 0, stream>>>(dst + base, c, k);
+        const hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
+    return hipSuccess;
+}
 
 hipError_t launch_compress(const Layout& L, const CompressArgs& c, hipStream_t stream) {
     const size_t lds = ((size_t)L.C + 512 + SEL_WAVES + 2) * sizeof(int);
     select_evict_kernel<<<L.U, SEL_THREADS, lds, stream>>>(L.cnt, L.srcmap, L.first, c.evicted, c.n, L.C,
-                                                           L.E, L.W32, c.r, c.m);
+                                                           L.E, L.W32, c.r, c.m, c.seq);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     CompactArgs a;
@@ -239,6 +275,7 @@ hipError_t launch_compress(const Layout& L, const CompressArgs& c, hipStream_t s
     a.n_old = c.n;
     a.n_new = c.n - c.m;
     a.zero_bucket = c.zero_bucket;
+    a.seq = c.seq;
     compact_kernel<<<dim3(L.U, 3), 256, 0, stream>>>(a);
     return hipGetLastError();
 }

@@ -62,7 +62,25 @@ struct AttnArgs {
     int counted;
     void* q_keep;         // where unit 0's query of this step is kept (record rebuilt at
     long q_keep_stride;   // compression time), elements between units; null: not kept
+    SeqSched seq;         // ragged batches (seq.off != null): the fields above that depend on the
+    uint16_t* cnt_base;   // step are derived per sequence; cnt_base = bucket (ring word) 0 of unit 0
 };
+
+// Ragged batches: replace the lock-step scalars by those of unit u's sequence.  False when the
+// sequence does not take part in this step (the workgroup then has nothing to do).
+__device__ __forceinline__ bool seq_apply(AttnArgs& a, int u) {
+    const int off = a.seq.off[u / a.seq.heads];
+    if (off == kSeqIdle) return false;
+    const SeqStep s = sched_step(a.seq, (long)off + a.seq.step);
+    a.n = s.n;
+    a.pos_value = s.pos_value;
+    a.tau = s.tau;
+    a.counted = s.counted;
+    a.ring_bit = s.ring_bit;
+    a.cnt = a.seq.W32 ? reinterpret_cast<uint16_t*>(reinterpret_cast<uint32_t*>(a.cnt_base) + (size_t)s.bucket * a.C)
+                      : a.cnt_base + (size_t)s.bucket * a.C;
+    return true;
+}
 
 template <typename T, int N>
 union Frag {
@@ -201,6 +219,7 @@ __device__ __forceinline__ uint4 load_stream16(const void* base, uint32_t byte_o
 
 template <typename T, int D, int NW, int UNR>
 __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
+    if (a.seq.off && !seq_apply(a, blockIdx.x)) return;
     constexpr int EPL = 16 / (int)sizeof(T);  // elements per lane
     constexpr int LPR = D / EPL;              // lanes per row
     constexpr int RPW = 64 / LPR;             // rows per wave load
@@ -380,6 +399,7 @@ __device__ __forceinline__ float row_groups_max(float v) {
 // their partial sums merge with plain DPP adds.
 template <int D, int NW, int UNR>
 __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
+    if (a.seq.off && !seq_apply(a, blockIdx.x)) return;
     constexpr int LPR = D / 32;   // lanes per cache row (16 bytes = 32 codes per lane)
     constexpr int RPW = 64 / LPR; // cache rows per wave load
     constexpr int GPR = D / 64;   // quantisation groups per cache row
@@ -633,6 +653,7 @@ __device__ __forceinline__ float row16_max(float v) {
 
 template <int NW, int UNR>
 __global__ void __launch_bounds__(NW * 64) attn_i4_mfma_kernel(AttnArgs a) {
+    if (a.seq.off && !seq_apply(a, blockIdx.x)) return;
     constexpr int D = 128;
     constexpr int RPW = 16;           // cache rows per tile (one wave load)
     constexpr int GPR = 2;            // quantisation groups per cache row
@@ -964,6 +985,8 @@ hipError_t launch_decode_step(const Layout& L, const StepArgs& s, hipStream_t st
     a.counted = s.counted;
     a.q_keep = s.q_keep;
     a.q_keep_stride = (long)L.w * L.d;
+    a.seq = s.seq;
+    a.cnt_base = L.cnt;
     const int nw = pick_waves(L.U);
     if (L.kv_dtype == KV_F32)
         return L.d == 64 ? launch_rows<float, 64, 2>(a, L.U, nw, stream)

@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cmath>
 #include <new>
+#include <vector>
 
 #include "sc_kernels.hpp"
 
@@ -17,6 +18,17 @@ struct sc_cache {
     int32_t n;
     int64_t t;
     float qk_log2;
+    // Ragged batches: once a *_ragged call has been made every sequence has its own counters
+    // (ts, ns) and the lock-step pair (n, t) above is no longer used.
+    bool ragged;
+    std::vector<int64_t> ts;       // tokens seen by each sequence
+    std::vector<int32_t> ns;       // resident rows of each sequence
+    std::vector<int32_t> table;    // what the device table holds (t_b - step, or kSeqIdle)
+    std::vector<int32_t> wanted;   // scratch for building the next table
+    bool table_known;              // false until the first upload
+    int32_t step;                  // ragged decode calls made so far
+    int32_t* seq_off;              // device [batch]
+    size_t row_bytes, meta_bytes;  // per K (or V) row, for views of a range of sequences
 };
 
 namespace {
@@ -28,7 +40,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct Sizes {
     int32_t n_trig, C, E, W32;
     size_t row_bytes, meta_bytes;  // per K (or V) row
-    size_t off_K, off_V, off_Km, off_Vm, off_pos, off_cnt, off_qh, off_map, off_first, total;
+    size_t off_K, off_V, off_Km, off_Vm, off_pos, off_cnt, off_qh, off_map, off_first, off_seq, total;
     bool recompute;
 };
 
@@ -83,6 +95,7 @@ sc_status derive(const sc_config* cfg, Sizes* s) {
         off = align_up(off + (size_t)cfg->batch * cfg->heads * (size_t)cfg->history * d * 2);
     s->off_map = off;   off = align_up(off + rows * 4);
     s->off_first = off; off = align_up(off + (size_t)cfg->batch * cfg->heads * 4);
+    s->off_seq = off;   off = align_up(off + (size_t)cfg->batch * 4);
     s->total = off;
     return SC_OK;
 }
@@ -188,6 +201,124 @@ sc_status compress_impl(sc_cache* c, int32_t* evicted_out, float* probs_out, hip
     return SC_OK;
 }
 
+// The same cache restricted to the units of sequences [b0, b1).
+sc::Layout view_of(const sc_cache* c, const sc::Layout& whole, int b0, int b1) {
+    sc::Layout L = whole;
+    const size_t u0 = (size_t)b0 * c->cfg.heads, C = (size_t)whole.C;
+    L.U = (b1 - b0) * c->cfg.heads;
+    L.K = static_cast<char*>(whole.K) + u0 * C * c->row_bytes;
+    L.V = static_cast<char*>(whole.V) + u0 * C * c->row_bytes;
+    if (whole.K_meta) {
+        L.K_meta = static_cast<char*>(whole.K_meta) + u0 * C * c->meta_bytes;
+        L.V_meta = static_cast<char*>(whole.V_meta) + u0 * C * c->meta_bytes;
+    }
+    L.pos = whole.pos + u0 * C;
+    L.cnt = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(whole.cnt) +
+                                        u0 * C * ((size_t)whole.E * 2 + (size_t)whole.W32 * 4));
+    if (whole.Qh) L.Qh = static_cast<char*>(whole.Qh) + u0 * (size_t)whole.w * whole.d * 2;
+    L.srcmap = whole.srcmap + u0 * C;
+    L.first = whole.first + u0;
+    return L;
+}
+
+// From lock step to per-sequence counters (nothing on the device changes).
+sc_status enter_ragged(sc_cache* c) {
+    if (c->ragged) return SC_OK;
+    if (c->n >= c->n_trig) return SC_ERR_FULL;  // the pending lock-step compression comes first
+    const size_t B = (size_t)c->cfg.batch;
+    c->ts.assign(B, c->t);
+    c->ns.assign(B, c->n);
+    c->table.assign(B, sc::kSeqIdle);
+    c->wanted.assign(B, sc::kSeqIdle);
+    c->table_known = false;
+    c->step = 0;
+    c->ragged = true;
+    return SC_OK;
+}
+
+sc::SeqSched make_sched(const sc_cache* c, int32_t step) {
+    sc::SeqSched q;
+    q.off = c->seq_off;
+    q.step = step;
+    q.heads = c->cfg.heads;
+    q.n_trig = c->n_trig;
+    q.m = c->cfg.drop;
+    q.w = c->cfg.history;
+    q.E = c->L.E;
+    q.W32 = c->L.W32;
+    q.thresh_len = c->cfg.thresh_mode == SC_THRESH_INV_LEN;
+    return q;
+}
+
+// Make the device table equal to c->wanted (uploaded only when it differs).
+sc_status sync_table(sc_cache* c, hipStream_t s) {
+    if (c->table_known && c->table == c->wanted) return SC_OK;
+    if (sc::launch_write_seq_table(c->seq_off, c->wanted.data(), c->cfg.batch, s) != hipSuccess)
+        return SC_ERR_DEVICE;
+    c->table = c->wanted;
+    c->table_known = true;
+    return SC_OK;
+}
+
+// The prompt of all units of c->L (which may be a view of a range of sequences), cut into runs.
+// stride / out_stride / probs_stride: elements between units in q,k,v / out / probs_out.
+sc_status prefill_core(sc_cache* c, const void* q, const void* k, const void* v, int64_t prompt_len,
+                       int64_t stride, void* out, int64_t out_stride, float* probs_out, int64_t probs_stride,
+                       int32_t mode, hipStream_t s) {
+    const int64_t d = c->cfg.head_dim;
+    const size_t eb = elem_bytes(c->cfg);
+    Sizes z;
+    if (derive(&c->cfg, &z) != SC_OK) return SC_ERR_INVALID_ARG;
+    int64_t i = 0;
+    while (i < prompt_len) {
+        const Run r = next_run(c->cfg, z, mode, c->t, prompt_len - i);
+        const int64_t run = r.len, ep = r.epoch;
+        const size_t off = (size_t)i * d * eb;
+        void* o = out ? static_cast<char*>(out) + off : nullptr;
+        float* pr = probs_out ? probs_out + (size_t)i * c->L.C : nullptr;
+        if (r.dense) {
+            sc::ChunkArgs a;
+            a.q = static_cast<const char*>(q) + off;
+            a.k = static_cast<const char*>(k) + off;
+            a.v = static_cast<const char*>(v) + off;
+            a.unit_stride = (long)stride;
+            a.out = o;
+            a.out_unit_stride = (long)out_stride;
+            a.probs = pr;
+            a.probs_unit_stride = (long)probs_stride;
+            a.n0 = c->n;
+            a.c = (int)run;
+            a.t0 = (long)c->t;
+            a.bucket = c->L.E ? bucket_of(ep, c->L.E) : 0;
+            // the ring records every step; counters skip steps older than every window
+            a.counted = c->L.W32 ? 1 : (!c->L.Qh && ep > -(int64_t)c->L.E);
+            a.thresh_len = c->cfg.thresh_mode == SC_THRESH_INV_LEN;
+            a.qk_log2 = c->qk_log2;
+            if (sc::launch_prefill_chunk(c->L, a, s) != hipSuccess) return SC_ERR_DEVICE;
+            if (c->L.Qh && sc::launch_store_queries(c->L, a.q, (long)stride, (int)run, (long)c->t, s) != hipSuccess)
+                return SC_ERR_DEVICE;
+            c->t += run;
+            c->n += (int32_t)run;
+        } else {
+            for (int64_t j = 0; j < run; ++j) {
+                const size_t offj = off + (size_t)j * d * eb;
+                sc_status st = step_impl(c, static_cast<const char*>(q) + offj, static_cast<const char*>(k) + offj,
+                                         static_cast<const char*>(v) + offj, stride,
+                                         o ? static_cast<char*>(o) + (size_t)j * d * eb : nullptr,
+                                         out_stride, pr ? pr + (size_t)j * c->L.C : nullptr,
+                                         probs_stride, s);
+                if (st != SC_OK) return st;
+            }
+        }
+        i += run;
+        if (c->n == c->n_trig) {
+            const sc_status st = compress_impl(c, nullptr, nullptr, s);
+            if (st != SC_OK) return st;
+        }
+    }
+    return SC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -226,6 +357,16 @@ sc_status sc_schedule(const sc_config* cfg, int64_t t, int64_t* epoch, int32_t* 
     return SC_OK;
 }
 
+sc_status sc_schedule_rows(const sc_config* cfg, int64_t t, int32_t* rows, int32_t* due) {
+    Sizes s;
+    const sc_status st = derive(cfg, &s);
+    if (st != SC_OK) return st;
+    if (t < 1) return SC_ERR_INVALID_ARG;
+    if (rows) *rows = sc::sched_rows((long)t, s.n_trig, cfg->drop);
+    if (due) *due = sc::sched_due((long)t, s.n_trig, cfg->drop);
+    return SC_OK;
+}
+
 sc_status sc_cache_create(const sc_config* cfg, void* dev_workspace, size_t bytes, void* stream,
                           sc_cache** out) {
     if (!out) return SC_ERR_INVALID_ARG;
@@ -256,6 +397,12 @@ sc_status sc_cache_create(const sc_config* cfg, void* dev_workspace, size_t byte
     L.w = cfg->history;
     L.srcmap = reinterpret_cast<int32_t*>(base + s.off_map);
     L.first = reinterpret_cast<int32_t*>(base + s.off_first);
+    c->ragged = false;
+    c->table_known = false;
+    c->step = 0;
+    c->seq_off = reinterpret_cast<int32_t*>(base + s.off_seq);
+    c->row_bytes = s.row_bytes;
+    c->meta_bytes = s.meta_bytes;
     c->n_trig = s.n_trig;
     c->n = 0;
     c->t = 0;
@@ -274,6 +421,9 @@ sc_status sc_cache_reset(sc_cache* c, void* stream) {
     if (sc::launch_clear_counters(c->L, static_cast<hipStream_t>(stream)) != hipSuccess) return SC_ERR_DEVICE;
     c->n = 0;
     c->t = 0;
+    c->ragged = false;
+    c->table_known = false;
+    c->step = 0;
     return SC_OK;
 }
 
@@ -289,6 +439,7 @@ sc_status sc_decode_step(sc_cache* c, const void* q, const void* k_new, const vo
     if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_new) |
          reinterpret_cast<uintptr_t>(v_new) | reinterpret_cast<uintptr_t>(out)) % 16 != 0)
         return SC_ERR_INVALID_ARG;
+    if (c->ragged) return SC_ERR_STATE;
     if (c->n >= c->n_trig) return SC_ERR_FULL;
     const int64_t stride = in_stride ? in_stride : c->cfg.head_dim;
     const sc_status st = step_impl(c, q, k_new, v_new, stride, out, c->cfg.head_dim, probs_out, c->L.C,
@@ -300,7 +451,7 @@ sc_status sc_decode_step(sc_cache* c, const void* q, const void* k_new, const vo
 
 sc_status sc_compress(sc_cache* c, int32_t* evicted_out, float* probs_out, void* stream) {
     if (!c) return SC_ERR_INVALID_ARG;
-    if (c->n != c->n_trig) return SC_ERR_STATE;
+    if (c->ragged || c->n != c->n_trig) return SC_ERR_STATE;
     return compress_impl(c, evicted_out, probs_out, static_cast<hipStream_t>(stream));
 }
 
@@ -308,7 +459,7 @@ sc_status sc_prefill(sc_cache* c, const void* q, const void* k, const void* v, i
                      int64_t unit_stride, void* out, float* probs_out, int32_t mode, void* stream) {
     if (!c || !q || !k || !v || prompt_len < 1) return SC_ERR_INVALID_ARG;
     if (mode != SC_PREFILL_AUTO && mode != SC_PREFILL_STREAMED) return SC_ERR_INVALID_ARG;
-    if (c->n != 0 || c->t != 0) return SC_ERR_STATE;
+    if (c->ragged || c->n != 0 || c->t != 0) return SC_ERR_STATE;
     const int64_t d = c->cfg.head_dim;
     const int64_t stride = unit_stride ? unit_stride : (int64_t)prompt_len * d;
     if (stride < (int64_t)prompt_len * d) return SC_ERR_INVALID_ARG;
@@ -317,58 +468,8 @@ sc_status sc_prefill(sc_cache* c, const void* q, const void* k, const void* v, i
     if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k) | reinterpret_cast<uintptr_t>(v) |
          reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(probs_out)) % 16 != 0)
         return SC_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const int64_t probs_stride = (int64_t)prompt_len * c->L.C;
-    Sizes z;
-    if (derive(&c->cfg, &z) != SC_OK) return SC_ERR_INVALID_ARG;
-    int64_t i = 0;
-    while (i < prompt_len) {
-        const Run r = next_run(c->cfg, z, mode, c->t, prompt_len - i);
-        const int64_t run = r.len, ep = r.epoch;
-        const size_t off = (size_t)i * d * eb;
-        void* o = out ? static_cast<char*>(out) + off : nullptr;
-        float* pr = probs_out ? probs_out + (size_t)i * c->L.C : nullptr;
-        if (r.dense) {
-            sc::ChunkArgs a;
-            a.q = static_cast<const char*>(q) + off;
-            a.k = static_cast<const char*>(k) + off;
-            a.v = static_cast<const char*>(v) + off;
-            a.unit_stride = (long)stride;
-            a.out = o;
-            a.out_unit_stride = (long)((int64_t)prompt_len * d);
-            a.probs = pr;
-            a.probs_unit_stride = (long)probs_stride;
-            a.n0 = c->n;
-            a.c = (int)run;
-            a.t0 = (long)c->t;
-            a.bucket = c->L.E ? bucket_of(ep, c->L.E) : 0;
-            // the ring records every step; counters skip steps older than every window
-            a.counted = c->L.W32 ? 1 : (!c->L.Qh && ep > -(int64_t)c->L.E);
-            a.thresh_len = c->cfg.thresh_mode == SC_THRESH_INV_LEN;
-            a.qk_log2 = c->qk_log2;
-            if (sc::launch_prefill_chunk(c->L, a, s) != hipSuccess) return SC_ERR_DEVICE;
-            if (c->L.Qh && sc::launch_store_queries(c->L, a.q, (long)stride, (int)run, (long)c->t, s) != hipSuccess)
-                return SC_ERR_DEVICE;
-            c->t += run;
-            c->n += (int32_t)run;
-        } else {
-            for (int64_t j = 0; j < run; ++j) {
-                const size_t offj = off + (size_t)j * d * eb;
-                sc_status st = step_impl(c, static_cast<const char*>(q) + offj, static_cast<const char*>(k) + offj,
-                                         static_cast<const char*>(v) + offj, stride,
-                                         o ? static_cast<char*>(o) + (size_t)j * d * eb : nullptr,
-                                         (int64_t)prompt_len * d, pr ? pr + (size_t)j * c->L.C : nullptr,
-                                         probs_stride, s);
-                if (st != SC_OK) return st;
-            }
-        }
-        i += run;
-        if (c->n == c->n_trig) {
-            const sc_status st = compress_impl(c, nullptr, nullptr, s);
-            if (st != SC_OK) return st;
-        }
-    }
-    return SC_OK;
+    return prefill_core(c, q, k, v, prompt_len, stride, out, (int64_t)prompt_len * d, probs_out,
+                        (int64_t)prompt_len * c->L.C, mode, static_cast<hipStream_t>(stream));
 }
 
 sc_status sc_prefill_plan(const sc_config* cfg, int32_t prompt_len, int32_t mode, int32_t max_runs,
@@ -400,8 +501,166 @@ sc_status sc_prefill_plan(const sc_config* cfg, int32_t prompt_len, int32_t mode
 
 sc_status sc_cache_len(const sc_cache* c, int32_t* n, int64_t* t) {
     if (!c) return SC_ERR_INVALID_ARG;
+    if (c->ragged) return SC_ERR_STATE;
     if (n) *n = c->n;
     if (t) *t = c->t;
+    return SC_OK;
+}
+
+sc_status sc_cache_len_seq(const sc_cache* c, int32_t b, int32_t* n, int64_t* t) {
+    if (!c || b < 0 || b >= c->cfg.batch) return SC_ERR_INVALID_ARG;
+    if (n) *n = c->ragged ? c->ns[b] : c->n;
+    if (t) *t = c->ragged ? c->ts[b] : c->t;
+    return SC_OK;
+}
+
+sc_status sc_prefill_ragged(sc_cache* c, const void* q, const void* k, const void* v,
+                            const int32_t* prompt_len, int64_t unit_stride, void* out, float* probs_out,
+                            int32_t mode, void* stream) {
+    if (!c || !q || !k || !v || !prompt_len) return SC_ERR_INVALID_ARG;
+    if (mode != SC_PREFILL_AUTO && mode != SC_PREFILL_STREAMED) return SC_ERR_INVALID_ARG;
+    if (c->L.Qh) return SC_ERR_UNSUPPORTED;
+    const int B = c->cfg.batch;
+    int64_t longest = 0;
+    for (int b = 0; b < B; ++b) {
+        if (prompt_len[b] < 0) return SC_ERR_INVALID_ARG;
+        if (prompt_len[b] > 0 && (c->ragged ? c->ts[b] : c->t) != 0) return SC_ERR_STATE;
+        longest = std::max<int64_t>(longest, prompt_len[b]);
+    }
+    if (longest == 0) return SC_ERR_INVALID_ARG;
+    const int64_t d = c->cfg.head_dim;
+    const int64_t stride = unit_stride ? unit_stride : longest * d;
+    if (stride < longest * d) return SC_ERR_INVALID_ARG;
+    const size_t eb = elem_bytes(c->cfg);
+    if ((stride * eb) % 16 != 0) return SC_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k) | reinterpret_cast<uintptr_t>(v) |
+         reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(probs_out)) % 16 != 0)
+        return SC_ERR_INVALID_ARG;
+    const sc_status st0 = enter_ragged(c);
+    if (st0 != SC_OK) return st0;
+    // Consecutive sequences with the same prompt length advance in lock step: each such range is
+    // prefilled as a view of the cache, with the same kernels as a whole batch.
+    const sc::Layout whole = c->L;
+    const int32_t n_saved = c->n;
+    const int64_t t_saved = c->t;
+    const int64_t out_stride = longest * d, probs_stride = longest * whole.C;
+    sc_status st = SC_OK;
+    for (int b0 = 0; b0 < B && st == SC_OK;) {
+        int b1 = b0 + 1;
+        while (b1 < B && prompt_len[b1] == prompt_len[b0]) ++b1;
+        if (prompt_len[b0] > 0) {
+            const size_t u0 = (size_t)b0 * c->cfg.heads;
+            c->L = view_of(c, whole, b0, b1);
+            c->n = 0;
+            c->t = 0;
+            st = prefill_core(c, static_cast<const char*>(q) + u0 * stride * eb,
+                              static_cast<const char*>(k) + u0 * stride * eb,
+                              static_cast<const char*>(v) + u0 * stride * eb, prompt_len[b0], stride,
+                              out ? static_cast<char*>(out) + u0 * out_stride * eb : nullptr, out_stride,
+                              probs_out ? probs_out + u0 * probs_stride : nullptr, probs_stride, mode,
+                              static_cast<hipStream_t>(stream));
+            for (int b = b0; b < b1; ++b) {
+                c->ts[b] = c->t;
+                c->ns[b] = c->n;
+            }
+        }
+        b0 = b1;
+    }
+    c->L = whole;
+    c->n = n_saved;
+    c->t = t_saved;
+    return st;
+}
+
+sc_status sc_decode_step_ragged(sc_cache* c, const void* q, const void* k_new, const void* v_new,
+                                int64_t in_stride, void* out, float* probs_out, const uint8_t* active,
+                                int32_t* n_due, void* stream) {
+    if (!c || !q || !k_new || !v_new || !out) return SC_ERR_INVALID_ARG;
+    if (in_stride < 0 || (in_stride != 0 && in_stride < c->cfg.head_dim)) return SC_ERR_INVALID_ARG;
+    const size_t eb = elem_bytes(c->cfg);
+    if (in_stride != 0 && (in_stride * eb) % 16 != 0) return SC_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_new) |
+         reinterpret_cast<uintptr_t>(v_new) | reinterpret_cast<uintptr_t>(out)) % 16 != 0)
+        return SC_ERR_INVALID_ARG;
+    if (c->L.Qh) return SC_ERR_UNSUPPORTED;
+    const int B = c->cfg.batch;
+    bool any = false;
+    for (int b = 0; b < B; ++b) any = any || !active || active[b];
+    if (!any) return SC_ERR_INVALID_ARG;
+    const sc_status st0 = enter_ragged(c);
+    if (st0 != SC_OK) return st0;
+    for (int b = 0; b < B; ++b)
+        if (c->ns[b] >= c->n_trig) return SC_ERR_FULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // t_b of the step being computed = table[b] + (step + 1)
+    for (int b = 0; b < B; ++b)
+        c->wanted[b] = (!active || active[b]) ? (int32_t)(c->ts[b] - c->step) : sc::kSeqIdle;
+    const sc_status stt = sync_table(c, s);
+    if (stt != SC_OK) return stt;
+    sc::StepArgs a;
+    a.q = q;
+    a.k_new = k_new;
+    a.v_new = v_new;
+    a.in_stride = (long)(in_stride ? in_stride : c->cfg.head_dim);
+    a.out = out;
+    a.out_stride = c->cfg.head_dim;
+    a.probs = probs_out;
+    a.probs_stride = c->L.C;
+    a.n = 0;
+    a.pos_value = 0;
+    a.bucket = 0;
+    a.counted = 0;
+    a.ring_bit = 0;
+    a.qk_log2 = c->qk_log2;
+    a.tau = 0.f;
+    a.q_keep = nullptr;
+    a.seq = make_sched(c, c->step + 1);
+    if (sc::launch_decode_step(c->L, a, s) != hipSuccess) return SC_ERR_DEVICE;
+    c->step += 1;
+    int32_t due = 0;
+    for (int b = 0; b < B; ++b) {
+        if (c->wanted[b] == sc::kSeqIdle) continue;
+        c->ts[b] += 1;
+        c->ns[b] += 1;
+        due += c->ns[b] == c->n_trig;
+    }
+    if (n_due) *n_due = due;
+    return SC_OK;
+}
+
+sc_status sc_compress_ragged(sc_cache* c, int32_t* evicted_out, void* stream) {
+    if (!c) return SC_ERR_INVALID_ARG;
+    if (!c->ragged) return SC_ERR_STATE;
+    const int B = c->cfg.batch;
+    bool any = false, table_fits = c->table_known;
+    for (int b = 0; b < B; ++b) {
+        const bool pending = c->ns[b] == c->n_trig;
+        any = any || pending;
+        c->wanted[b] = pending ? (int32_t)(c->ts[b] - c->step) : sc::kSeqIdle;
+        if (!table_fits) continue;
+        // The table of the latest step serves as it is when it marks exactly the pending
+        // sequences as due (the others are idle or stand between two compressions).
+        const int32_t e = c->table[b];
+        const bool due_by_table = e != sc::kSeqIdle && sc::sched_due((long)e + c->step, c->n_trig, c->cfg.drop);
+        table_fits = pending ? (e == c->wanted[b]) : !due_by_table;
+    }
+    if (!any) return SC_ERR_STATE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!table_fits) {
+        c->table_known = false;
+        const sc_status stt = sync_table(c, s);
+        if (stt != SC_OK) return stt;
+    }
+    sc::CompressArgs a;
+    a.n = c->n_trig;
+    a.r = c->cfg.recent;
+    a.m = c->cfg.drop;
+    a.zero_bucket = -1;
+    a.evicted = evicted_out;
+    a.seq = make_sched(c, c->step);
+    if (sc::launch_compress(c->L, a, s) != hipSuccess) return SC_ERR_DEVICE;
+    for (int b = 0; b < B; ++b)
+        if (c->ns[b] == c->n_trig) c->ns[b] -= c->cfg.drop;
     return SC_OK;
 }
 
@@ -433,6 +692,7 @@ sc_status sc_diag_persistence(const float* probs, int32_t units, int32_t length,
 sc_status sc_diag_kept_mass(const sc_cache* c, const float* probs_full, int64_t unit_stride, float* mass_out,
                             void* stream) {
     if (!c || !probs_full || !mass_out || unit_stride < c->t) return SC_ERR_INVALID_ARG;
+    if (c->ragged) return SC_ERR_STATE;
     if (sc::launch_kept_mass(c->L, c->n, probs_full, (long)unit_stride, mass_out,
                              static_cast<hipStream_t>(stream)) != hipSuccess)
         return SC_ERR_DEVICE;

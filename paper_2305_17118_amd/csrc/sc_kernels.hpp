@@ -28,6 +28,76 @@ struct Layout {
     int32_t* first;   // [U] scratch: first slot whose row moves
 };
 
+// ---- Ragged batches: every sequence runs Alg. 1 on its own clock ----------------------------
+// The schedule of a sequence is a function of the number of tokens it has seen: as long as every
+// due compression is carried out before the next step, the resident rows, the history bucket (or
+// ring bit), the threshold and the steps at which a compression is due all follow from t_b.  The
+// device therefore only needs t_b per sequence: a table off[b] = t_b - step that stays valid
+// while a sequence takes part in consecutive steps (both sides advance by one per call), and is
+// rewritten only when a sequence joins, leaves or is prefilled.
+constexpr int32_t kSeqIdle = INT32_MIN;  // table entry of a sequence that does not take part
+
+struct SeqSched {
+    const int32_t* off;  // device [batch], or null: all units in lock step (scalar arguments apply)
+    int step;            // t_b = off[b] + step is the step being computed (decode) or just computed (compress)
+    int heads;           // units per sequence
+    int n_trig, m, w;    // trigger size, rows dropped per compression, history window
+    int E, W32;          // record layout (buckets, or ring words)
+    int thresh_len;      // threshold 1/n instead of 1/t
+};
+
+struct SeqStep {
+    int n;          // resident rows including the one this step appends
+    int pos_value;  // stream position of that row
+    int bucket;     // counter bucket, or ring word, of this step
+    int counted;
+    uint32_t ring_bit;
+    float tau;
+};
+
+// ceil((t - n_trig) / m) for any sign.
+__host__ __device__ inline long sched_epoch(long t, long n_trig, long m) {
+    const long a = t - n_trig;
+    return a >= 0 ? (a + m - 1) / m : -((-a) / m);
+}
+
+// Resident rows right after step t (before the compression that may then be due).
+__host__ __device__ inline int sched_rows(long t, int n_trig, int m) {
+    return t <= n_trig ? (int)t : n_trig - m + (int)((t - n_trig - 1) % m) + 1;
+}
+
+// A compression is due right after step t.
+__host__ __device__ inline bool sched_due(long t, int n_trig, int m) {
+    return t >= n_trig && (t - n_trig) % m == 0;
+}
+
+__host__ __device__ inline SeqStep sched_step(const SeqSched& s, long t1) {
+    SeqStep r;
+    r.n = sched_rows(t1, s.n_trig, s.m);
+    r.pos_value = (int)(t1 - 1);
+    if (s.W32) {
+        const long rho = t1 % s.w;  // ring bit owned by this step
+        r.bucket = (int)(rho >> 5);
+        r.ring_bit = 1u << (rho & 31);
+        r.counted = 1;
+    } else {
+        const long ep = sched_epoch(t1, s.n_trig, s.m);
+        r.bucket = (int)(((ep % s.E) + s.E) % s.E);
+        r.ring_bit = 0;
+        r.counted = ep > -(long)s.E;
+    }
+    const float x = (float)(s.thresh_len ? (long)r.n : t1);
+#if defined(__HIP_DEVICE_COMPILE__)
+    r.tau = __fdiv_rn(1.0f, x);
+#else
+    r.tau = 1.0f / x;
+#endif
+    return r;
+}
+
+// Write `count` table entries (host values) to device memory on `stream`.
+hipError_t launch_write_seq_table(int32_t* dst, const int32_t* host_values, int count, hipStream_t stream);
+
 struct StepArgs {
     const void* q;
     const void* k_new;
@@ -44,8 +114,9 @@ struct StepArgs {
     uint32_t ring_bit;  // ring mode: mask of this step's bit inside its word
     float qk_log2;    // score scale * log2(e)
     float tau;        // low-score threshold
-    void* q_keep;     // ring slot of this step for unit 0 (units are w*d elements apart), or null;
-                      // honoured by the fp32/fp16 kernels (the only storage the replay supports)
+    void* q_keep;     // ring slot of this step for unit 0 (units are w*d elements apart), or null
+    SeqSched seq{};   // seq.off != null: n, pos_value, bucket, counted, ring_bit and tau above are
+                      // ignored and derived per sequence on the device
 };
 
 // One launch on `stream`: append the new row and attend.
@@ -56,6 +127,9 @@ struct CompressArgs {
     int r, m;       // recent window, rows to drop
     int zero_bucket;  // bucket the following epoch will count into (cleared here)
     int32_t* evicted; // [U][m] or null
+    SeqSched seq{};   // seq.off != null: only the units of sequences that are due after step
+                      // off[b] + step are compressed (n is the trigger size for all of them),
+                      // zero_bucket is derived per sequence
 };
 
 hipError_t launch_compress(const Layout& L, const CompressArgs& a, hipStream_t stream);

@@ -32,6 +32,25 @@ def dequant_i4(codes_u8: np.ndarray, meta_f16: np.ndarray) -> np.ndarray:
     return (codes * scale).astype(np.float32) + zero
 
 
+def compare_step(o_gpu, o_ref, p_gpu, p_ref, tol, kv_dtype, stats, label):
+    """One step's outputs [U, d] and probabilities [U, n] against the oracle's, within the
+    spec tolerance; updates the running maxima in `stats`."""
+    assert np.all(np.isfinite(o_gpu)) and np.all(np.isfinite(p_gpu)), label
+    sum_err = np.abs(p_gpu.astype(np.float64).sum(axis=1) - 1.0).max()
+    assert sum_err <= 1e-5, "%s: probabilities sum off by %g" % (label, sum_err)
+    dp = np.abs(p_gpu - p_ref).max(axis=1)
+    lim = tol * p_ref.max(axis=1) if kv_dtype != B.SC_KV_F32 else 1e-5
+    assert np.all(dp <= lim), "%s: probability error %g" % (label, dp.max())
+    rel = np.linalg.norm(o_gpu - o_ref, axis=1) / np.linalg.norm(o_ref, axis=1)
+    assert np.all(rel <= tol), "%s: output relative error %g > %g" % (label, rel.max(), tol)
+    rms = np.sqrt((o_ref ** 2).mean(axis=1, keepdims=True))
+    assert np.all(np.abs(o_gpu - o_ref) <= tol * (np.abs(o_ref) + rms)), "%s elementwise" % label
+    st = stats
+    st["max_rel_out"] = max(st["max_rel_out"], float(rel.max()))
+    st["max_dp"] = max(st["max_dp"], float(dp.max()))
+    st["max_sum_err"] = max(st["max_sum_err"], float(sum_err))
+
+
 class ParityRun:
     """One workload on the GPU (all units) and on the oracle (the units in `sel`)."""
 
@@ -82,21 +101,7 @@ class ParityRun:
         return due
 
     def _compare(self, o_gpu, o_ref, p_gpu, p_ref, s):
-        tol = self.tol
-        assert np.all(np.isfinite(o_gpu)) and np.all(np.isfinite(p_gpu)), "step %d" % s
-        sum_err = np.abs(p_gpu.astype(np.float64).sum(axis=1) - 1.0).max()
-        assert sum_err <= 1e-5, "step %d: probabilities sum off by %g" % (s, sum_err)
-        dp = np.abs(p_gpu - p_ref).max(axis=1)
-        lim = tol * p_ref.max(axis=1) if self.wl.kv_dtype != B.SC_KV_F32 else 1e-5
-        assert np.all(dp <= lim), "step %d: probability error %g" % (s, dp.max())
-        rel = np.linalg.norm(o_gpu - o_ref, axis=1) / np.linalg.norm(o_ref, axis=1)
-        assert np.all(rel <= tol), "step %d: output relative error %g > %g" % (s, rel.max(), tol)
-        rms = np.sqrt((o_ref ** 2).mean(axis=1, keepdims=True))
-        assert np.all(np.abs(o_gpu - o_ref) <= tol * (np.abs(o_ref) + rms)), "step %d elementwise" % s
-        st = self.stats
-        st["max_rel_out"] = max(st["max_rel_out"], float(rel.max()))
-        st["max_dp"] = max(st["max_dp"], float(dp.max()))
-        st["max_sum_err"] = max(st["max_sum_err"], float(sum_err))
+        compare_step(o_gpu, o_ref, p_gpu, p_ref, self.tol, self.wl.kv_dtype, self.stats, "step %d" % s)
 
     # -- the prompt through sc_prefill, the oracle stepped through the same positions ----------
     def prefill(self, P, mode=B.SC_PREFILL_AUTO):

@@ -224,3 +224,25 @@ def test_recomputed_record_configuration():
     with pytest.raises(B.ScError) as e:
         B.sc_config_sizes(_cfg(record_mode=3))
     assert e.value.status == B.SC_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("kw", [
+    dict(), dict(trigger=B.SC_TRIGGER_HIGH_WATER), dict(budget=20, recent=3, history=8, drop=1),
+    dict(budget=50, recent=5, history=51, drop=23), dict(budget=9, recent=1, history=6, drop=9,
+                                                         trigger=B.SC_TRIGGER_HIGH_WATER),
+])
+def test_rows_and_due_steps_follow_from_the_token_count(kw):
+    """Ragged batches evaluate n_b and "compression due" on the device from t_b alone; that closed
+    form must equal the state machine of Alg. 1 (append one row per step, drop m whenever the
+    trigger size is reached) at every step, and agree with sc_schedule about the buckets."""
+    cfg = _cfg(**kw)
+    n_trig = B.sc_config_sizes(cfg)[0]
+    n = 0
+    for t in range(1, 6 * n_trig):
+        n += 1
+        rows, due = B.sc_schedule_rows(cfg, t)
+        assert rows == n and due == (n == n_trig), (t, rows, n, due)
+        if due:
+            n -= cfg.drop
+    with pytest.raises(B.ScError):
+        B.sc_schedule_rows(cfg, 0)
