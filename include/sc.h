@@ -263,6 +263,34 @@ sc_status sc_compress_ragged(sc_cache *c, int32_t *evicted_out, void *stream);
 /* Resident rows and tokens seen of sequence b (works for lock-step handles too). */
 sc_status sc_cache_len_seq(const sc_cache *c, int32_t b, int32_t *n, int64_t *t);
 
+/* ---- One cache per transformer layer, each with its own budget ------------------------------
+ * Sec. 4.1 "Allocating Budgets Across Attention Heads": a total budget is distributed over the
+ * layers (more to later layers, whose persistence ratio is lower) and evenly over the heads of
+ * a layer.  A layer set is L caches that share every parameter of `cfg` except the per-layer
+ * budget B_l and rows dropped per compression m_l (the paper ties m to B, m = B/2), carved out
+ * of one caller-provided workspace.  Each layer is an ordinary sc_cache: the handle returned by
+ * sc_layers_get is used with every call above (lock step or ragged) and is owned by the set. */
+typedef struct sc_layers sc_layers; /* opaque, host side */
+
+/* Bytes of 256-byte aligned device workspace for the whole set; 0 if any layer's configuration
+ * is invalid.  budgets: host int32 [layers]; drops: host int32 [layers] or NULL (cfg->drop). */
+size_t sc_layers_workspace_bytes(const sc_config *cfg, int32_t layers, const int32_t *budgets,
+                                 const int32_t *drops);
+
+/* Create the L empty caches.  Errors as sc_cache_create (the first failing layer's status). */
+sc_status sc_layers_create(const sc_config *cfg, int32_t layers, const int32_t *budgets,
+                           const int32_t *drops, void *dev_workspace, size_t bytes, void *stream,
+                           sc_layers **out);
+
+/* The cache of one layer (NULL when out of range).  Owned by the set: do not destroy it. */
+sc_cache *sc_layers_get(sc_layers *ls, int32_t layer);
+
+/* Number of layers. */
+int32_t sc_layers_count(const sc_layers *ls);
+
+/* Free the host metadata of the set and of its caches. */
+void sc_layers_destroy(sc_layers *ls);
+
 /* Device pointers into the workspace, for inspection (any pointer may be NULL):
  *   K, V    : [U][capacity] rows; F32/F16: head_dim elements; I4G64: head_dim/2 bytes of
  *             codes, channel 2i in the low nibble of byte i

@@ -28,6 +28,7 @@ EXPORTS = (
     "sc_diag_persistence", "sc_diag_kept_mass",
     "sc_prefill_ragged", "sc_decode_step_ragged", "sc_compress_ragged", "sc_cache_len_seq",
     "sc_schedule_rows",
+    "sc_layers_workspace_bytes", "sc_layers_create", "sc_layers_get", "sc_layers_count", "sc_layers_destroy",
 )
 
 
@@ -79,10 +80,20 @@ def lib():
     l.sc_compress_ragged.argtypes = [vp, vp, vp]
     l.sc_cache_len_seq.argtypes = [vp, C.c_int32, i32p, i64p]
     l.sc_schedule_rows.argtypes = [cfgp, C.c_int64, i32p, i32p]
+    l.sc_layers_workspace_bytes.argtypes = [cfgp, C.c_int32, i32p, i32p]
+    l.sc_layers_workspace_bytes.restype = C.c_size_t
+    l.sc_layers_create.argtypes = [cfgp, C.c_int32, i32p, i32p, vp, C.c_size_t, vp, C.POINTER(vp)]
+    l.sc_layers_get.argtypes = [vp, C.c_int32]
+    l.sc_layers_get.restype = vp
+    l.sc_layers_count.argtypes = [vp]
+    l.sc_layers_count.restype = C.c_int32
+    l.sc_layers_destroy.argtypes = [vp]
+    l.sc_layers_destroy.restype = None
     l.sc_status_str.argtypes = [C.c_int]
     l.sc_status_str.restype = C.c_char_p
     for name in EXPORTS:
-        if name not in ("sc_workspace_bytes", "sc_cache_destroy", "sc_status_str"):
+        if name not in ("sc_workspace_bytes", "sc_cache_destroy", "sc_status_str", "sc_layers_workspace_bytes",
+                        "sc_layers_get", "sc_layers_count", "sc_layers_destroy"):
             getattr(l, name).restype = C.c_int
     _lib = l
     return l
@@ -242,7 +253,8 @@ class BudgetCache:
     Marshalling only: every method forwards to the C entry point of the same name with the
     tensors' device addresses and the current torch stream."""
 
-    def __init__(self, cfg: sc_config, device="cuda:0"):
+    def __init__(self, cfg: sc_config, device="cuda:0", _borrowed=None):
+        """`_borrowed` = (handle, workspace tensor) of a cache owned by a LayerSet."""
         import torch
 
         self._torch = torch
@@ -250,13 +262,17 @@ class BudgetCache:
         self.device = torch.device(device)
         self.n_trig, self.capacity, self.buckets, self.ring_words = sc_config_sizes(cfg)
         self.units = cfg.batch * cfg.heads
-        nbytes = sc_workspace_bytes(cfg)
-        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
-        base = self.workspace.data_ptr()
-        self._ws_ptr = (base + 255) // 256 * 256
         self.io_dtype = torch.float32 if cfg.kv_dtype == SC_KV_F32 else torch.float16
-        self.handle = sc_cache_create(cfg, self._ws_ptr, nbytes, self._stream())
-        self._destroy = lib().sc_cache_destroy  # kept here: module globals may be gone at interpreter exit
+        if _borrowed is not None:
+            self.handle, self.workspace = _borrowed
+            self._destroy = lambda h: None
+        else:
+            nbytes = sc_workspace_bytes(cfg)
+            self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+            base = self.workspace.data_ptr()
+            self._ws_ptr = (base + 255) // 256 * 256
+            self.handle = sc_cache_create(cfg, self._ws_ptr, nbytes, self._stream())
+            self._destroy = lib().sc_cache_destroy  # kept here: module globals may be gone at interpreter exit
         self._view = sc_cache_view(self.handle)
 
     def _stream(self) -> int:
@@ -356,3 +372,51 @@ def kv_cache_bytes(layers: int, d_model: int, batch: int, seq: int, bytes_per_el
     """Bytes of a full (uncompressed) KV cache: two tensors of [batch, seq, d_model] per layer
     (the accounting behind the memory table of the paper's introduction)."""
     return 2 * layers * d_model * bytes_per_elem * batch * seq
+
+
+class LayerSet:
+    """One cache per layer with per-layer budgets, in one torch workspace (sc_layers_*)."""
+
+    def __init__(self, cfg: sc_config, budgets, drops=None, device="cuda:0"):
+        import copy
+
+        import torch
+
+        self.device = torch.device(device)
+        L = len(budgets)
+        b = (C.c_int32 * L)(*[int(x) for x in budgets])
+        m = None if drops is None else (C.c_int32 * L)(*[int(x) for x in drops])
+        nbytes = int(lib().sc_layers_workspace_bytes(C.byref(cfg), L, b, m))
+        if nbytes == 0:
+            raise ScError(SC_ERR_INVALID_ARG, "sc_layers_workspace_bytes")
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        ws = (self.workspace.data_ptr() + 255) // 256 * 256
+        h = C.c_void_p()
+        stream = int(torch.cuda.current_stream(self.device).cuda_stream)
+        _check(lib().sc_layers_create(C.byref(cfg), L, b, m, ws, nbytes, stream, C.byref(h)), "sc_layers_create")
+        self.handle = h
+        self._destroy = lib().sc_layers_destroy
+        self.layers = []
+        for l in range(L):
+            c = copy.copy(cfg)
+            c.budget = int(budgets[l])
+            if drops is not None:
+                c.drop = int(drops[l])
+            self.layers.append(BudgetCache(c, device, _borrowed=(C.c_void_p(lib().sc_layers_get(h, l)),
+                                                                 self.workspace)))
+        assert lib().sc_layers_count(h) == L
+
+    def __len__(self):
+        return len(self.layers)
+
+    def __getitem__(self, l):
+        return self.layers[l]
+
+    def close(self):
+        if getattr(self, "handle", None):
+            for c in self.layers:
+                c.handle = None
+            self._destroy(self.handle)
+            self.handle = None
+
+    __del__ = close

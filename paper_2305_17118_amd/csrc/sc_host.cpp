@@ -31,6 +31,10 @@ struct sc_cache {
     size_t row_bytes, meta_bytes;  // per K (or V) row, for views of a range of sequences
 };
 
+struct sc_layers {
+    std::vector<sc_cache*> layer;
+};
+
 namespace {
 
 constexpr size_t kAlign = 256;
@@ -697,6 +701,60 @@ sc_status sc_diag_kept_mass(const sc_cache* c, const float* probs_full, int64_t 
                              static_cast<hipStream_t>(stream)) != hipSuccess)
         return SC_ERR_DEVICE;
     return SC_OK;
+}
+
+size_t sc_layers_workspace_bytes(const sc_config* cfg, int32_t layers, const int32_t* budgets,
+                                 const int32_t* drops) {
+    if (!cfg || layers < 1 || !budgets) return 0;
+    size_t total = 0;
+    for (int32_t l = 0; l < layers; ++l) {
+        sc_config c = *cfg;
+        c.budget = budgets[l];
+        if (drops) c.drop = drops[l];
+        const size_t b = sc_workspace_bytes(&c);
+        if (b == 0) return 0;
+        total += b;  // every cache's size is a multiple of the alignment
+    }
+    return total;
+}
+
+sc_status sc_layers_create(const sc_config* cfg, int32_t layers, const int32_t* budgets, const int32_t* drops,
+                           void* dev_workspace, size_t bytes, void* stream, sc_layers** out) {
+    if (!cfg || layers < 1 || !budgets || !out) return SC_ERR_INVALID_ARG;
+    if (!dev_workspace) return SC_ERR_INVALID_ARG;
+    sc_layers* ls = new (std::nothrow) sc_layers;
+    if (!ls) return SC_ERR_INVALID_ARG;
+    size_t off = 0;
+    for (int32_t l = 0; l < layers; ++l) {
+        sc_config c = *cfg;
+        c.budget = budgets[l];
+        if (drops) c.drop = drops[l];
+        Sizes z;
+        sc_status st = derive(&c, &z);
+        if (st == SC_OK && off + z.total > bytes) st = SC_ERR_WORKSPACE;
+        sc_cache* h = nullptr;
+        if (st == SC_OK) st = sc_cache_create(&c, static_cast<char*>(dev_workspace) + off, z.total, stream, &h);
+        if (st != SC_OK) {
+            sc_layers_destroy(ls);
+            return st;
+        }
+        ls->layer.push_back(h);
+        off += z.total;
+    }
+    *out = ls;
+    return SC_OK;
+}
+
+sc_cache* sc_layers_get(sc_layers* ls, int32_t layer) {
+    return ls && layer >= 0 && (size_t)layer < ls->layer.size() ? ls->layer[(size_t)layer] : nullptr;
+}
+
+int32_t sc_layers_count(const sc_layers* ls) { return ls ? (int32_t)ls->layer.size() : 0; }
+
+void sc_layers_destroy(sc_layers* ls) {
+    if (!ls) return;
+    for (sc_cache* h : ls->layer) sc_cache_destroy(h);
+    delete ls;
 }
 
 const char* sc_status_str(sc_status s) {

@@ -150,3 +150,52 @@ def test_random_ragged_configuration_matches_oracle(seed):
     run.prefill()
     st = run.run()
     assert st["seq_steps"] == sum(decodes)
+
+
+def test_layer_set_with_growing_budgets_matches_standalone_caches_and_oracle():
+    """One cache per layer, later layers with larger budgets (Sec. 4.1, budgets across layers;
+    m = B/2 per layer): every layer of the set behaves exactly like a standalone cache with that
+    layer's configuration (bit for bit), and the last layer is checked against the oracle."""
+    from tests.parity_util import ParityRun
+
+    budgets, drops = [32, 64, 96], [16, 32, 48]
+    base = _wl("layers", 2, 3, 128, KV_F16, 32, 8, 96, 16, 0.05)
+    T = 260
+    q, k, v = (torch.from_numpy(a).cuda() for a in streams(base, steps=T))
+    cfg = B.make_config(base.batch, base.heads, base.head_dim, base.kv_dtype, 32, base.recent, base.history, 16)
+    ls = B.LayerSet(cfg, budgets, drops)
+    assert len(ls) == 3
+    U, d = base.units, base.head_dim
+    for l, (bud, m) in enumerate(zip(budgets, drops)):
+        solo = B.BudgetCache(B.make_config(base.batch, base.heads, d, base.kv_dtype, bud, base.recent,
+                                           base.history, m))
+        layer = ls[l]
+        assert (layer.n_trig, layer.capacity) == (solo.n_trig, solo.capacity)
+        oa = torch.empty(U, d, dtype=torch.float16, device="cuda")
+        ob = torch.empty_like(oa)
+        comps = 0
+        for s in range(T):
+            due_a = layer.decode_step(q[:, s], k[:, s], v[:, s], oa, in_stride=T * d)
+            due_b = solo.decode_step(q[:, s], k[:, s], v[:, s], ob, in_stride=T * d)
+            assert due_a == due_b and torch.equal(oa, ob)
+            if due_a:
+                layer.compress()
+                solo.compress()
+                comps += 1
+        assert comps >= 3 and (layer.n, layer.t) == (solo.n, solo.t)
+        n = solo.n
+        assert torch.equal(layer.pos()[:, :n], solo.pos()[:, :n]) and torch.equal(layer.cnt(), solo.cnt())
+    # the layers did not disturb each other: layer 0 still holds what its own steps left
+    first = B.BudgetCache(B.make_config(base.batch, base.heads, d, base.kv_dtype, 32, base.recent, base.history, 16))
+    ob = torch.empty(U, d, dtype=torch.float16, device="cuda")
+    for s in range(T):
+        if first.decode_step(q[:, s], k[:, s], v[:, s], ob, in_stride=T * d):
+            first.compress()
+    n = first.n
+    K0, V0 = ls[0].kv_rows()
+    K1, V1 = first.kv_rows()
+    assert torch.equal(K0[:, :n], K1[:, :n]) and torch.equal(V0[:, :n], V1[:, :n])
+    ls.close()
+    wl = Workload("layer-2", 1300, base.batch, base.heads, d, base.kv_dtype, 0, T, 96, base.recent, base.history, 48, 0.05)
+    run = ParityRun(wl)
+    run.run()

@@ -246,3 +246,19 @@ def test_rows_and_due_steps_follow_from_the_token_count(kw):
             n -= cfg.drop
     with pytest.raises(B.ScError):
         B.sc_schedule_rows(cfg, 0)
+
+
+def test_layer_set_workspace_is_the_sum_of_its_layers():
+    """Per-layer budgets (Sec. 4.1, budgets across layers): the set's workspace is the layers'
+    workspaces back to back; an invalid layer makes the whole set invalid."""
+    cfg = _cfg()
+    budgets, drops = [32, 64, 96, 200], [16, 32, 48, 100]
+    lib = B.lib()
+    arr = lambda xs: (ctypes.c_int32 * len(xs))(*xs)
+    total = lib.sc_layers_workspace_bytes(ctypes.byref(cfg), 4, arr(budgets), arr(drops))
+    assert total == sum(B.sc_workspace_bytes(_cfg(budget=b, drop=m)) for b, m in zip(budgets, drops))
+    same_drop = lib.sc_layers_workspace_bytes(ctypes.byref(cfg), 2, arr([64, 128]), None)
+    assert same_drop == B.sc_workspace_bytes(_cfg(budget=64)) + B.sc_workspace_bytes(_cfg(budget=128))
+    assert lib.sc_layers_workspace_bytes(ctypes.byref(cfg), 2, arr([64, 0]), None) == 0
+    assert lib.sc_layers_workspace_bytes(ctypes.byref(cfg), 0, arr([64]), None) == 0
+    assert lib.sc_layers_count(None) == 0 and not lib.sc_layers_get(None, 0)
