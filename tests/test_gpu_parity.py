@@ -457,3 +457,80 @@ def test_free_running_oracle_divergence_is_reported(kv, record_property):
           "%.4f of the final resident positions in common" % (
               ("f32", "f16", "i4")[kv], int(agree.sum()), U, comps // max(1, U), common), flush=True)
     assert common >= 0.9
+
+
+PATTERNS = ["random", "front", "back", "alternate", "block", "two-blocks"]
+
+
+@pytest.mark.parametrize("pattern", PATTERNS)
+@pytest.mark.parametrize("kv,d", [(KV_F16, 128), (KV_I4G64, 128), (KV_F32, 64), (KV_F16, 64)],
+                         ids=["f16", "i4", "f32", "f16-d64"])
+def test_in_place_compaction_equals_out_of_place_gather(kv, d, pattern):
+    """The compaction moves rows inside the arrays it reads.  Here the records are written by the
+    test so that Alg. 2 must evict a chosen set of slots (each unit its own), and the result is
+    compared with an out-of-place gather of the snapshot taken before: stored rows, 4-bit
+    meta words, positions and the surviving counter bucket, for eviction patterns that stress the
+    chunked in-place move (evictions at the very front, right below the recent window,
+    alternating, in blocks)."""
+    m, r, budget = 96, 8, 299  # trigger size 300, not a multiple of the 64-slot capacity rounding
+    wl = _wl("compact", 2, 3, d, kv, 0, budget + 1, budget, r, 2 * m, m)
+    U, n = wl.units, budget + 1
+    q, k, v = (torch.from_numpy(a).cuda() for a in streams(wl))
+    cfg = B.make_config(wl.batch, wl.heads, d, kv, budget, r, 2 * m, m)
+    cache = B.BudgetCache(cfg)
+    out = torch.empty(U, d, dtype=cache.io_dtype, device="cuda")
+    due = False
+    for s in range(n):
+        due = cache.decode_step(q[:, s], k[:, s], v[:, s], out, in_stride=n * d)
+    assert due and cache.n == n
+    rng = np.random.default_rng(1000 * kv + d + 7919 * PATTERNS.index(pattern))
+    ncand = n - r
+    chosen = np.zeros((U, m), dtype=np.int64)
+    for u in range(U):
+        if pattern == "random":
+            c = rng.choice(ncand, m, replace=False)
+        elif pattern == "front":
+            c = np.arange(m)
+        elif pattern == "back":
+            c = np.arange(ncand - m, ncand)
+        elif pattern == "alternate":
+            c = np.arange(u % 2, u % 2 + 2 * m, 2)
+        elif pattern == "block":
+            start = int(rng.integers(0, ncand - m + 1))
+            c = np.arange(start, start + m)
+        else:
+            a = int(rng.integers(0, 60))
+            b_ = int(rng.integers(a + m // 2 + 1, ncand - m // 2 + 1))
+            c = np.concatenate([np.arange(a, a + m // 2), np.arange(b_, b_ + m // 2)])
+        chosen[u] = np.sort(c)
+    cnt = cache.cnt()  # [U, 2, C] view into the workspace
+    marks = torch.zeros(U, cache.capacity, dtype=torch.int16, device="cuda")
+    marks.scatter_(1, torch.from_numpy(chosen).cuda(), 7)
+    t = cache.t
+    live = 1 - B.sc_schedule(cfg, t + 1)[1]  # the bucket the next epoch does NOT reuse survives
+    cnt.zero_()
+    cnt[:, live] = marks
+    K0, V0 = (x.clone() for x in cache.kv_rows())
+    pos0 = cache.pos().clone()
+    meta0 = [x.clone() for x in cache.kv_meta()] if kv == KV_I4G64 else None
+    ev = torch.empty(U, m, dtype=torch.int32, device="cuda")
+    cache.compress(ev)
+    assert np.array_equal(ev.cpu().numpy(), chosen)
+    keep = np.stack([np.setdiff1d(np.arange(n), chosen[u]) for u in range(U)])
+    kt = torch.from_numpy(keep).cuda()
+    nn = n - m
+    assert cache.n == nn
+
+    def gathered(x):
+        idx = kt.view(U, nn, *([1] * (x.dim() - 2))).expand(U, nn, *x.shape[2:])
+        return torch.gather(x[:, :n], 1, idx)
+
+    K1, V1 = cache.kv_rows()
+    assert torch.equal(K1[:, :nn], gathered(K0)) and torch.equal(V1[:, :nn], gathered(V0))
+    assert torch.equal(cache.pos()[:, :nn], gathered(pos0))
+    if meta0 is not None:
+        Km1, Vm1 = cache.kv_meta()
+        assert torch.equal(Km1[:, :nn], gathered(meta0[0])) and torch.equal(Vm1[:, :nn], gathered(meta0[1]))
+    c1 = cache.cnt()
+    assert int(c1[:, live, :nn].abs().max().item()) == 0  # every marked row is gone
+    assert int(c1[:, :, nn:].abs().max().item()) == 0 and int(c1[:, 1 - live].abs().max().item()) == 0
