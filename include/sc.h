@@ -46,7 +46,7 @@ typedef enum {
     SC_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, m > trigger size - r, ...    */
     SC_ERR_WORKSPACE = 2,   /* workspace too small or not 256-byte aligned                    */
     SC_ERR_FULL = 3,        /* sc_decode_step while a compression is due                      */
-    SC_ERR_STATE = 4,       /* sc_compress when none is due; sc_prefill on a non-empty cache  */
+    SC_ERR_STATE = 4,       /* sc_compress when none is due; lock-step call on a ragged handle */
     SC_ERR_UNSUPPORTED = 5, /* head_dim / kv_dtype / sizes this build does not cover          */
     SC_ERR_DEVICE = 6       /* a kernel launch failed (hipGetLastError)                       */
 } sc_status;
@@ -182,7 +182,9 @@ typedef enum {
 
 /* Stream a prompt through Alg. 1 (Def. 4.1 treats prompt and generated tokens as one
  * stream): for each of the prompt_len positions in order, one decode step, then a
- * compression whenever one is due.  The cache must be empty.  Between two compressions the
+ * compression whenever one is due.  The cache need not be empty: the positions continue its
+ * stream from wherever it stands (a prompt handed over in chunks, a later turn of a
+ * conversation); SC_ERR_FULL if a compression is due.  Between two compressions the
  * cache only grows, so the positions in between form one dense causal attention block
  * (Sec. 4.1 estimator per position, Alg. 2 record update per position); SC_PREFILL_AUTO
  * computes them that way.
@@ -231,8 +233,9 @@ sc_status sc_schedule_rows(const sc_config *cfg, int64_t t, int32_t *rows, int32
 
 /* Prompts of different lengths: sequence b streams its first prompt_len[b] positions through
  * Alg. 1 exactly as sc_prefill does for a whole batch (consecutive sequences of equal length
- * share their launches).  Sequences with prompt_len[b] == 0 are left alone; the others must be
- * empty (SC_ERR_STATE).
+ * share their launches when their counters are equal too).  Sequences with prompt_len[b] == 0
+ * are left alone; the others continue from wherever they stand (SC_ERR_FULL if one of them has
+ * a compression due).
  *   prompt_len : host int32 [batch]
  *   q, k, v    : device, [U][>= max prompt_len][head_dim], units `unit_stride` elements apart
  *                (0 = max prompt_len * head_dim)

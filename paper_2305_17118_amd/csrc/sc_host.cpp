@@ -463,7 +463,8 @@ sc_status sc_prefill(sc_cache* c, const void* q, const void* k, const void* v, i
                      int64_t unit_stride, void* out, float* probs_out, int32_t mode, void* stream) {
     if (!c || !q || !k || !v || prompt_len < 1) return SC_ERR_INVALID_ARG;
     if (mode != SC_PREFILL_AUTO && mode != SC_PREFILL_STREAMED) return SC_ERR_INVALID_ARG;
-    if (c->ragged || c->n != 0 || c->t != 0) return SC_ERR_STATE;
+    if (c->ragged) return SC_ERR_STATE;
+    if (c->n >= c->n_trig) return SC_ERR_FULL;
     const int64_t d = c->cfg.head_dim;
     const int64_t stride = unit_stride ? unit_stride : (int64_t)prompt_len * d;
     if (stride < (int64_t)prompt_len * d) return SC_ERR_INVALID_ARG;
@@ -528,7 +529,7 @@ sc_status sc_prefill_ragged(sc_cache* c, const void* q, const void* k, const voi
     int64_t longest = 0;
     for (int b = 0; b < B; ++b) {
         if (prompt_len[b] < 0) return SC_ERR_INVALID_ARG;
-        if (prompt_len[b] > 0 && (c->ragged ? c->ts[b] : c->t) != 0) return SC_ERR_STATE;
+        if (prompt_len[b] > 0 && (c->ragged ? c->ns[b] : c->n) >= c->n_trig) return SC_ERR_FULL;
         longest = std::max<int64_t>(longest, prompt_len[b]);
     }
     if (longest == 0) return SC_ERR_INVALID_ARG;
@@ -542,8 +543,9 @@ sc_status sc_prefill_ragged(sc_cache* c, const void* q, const void* k, const voi
         return SC_ERR_INVALID_ARG;
     const sc_status st0 = enter_ragged(c);
     if (st0 != SC_OK) return st0;
-    // Consecutive sequences with the same prompt length advance in lock step: each such range is
-    // prefilled as a view of the cache, with the same kernels as a whole batch.
+    // Consecutive sequences with the same counters and the same prompt length advance in lock
+    // step: each such range is prefilled as a view of the cache, with the same kernels as a
+    // whole batch.
     const sc::Layout whole = c->L;
     const int32_t n_saved = c->n;
     const int64_t t_saved = c->t;
@@ -551,12 +553,13 @@ sc_status sc_prefill_ragged(sc_cache* c, const void* q, const void* k, const voi
     sc_status st = SC_OK;
     for (int b0 = 0; b0 < B && st == SC_OK;) {
         int b1 = b0 + 1;
-        while (b1 < B && prompt_len[b1] == prompt_len[b0]) ++b1;
+        while (b1 < B && prompt_len[b1] == prompt_len[b0] && c->ts[b1] == c->ts[b0] && c->ns[b1] == c->ns[b0])
+            ++b1;
         if (prompt_len[b0] > 0) {
             const size_t u0 = (size_t)b0 * c->cfg.heads;
             c->L = view_of(c, whole, b0, b1);
-            c->n = 0;
-            c->t = 0;
+            c->n = c->ns[b0];
+            c->t = c->ts[b0];
             st = prefill_core(c, static_cast<const char*>(q) + u0 * stride * eb,
                               static_cast<const char*>(k) + u0 * stride * eb,
                               static_cast<const char*>(v) + u0 * stride * eb, prompt_len[b0], stride,

@@ -110,26 +110,27 @@ class ParityRun:
         position's output and probabilities are compared.  Evictions inside the call are not
         visible one by one; the positions and stored rows after the call are, and must agree
         bit for bit (any differing eviction changes them)."""
-        assert self.step_idx == 0
+        s0 = self.step_idx  # the call continues the stream from wherever the cache stands
         d, C = self.wl.head_dim, self.cache.capacity
         out = torch.empty(self.U, P, d, dtype=self.cache.io_dtype, device=self.dev)
         probs = torch.zeros(self.U, P, C, dtype=torch.float32, device=self.dev)
-        self.cache.prefill(self.q, self.k, self.v, P, self.T * d, out, probs, mode)
+        self.cache.prefill(self.q[:, s0:], self.k[:, s0:], self.v[:, s0:], P, self.T * d, out, probs, mode)
         o_all = out.index_select(0, self.sel_t).float().cpu().numpy().astype(np.float64)
         p_all = probs.index_select(0, self.sel_t).cpu().numpy()
         del out, probs
-        for s in range(P):
+        for i in range(P):
+            s = s0 + i
             n = self.oracle.n + 1
-            p_gpu = np.ascontiguousarray(p_all[:, s, :n])
+            p_gpu = np.ascontiguousarray(p_all[:, i, :n])
             o_ref, p_ref, due = self.oracle.step(self.hq[:, s], self.hk[:, s], self.hv[:, s],
                                                  p_forced=p_gpu)
-            self._compare(o_all[:, s], o_ref, p_gpu, p_ref[:, :n], s)
+            self._compare(o_all[:, i], o_ref, p_gpu, p_ref[:, :n], s)
             self.stats["steps"] += 1
             if due:
                 assert not self.recompute, "prefill parity with a recomputed record: step instead"
                 self.oracle.compress()
                 self.stats["compressions"] += 1
-        self.step_idx = P
+        self.step_idx = s0 + P
         assert (self.cache.n, self.cache.t) == (self.oracle.n, self.oracle.t)
         self.check_state()
         return self.stats

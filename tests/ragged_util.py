@@ -47,29 +47,39 @@ class RaggedParityRun:
         return slice(b * self.heads, (b + 1) * self.heads)
 
     # -- prompts of different lengths through one sc_prefill_ragged call ---------------------
-    def prefill(self, mode=B.SC_PREFILL_AUTO):
-        P = max(self.prompts)
+    def prefill(self, mode=B.SC_PREFILL_AUTO, lengths=None):
+        """`lengths` (default: the prompts) more positions per sequence, continuing each
+        sequence's stream from the position it has consumed so far."""
+        lengths = self.prompts if lengths is None else list(lengths)
+        P = max(lengths)
         assert P > 0
         out = torch.full((self.U, P, self.d), float("nan"), dtype=self.cache.io_dtype, device=self.dev)
         probs = torch.zeros(self.U, P, self.C, dtype=torch.float32, device=self.dev)
-        self.cache.prefill_ragged(self.q, self.k, self.v, self.prompts, self.T * self.d, out, probs, mode)
+        # every sequence reads from its own offset: gather the chunks into one [U, P, d] block
+        idx = torch.tensor([[min(self.consumed[b] + i, self.T - 1) for i in range(P)]
+                            for b in range(self.batch)], device=self.dev).repeat_interleave(self.heads, dim=0)
+        ar = torch.arange(self.U, device=self.dev).unsqueeze(1)
+        qs, ks, vs = (x[ar, idx].contiguous() for x in (self.q, self.k, self.v))
+        self.cache.prefill_ragged(qs, ks, vs, lengths, P * self.d, out, probs, mode)
         o_all = out.float().cpu().numpy().astype(np.float64)
         p_all = probs.cpu().numpy()
         del out, probs
         for b in range(self.batch):
             u = self._units(b)
             seq = self.oracle.seq[b]
-            for s in range(self.prompts[b]):
+            c0 = self.consumed[b]
+            for i in range(lengths[b]):
+                s = c0 + i
                 n = seq.n + 1
-                p_gpu = np.ascontiguousarray(p_all[u, s, :n])
+                p_gpu = np.ascontiguousarray(p_all[u, i, :n])
                 o_ref, p_ref, due = seq.step(self.hq[u, s], self.hk[u, s], self.hv[u, s], p_forced=p_gpu)
-                compare_step(o_all[u, s], o_ref, p_gpu, p_ref[:, :n], self.tol, self.wl.kv_dtype, self.stats,
+                compare_step(o_all[u, i], o_ref, p_gpu, p_ref[:, :n], self.tol, self.wl.kv_dtype, self.stats,
                              "sequence %d prompt position %d" % (b, s))
                 if due:
                     seq.compress()
             # rows past the sequence's own prompt were not written
-            assert np.all(np.isnan(o_all[u, self.prompts[b]:]))
-            self.consumed[b] = self.prompts[b]
+            assert np.all(np.isnan(o_all[u, lengths[b]:]))
+            self.consumed[b] = c0 + lengths[b]
             assert self.cache.len_seq(b) == seq.lengths()[:2]
         self.check_state()
 

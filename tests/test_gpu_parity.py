@@ -232,6 +232,27 @@ def test_dense_prefill_with_ring_record_matches_oracle(wl):
     assert st["steps"] == wl.total and st["compressions"] >= 2
 
 
+@pytest.mark.parametrize("kv,window", [(KV_F16, B.SC_WINDOW_AUTO), (KV_I4G64, B.SC_WINDOW_AUTO),
+                                       (KV_F16, B.SC_WINDOW_RING), (KV_F32, B.SC_WINDOW_AUTO)],
+                         ids=["f16", "i4", "f16-ring", "f32-streamed"])
+def test_prefill_continues_a_cache_that_is_not_empty(kv, window):
+    """A prompt handed over in chunks, decode steps, then a later turn's prompt: every sc_prefill
+    call continues the stream from wherever the cache stands (chunks that start in the middle of
+    a run between two compressions, right after a compression, and after decode steps)."""
+    d = 64 if kv == KV_F32 else 128
+    wl = _wl("pf-chunks", 1, 3, d, kv, 0, 700, 150, 8, 96, 48, 0.05)
+    run = ParityRun(wl, window_mode=window)
+    run.prefill(100)        # ends before the first compression
+    run.prefill(51)         # reaches the trigger size exactly: the compression happens inside
+    assert run.cache.n == 151 - 48
+    run.prefill(130)        # several runs, starts right after a compression
+    run.run(steps=75)       # decode steps (with their own compressions)
+    run.prefill(200)        # a later turn: starts in the middle of a run
+    run.prefill(1)          # a single position
+    st = run.run()
+    assert st["steps"] == wl.total and st["compressions"] >= 8
+
+
 def test_dense_prefill_inverse_length_threshold():
     wl = _wl("pf-inv-len", 1, 3, 128, KV_F16, 300, 80, 120, 8, 64, 32, 0.05)
     run = ParityRun(wl, thresh=B.SC_THRESH_INV_LEN, scale=0.2)
@@ -376,9 +397,6 @@ def test_dense_prefill_production_path_and_reset(kv):
     bare.prefill(q, k, v, T, 0, out2)
     assert same(bare) and torch.equal(out2, out)
     with pytest.raises(B.ScError) as e:
-        bare.prefill(q, k, v, T)  # not empty any more
-    assert e.value.status == B.SC_ERR_STATE
-    with pytest.raises(B.ScError) as e:
         B.BudgetCache(cfg).prefill(q, k, v, T, mode=5)
     assert e.value.status == B.SC_ERR_INVALID_ARG
 
@@ -400,8 +418,8 @@ def test_error_codes_leave_state_untouched():
         c.decode_step(x, x, x, out)
     assert e.value.status == B.SC_ERR_FULL and (c.n, c.t) == (9, 9)
     with pytest.raises(B.ScError) as e:
-        c.prefill(x, x, x, 1)
-    assert e.value.status == B.SC_ERR_STATE
+        c.prefill(x, x, x, 1)  # a compression is due
+    assert e.value.status == B.SC_ERR_FULL and (c.n, c.t) == (9, 9)
     with pytest.raises(B.ScError) as e:
         B.sc_decode_step(c.handle, x.data_ptr() + 4, x.data_ptr(), x.data_ptr(), 0, out.data_ptr())
     assert e.value.status == B.SC_ERR_INVALID_ARG

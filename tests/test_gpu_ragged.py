@@ -49,6 +49,26 @@ def test_ragged_batch_with_ring_record_and_inverse_length_threshold(kv, d):
     assert st["seq_compressions"] >= 3
 
 
+@pytest.mark.parametrize("kv", [KV_F16, KV_I4G64], ids=["f16", "i4"])
+def test_ragged_prompts_continue_sequences_that_are_not_empty(kv):
+    """A second turn: after some decode steps a few sequences receive more prompt positions (of
+    different lengths), the others none; then all decode again."""
+    wl = _wl("rag-turns", 4, 2, 128, kv, 64, 8, 32, 16, 0.05)
+    #                prompts            decode steps taken in two phases of 30 and 40
+    run = RaggedParityRun(wl, [40, 0, 97, 20], [0, 0, 0, 0], [70 + 120, 70, 70 + 35, 70 + 120])
+    run.prefill()
+    for s in range(30):
+        if run.step(s):
+            run.compress()
+    run.prefill(lengths=[120, 0, 35, 120])
+    run.decodes = [70, 70, 70, 70]
+    for s in range(30, 70):
+        if run.step(s):
+            run.compress()
+    run.check_state()
+    assert run.stats["seq_steps"] == 4 * 70 and run.stats["seq_compressions"] >= 8
+
+
 def test_ragged_calls_with_equal_lengths_equal_the_lock_step_calls():
     """All sequences active with equal counters: the ragged calls must leave exactly the state and
     outputs of sc_decode_step / sc_compress (same kernels, per-sequence values derived on the device)."""
@@ -103,9 +123,8 @@ def test_ragged_state_machine_errors():
     with pytest.raises(B.ScError) as e:
         c.compress_ragged()
     assert e.value.status == B.SC_ERR_STATE
-    with pytest.raises(B.ScError) as e:  # sequence 0 is not empty
-        c.prefill_ragged(x, x, x, [1, 0])
-    assert e.value.status == B.SC_ERR_STATE
+    c.prefill_ragged(x, x, x, [1, 0])  # a prompt may continue a sequence that is not empty
+    assert c.len_seq(0) == (14, 18)
     c.reset()  # back to lock step, empty
     assert (c.n, c.t) == (0, 0)
     assert c.decode_step(x, x, x, out) is False
