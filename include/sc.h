@@ -223,7 +223,7 @@ sc_status sc_cache_len(const sc_cache *c, int32_t *n, int64_t *t);
  * The first *_ragged call switches the handle to per-sequence counters (SC_ERR_FULL if a
  * lock-step compression is still due); from then on the lock-step calls (sc_decode_step,
  * sc_compress, sc_prefill, sc_cache_len, sc_diag_kept_mass) return SC_ERR_STATE until
- * sc_cache_reset.  SC_RECORD_RECOMPUTE is not offered for ragged batches (SC_ERR_UNSUPPORTED). */
+ * sc_cache_reset. */
 
 /* Host only: the resident rows of a sequence right after its step t (t >= 1, counting the row
  * that step appended, before the compression that may then be due) and whether a compression is
@@ -258,10 +258,15 @@ sc_status sc_decode_step_ragged(sc_cache *c, const void *q, const void *k_new, c
                                 int64_t in_stride, void *out, float *probs_out, const uint8_t *active,
                                 int32_t *n_due, void *stream);
 
-/* Alg. 2 on the units of every sequence that is due (one launch pair for all of them).
+/* Alg. 2 on the units of every sequence that is due (one launch pair for all of them; with
+ * SC_RECORD_RECOMPUTE preceded by one replay of the kept queries per range of due sequences
+ * with equal token counts).
  *   evicted_out : device int32 [U][m] or NULL; rows of sequences that were not due are untouched
+ *   probs_out   : SC_RECORD_RECOMPUTE only (ignored otherwise), device fp32 [U][w][capacity] or
+ *                 NULL: for the units of a due sequence b, row k < min(w, t_b) receives the
+ *                 probabilities of replayed step t_b - min(w, t_b) + 1 + k as in sc_compress
  * SC_ERR_STATE when no sequence is due. */
-sc_status sc_compress_ragged(sc_cache *c, int32_t *evicted_out, void *stream);
+sc_status sc_compress_ragged(sc_cache *c, int32_t *evicted_out, float *probs_out, void *stream);
 
 /* Resident rows and tokens seen of sequence b (works for lock-step handles too). */
 sc_status sc_cache_len_seq(const sc_cache *c, int32_t b, int32_t *n, int64_t *t);

@@ -77,7 +77,7 @@ def lib():
     l.sc_diag_kept_mass.argtypes = [vp, vp, C.c_int64, vp, vp]
     l.sc_prefill_ragged.argtypes = [vp, vp, vp, vp, i32p, C.c_int64, vp, vp, C.c_int32, vp]
     l.sc_decode_step_ragged.argtypes = [vp, vp, vp, vp, C.c_int64, vp, vp, C.POINTER(C.c_uint8), i32p, vp]
-    l.sc_compress_ragged.argtypes = [vp, vp, vp]
+    l.sc_compress_ragged.argtypes = [vp, vp, vp, vp]
     l.sc_cache_len_seq.argtypes = [vp, C.c_int32, i32p, i64p]
     l.sc_schedule_rows.argtypes = [cfgp, C.c_int64, i32p, i32p]
     l.sc_layers_workspace_bytes.argtypes = [cfgp, C.c_int32, i32p, i32p]
@@ -219,8 +219,8 @@ def sc_decode_step_ragged(handle, q_ptr, k_ptr, v_ptr, in_stride, out_ptr, probs
     return due.value
 
 
-def sc_compress_ragged(handle, evicted_ptr=None, stream=0) -> None:
-    _check(lib().sc_compress_ragged(handle, evicted_ptr, stream), "sc_compress_ragged")
+def sc_compress_ragged(handle, evicted_ptr=None, probs_ptr=None, stream=0) -> None:
+    _check(lib().sc_compress_ragged(handle, evicted_ptr, probs_ptr, stream), "sc_compress_ragged")
 
 
 def sc_cache_view(handle):
@@ -326,9 +326,9 @@ class BudgetCache:
                                      out.data_ptr(), None if probs_out is None else probs_out.data_ptr(),
                                      active, self._stream())
 
-    def compress_ragged(self, evicted_out=None) -> None:
+    def compress_ragged(self, evicted_out=None, probs_out=None) -> None:
         sc_compress_ragged(self.handle, None if evicted_out is None else evicted_out.data_ptr(),
-                           self._stream())
+                           None if probs_out is None else probs_out.data_ptr(), self._stream())
 
     def _typed(self, key, dtype, shape):
         """A torch view (no copy) of one of the cache's arrays inside the workspace."""

@@ -64,6 +64,7 @@ struct AttnArgs {
     long q_keep_stride;   // compression time), elements between units; null: not kept
     SeqSched seq;         // ragged batches (seq.off != null): the fields above that depend on the
     uint16_t* cnt_base;   // step are derived per sequence; cnt_base = bucket (ring word) 0 of unit 0
+    long q_keep_slot_bytes;  // ragged + kept queries: q_keep = slot 0 of unit 0, slots this far apart
 };
 
 // Ragged batches: replace the lock-step scalars by those of unit u's sequence.  False when the
@@ -77,6 +78,8 @@ __device__ __forceinline__ bool seq_apply(AttnArgs& a, int u) {
     a.tau = s.tau;
     a.counted = s.counted;
     a.ring_bit = s.ring_bit;
+    if (a.q_keep)  // step t keeps its query in ring slot (t-1) mod w
+        a.q_keep = static_cast<char*>(a.q_keep) + (size_t)(s.pos_value % a.seq.w) * a.q_keep_slot_bytes;
     a.cnt = a.seq.W32 ? reinterpret_cast<uint16_t*>(reinterpret_cast<uint32_t*>(a.cnt_base) + (size_t)s.bucket * a.C)
                       : a.cnt_base + (size_t)s.bucket * a.C;
     return true;
@@ -987,6 +990,7 @@ hipError_t launch_decode_step(const Layout& L, const StepArgs& s, hipStream_t st
     a.q_keep_stride = (long)L.w * L.d;
     a.seq = s.seq;
     a.cnt_base = L.cnt;
+    a.q_keep_slot_bytes = (long)L.d * (L.kv_dtype == KV_F32 ? 4 : 2);
     const int nw = pick_waves(L.U);
     if (L.kv_dtype == KV_F32)
         return L.d == 64 ? launch_rows<float, 64, 2>(a, L.U, nw, stream)

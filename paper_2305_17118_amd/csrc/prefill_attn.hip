@@ -879,7 +879,7 @@ hipError_t launch_recompute_record(const Layout& L, const ReplayArgs& r, hipStre
     a.out = nullptr;
     a.out_unit_stride = 0;
     a.probs = r.probs;
-    a.probs_unit_stride = (long)W * L.C;
+    a.probs_unit_stride = r.probs_unit_stride ? r.probs_unit_stride : (long)W * L.C;
     a.cnt = L.cnt;
     a.cnt_unit_stride = (long)L.E * L.C;
     a.C = L.C;

@@ -187,6 +187,7 @@ sc_status compress_impl(sc_cache* c, int32_t* evicted_out, float* probs_out, hip
         r.thresh_len = c->cfg.thresh_mode == SC_THRESH_INV_LEN;
         r.qk_log2 = c->qk_log2;
         r.probs = probs_out;
+        r.probs_unit_stride = 0;
         if (sc::launch_recompute_record(c->L, r, stream) != hipSuccess) return SC_ERR_DEVICE;
     }
     sc::CompressArgs a;
@@ -251,6 +252,7 @@ sc::SeqSched make_sched(const sc_cache* c, int32_t step) {
     q.E = c->L.E;
     q.W32 = c->L.W32;
     q.thresh_len = c->cfg.thresh_mode == SC_THRESH_INV_LEN;
+    q.recompute = c->L.Qh != nullptr;
     return q;
 }
 
@@ -524,7 +526,6 @@ sc_status sc_prefill_ragged(sc_cache* c, const void* q, const void* k, const voi
                             int32_t mode, void* stream) {
     if (!c || !q || !k || !v || !prompt_len) return SC_ERR_INVALID_ARG;
     if (mode != SC_PREFILL_AUTO && mode != SC_PREFILL_STREAMED) return SC_ERR_INVALID_ARG;
-    if (c->L.Qh) return SC_ERR_UNSUPPORTED;
     const int B = c->cfg.batch;
     int64_t longest = 0;
     for (int b = 0; b < B; ++b) {
@@ -589,15 +590,14 @@ sc_status sc_decode_step_ragged(sc_cache* c, const void* q, const void* k_new, c
     if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_new) |
          reinterpret_cast<uintptr_t>(v_new) | reinterpret_cast<uintptr_t>(out)) % 16 != 0)
         return SC_ERR_INVALID_ARG;
-    if (c->L.Qh) return SC_ERR_UNSUPPORTED;
     const int B = c->cfg.batch;
     bool any = false;
     for (int b = 0; b < B; ++b) any = any || !active || active[b];
     if (!any) return SC_ERR_INVALID_ARG;
+    for (int b = 0; b < B; ++b)  // checked before anything changes, the counters' mode included
+        if ((c->ragged ? c->ns[b] : c->n) >= c->n_trig) return SC_ERR_FULL;
     const sc_status st0 = enter_ragged(c);
     if (st0 != SC_OK) return st0;
-    for (int b = 0; b < B; ++b)
-        if (c->ns[b] >= c->n_trig) return SC_ERR_FULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     // t_b of the step being computed = table[b] + (step + 1)
     for (int b = 0; b < B; ++b)
@@ -620,7 +620,7 @@ sc_status sc_decode_step_ragged(sc_cache* c, const void* q, const void* k_new, c
     a.ring_bit = 0;
     a.qk_log2 = c->qk_log2;
     a.tau = 0.f;
-    a.q_keep = nullptr;
+    a.q_keep = c->L.Qh;  // kept queries: the kernels pick each sequence's own ring slot
     a.seq = make_sched(c, c->step + 1);
     if (sc::launch_decode_step(c->L, a, s) != hipSuccess) return SC_ERR_DEVICE;
     c->step += 1;
@@ -635,7 +635,7 @@ sc_status sc_decode_step_ragged(sc_cache* c, const void* q, const void* k_new, c
     return SC_OK;
 }
 
-sc_status sc_compress_ragged(sc_cache* c, int32_t* evicted_out, void* stream) {
+sc_status sc_compress_ragged(sc_cache* c, int32_t* evicted_out, float* probs_out, void* stream) {
     if (!c) return SC_ERR_INVALID_ARG;
     if (!c->ragged) return SC_ERR_STATE;
     const int B = c->cfg.batch;
@@ -657,6 +657,27 @@ sc_status sc_compress_ragged(sc_cache* c, int32_t* evicted_out, void* stream) {
         c->table_known = false;
         const sc_status stt = sync_table(c, s);
         if (stt != SC_OK) return stt;
+    }
+    if (c->L.Qh) {
+        // Alg. 2 as printed: every range of due sequences with the same token count replays its
+        // kept queries as one dense block over its own units.
+        for (int b0 = 0; b0 < B;) {
+            int b1 = b0 + 1;
+            if (c->ns[b0] != c->n_trig) {
+                b0 = b1;
+                continue;
+            }
+            while (b1 < B && c->ns[b1] == c->n_trig && c->ts[b1] == c->ts[b0]) ++b1;
+            sc::ReplayArgs r;
+            r.n = c->n_trig;
+            r.t = (long)c->ts[b0];
+            r.thresh_len = c->cfg.thresh_mode == SC_THRESH_INV_LEN;
+            r.qk_log2 = c->qk_log2;
+            r.probs_unit_stride = (long)c->cfg.history * c->L.C;
+            r.probs = probs_out ? probs_out + (size_t)b0 * c->cfg.heads * (size_t)r.probs_unit_stride : nullptr;
+            if (sc::launch_recompute_record(view_of(c, c->L, b0, b1), r, s) != hipSuccess) return SC_ERR_DEVICE;
+            b0 = b1;
+        }
     }
     sc::CompressArgs a;
     a.n = c->n_trig;

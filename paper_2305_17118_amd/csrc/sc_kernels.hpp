@@ -44,6 +44,7 @@ struct SeqSched {
     int n_trig, m, w;    // trigger size, rows dropped per compression, history window
     int E, W32;          // record layout (buckets, or ring words)
     int thresh_len;      // threshold 1/n instead of 1/t
+    int recompute;       // record rebuilt at compression time: steps count nothing, queries are kept
 };
 
 struct SeqStep {
@@ -75,7 +76,11 @@ __host__ __device__ inline SeqStep sched_step(const SeqSched& s, long t1) {
     SeqStep r;
     r.n = sched_rows(t1, s.n_trig, s.m);
     r.pos_value = (int)(t1 - 1);
-    if (s.W32) {
+    if (s.recompute) {
+        r.bucket = 0;
+        r.ring_bit = 0;
+        r.counted = 0;
+    } else if (s.W32) {
         const long rho = t1 % s.w;  // ring bit owned by this step
         r.bucket = (int)(rho >> 5);
         r.ring_bit = 1u << (rho & 31);
@@ -175,6 +180,7 @@ hipError_t launch_store_queries(const Layout& L, const void* q, long unit_stride
 // Alg. 2 as printed: rebuild the record (16-bit counts in L.cnt, cleared first) by replaying
 // the kept queries of steps (t - min(w,t), t] over the n resident rows.
 struct ReplayArgs {
+    long probs_unit_stride;  // floats between units in probs (0: min(w, t) * C, densely packed)
     int n;
     long t;
     int thresh_len;

@@ -16,7 +16,8 @@ from tests.parity_util import TOL, compare_step, dequant_i4
 
 class RaggedParityRun:
     def __init__(self, wl: Workload, prompts, starts, decodes, trigger=B.SC_TRIGGER_HARD_CAP,
-                 thresh=B.SC_THRESH_INV_POS, window_mode=B.SC_WINDOW_AUTO, device="cuda:0"):
+                 thresh=B.SC_THRESH_INV_POS, window_mode=B.SC_WINDOW_AUTO,
+                 record_mode=B.SC_RECORD_ONLINE, device="cuda:0"):
         """Sequence b: `prompts[b]` prompt positions (0: none), then `decodes[b]` decode steps
         taken at the global steps starts[b] ... starts[b] + decodes[b] - 1."""
         self.wl = wl
@@ -27,10 +28,12 @@ class RaggedParityRun:
         self.T = max(p + n for p, n in zip(prompts, decodes))
         self.steps_total = max(s + n for s, n in zip(starts, decodes))
         self.cfg = B.make_config(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.budget, wl.recent,
-                                 wl.history, wl.drop, trigger, thresh, 0.0, window_mode)
+                                 wl.history, wl.drop, trigger, thresh, 0.0, window_mode, record_mode)
+        self.recompute = record_mode == B.SC_RECORD_RECOMPUTE
         self.cache = B.BudgetCache(self.cfg, device)
         self.oracle = RaggedOracle(OracleConfig(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.budget,
-                                                wl.recent, wl.history, wl.drop, trigger, thresh, 0.0))
+                                                wl.recent, wl.history, wl.drop, trigger, thresh, 0.0,
+                                                record_mode))
         q, k, v = streams(wl, steps=self.T, threads=16)
         self.hq, self.hk, self.hv = q, k, v
         self.q, self.k, self.v = (torch.from_numpy(a).to(self.dev) for a in (q, k, v))
@@ -76,6 +79,7 @@ class RaggedParityRun:
                 compare_step(o_all[u, i], o_ref, p_gpu, p_ref[:, :n], self.tol, self.wl.kv_dtype, self.stats,
                              "sequence %d prompt position %d" % (b, s))
                 if due:
+                    assert not self.recompute, "prefill parity with a recomputed record: step instead"
                     seq.compress()
             # rows past the sequence's own prompt were not written
             assert np.all(np.isnan(o_all[u, lengths[b]:]))
@@ -127,9 +131,43 @@ class RaggedParityRun:
         cnt = self.cache.cnt()[u][:, :, :n].to(torch.int32) & 0xFFFF
         return cnt.sum(dim=1).cpu().numpy()
 
+    def compress_recompute(self, due):
+        """Record rebuilt at compression time: each due sequence replays its own last min(w, t_b)
+        queries; the GPU dumps the probabilities its thresholds saw, the sequence's oracle replays
+        the same steps with them forced (evicted slots bit-exact, probabilities within tolerance)."""
+        w = self.wl.history
+        probs = torch.zeros(self.U, w, self.C, dtype=torch.float32, device=self.dev)
+        self.evicted.fill_(-1)
+        self.cache.compress_ragged(self.evicted, probs)
+        p_all = probs.cpu().numpy()
+        ev_gpu = self.evicted.cpu().numpy()
+        for b in range(self.batch):
+            u = self._units(b)
+            if not due[b]:
+                assert np.all(ev_gpu[u] == -1) and np.all(p_all[u] == 0.0)  # untouched
+                continue
+            seq = self.oracle.seq[b]
+            n, t, _ = seq.lengths()
+            W = min(w, t)
+            p_gpu = np.ascontiguousarray(p_all[u, :W, :n])
+            ev_ref, p_ref, _ = seq.compress_recompute(p_forced=p_gpu)
+            p_ref = p_ref[:, :, :n]
+            seen = p_ref.sum(axis=2) > 0.5
+            assert np.abs(p_gpu.astype(np.float64).sum(axis=2) - 1.0)[seen].max() <= 1e-5
+            assert np.all(p_gpu[~seen] == 0.0)
+            dp = np.abs(p_gpu - p_ref).max(axis=2)
+            lim = self.tol * p_ref.max(axis=2) if self.wl.kv_dtype != B.SC_KV_F32 else 1e-5
+            assert np.all(dp <= lim), "sequence %d: replayed probability error %g" % (b, dp.max())
+            assert np.array_equal(ev_gpu[u], ev_ref), "sequence %d: evicted slots differ" % b
+        self.check_state()
+        self.stats["compressions"] += 1
+        self.stats["seq_compressions"] += int(due.sum())
+
     def compress(self):
         due = self.oracle.due()
         assert due.any()
+        if self.recompute:
+            return self.compress_recompute(due)
         for b in np.flatnonzero(due):
             n = self.oracle.seq[b].n
             assert np.array_equal(self.gpu_record(b, n), self.oracle.importance(b)), \
