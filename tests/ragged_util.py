@@ -17,9 +17,10 @@ from tests.parity_util import TOL, compare_step, dequant_i4
 class RaggedParityRun:
     def __init__(self, wl: Workload, prompts, starts, decodes, trigger=B.SC_TRIGGER_HARD_CAP,
                  thresh=B.SC_THRESH_INV_POS, window_mode=B.SC_WINDOW_AUTO,
-                 record_mode=B.SC_RECORD_ONLINE, device="cuda:0"):
+                 record_mode=B.SC_RECORD_ONLINE, device="cuda:0", check_seqs=None):
         """Sequence b: `prompts[b]` prompt positions (0: none), then `decodes[b]` decode steps
-        taken at the global steps starts[b] ... starts[b] + decodes[b] - 1."""
+        taken at the global steps starts[b] ... starts[b] + decodes[b] - 1.  `check_seqs`: the
+        sequences followed by an oracle (default all); the others run on the GPU only."""
         self.wl = wl
         self.dev = torch.device(device)
         self.batch, self.heads, self.d, self.U = wl.batch, wl.heads, wl.head_dim, wl.units
@@ -43,8 +44,9 @@ class RaggedParityRun:
         self.evicted = torch.empty(self.U, wl.drop, dtype=torch.int32, device=self.dev)
         self.tol = TOL[wl.kv_dtype]
         self.stats = dict(steps=0, seq_steps=0, compressions=0, seq_compressions=0, max_rel_out=0.0,
-                          max_dp=0.0, max_sum_err=0.0, uploads_expected=0)
+                          max_dp=0.0, max_sum_err=0.0)
         self.consumed = [0] * self.batch  # stream positions each sequence has taken
+        self.check = list(range(self.batch)) if check_seqs is None else sorted(check_seqs)
 
     def _units(self, b):
         return slice(b * self.heads, (b + 1) * self.heads)
@@ -64,27 +66,30 @@ class RaggedParityRun:
         ar = torch.arange(self.U, device=self.dev).unsqueeze(1)
         qs, ks, vs = (x[ar, idx].contiguous() for x in (self.q, self.k, self.v))
         self.cache.prefill_ragged(qs, ks, vs, lengths, P * self.d, out, probs, mode)
-        o_all = out.float().cpu().numpy().astype(np.float64)
-        p_all = probs.cpu().numpy()
-        del out, probs
         for b in range(self.batch):
+            if b not in self.check:
+                self.consumed[b] += lengths[b]
+                continue
             u = self._units(b)
+            o_all = out[u].float().cpu().numpy().astype(np.float64)
+            p_all = probs[u].cpu().numpy()
             seq = self.oracle.seq[b]
             c0 = self.consumed[b]
             for i in range(lengths[b]):
                 s = c0 + i
                 n = seq.n + 1
-                p_gpu = np.ascontiguousarray(p_all[u, i, :n])
+                p_gpu = np.ascontiguousarray(p_all[:, i, :n])
                 o_ref, p_ref, due = seq.step(self.hq[u, s], self.hk[u, s], self.hv[u, s], p_forced=p_gpu)
-                compare_step(o_all[u, i], o_ref, p_gpu, p_ref[:, :n], self.tol, self.wl.kv_dtype, self.stats,
+                compare_step(o_all[:, i], o_ref, p_gpu, p_ref[:, :n], self.tol, self.wl.kv_dtype, self.stats,
                              "sequence %d prompt position %d" % (b, s))
                 if due:
                     assert not self.recompute, "prefill parity with a recomputed record: step instead"
                     seq.compress()
             # rows past the sequence's own prompt were not written
-            assert np.all(np.isnan(o_all[u, lengths[b]:]))
+            assert np.all(np.isnan(o_all[:, lengths[b]:]))
             self.consumed[b] = c0 + lengths[b]
             assert self.cache.len_seq(b) == seq.lengths()[:2]
+        del out, probs
         self.check_state()
 
     # -- one ragged decode step ------------------------------------------------------------
@@ -100,17 +105,24 @@ class RaggedParityRun:
         self.probs.fill_(-1.0)
         n_due = self.cache.decode_step_ragged(qs, ks, vs, self.out, self.probs, active=active)
         o_gpu = self.out.float().cpu().numpy().astype(np.float64)
-        p_gpu = self.probs.cpu().numpy()
+        p_gpu = self.probs.cpu().numpy() if len(self.check) == self.batch else None
+        n_trig = self.cache.n_trig
         due_ref = 0
         for b in range(self.batch):
             u = self._units(b)
             if not active[b]:  # units of idle sequences are not touched
-                assert np.all(np.isnan(o_gpu[u])) and np.all(p_gpu[u] == -1.0)
+                assert np.all(np.isnan(o_gpu[u]))
+                assert p_gpu is None or np.all(p_gpu[u] == -1.0)
+                continue
+            if b not in self.check:  # GPU only: its counters still have to follow the schedule
+                self.consumed[b] += 1
+                due_ref += int(self.cache.len_seq(b)[0] == n_trig)
+                self.stats["seq_steps"] += 1
                 continue
             seq = self.oracle.seq[b]
             n = seq.n + 1
             i = self.consumed[b]
-            pf = np.ascontiguousarray(p_gpu[u, :n])
+            pf = (self.probs[u, :n].cpu().numpy() if p_gpu is None else np.ascontiguousarray(p_gpu[u, :n]))
             o_ref, p_ref, due = seq.step(self.hq[u, i], self.hk[u, i], self.hv[u, i], p_forced=pf)
             compare_step(o_gpu[u], o_ref, pf, p_ref[:, :n], self.tol, self.wl.kv_dtype, self.stats,
                          "step %d sequence %d (t=%d)" % (s, b, seq.t))
@@ -146,6 +158,8 @@ class RaggedParityRun:
             if not due[b]:
                 assert np.all(ev_gpu[u] == -1) and np.all(p_all[u] == 0.0)  # untouched
                 continue
+            if b not in self.check:
+                continue
             seq = self.oracle.seq[b]
             n, t, _ = seq.lengths()
             W = min(w, t)
@@ -164,18 +178,27 @@ class RaggedParityRun:
         self.stats["seq_compressions"] += int(due.sum())
 
     def compress(self):
-        due = self.oracle.due()
-        assert due.any()
+        n_trig = self.cache.n_trig
+        due = np.array([self.cache.len_seq(b)[0] == n_trig for b in range(self.batch)])
+        assert due.any() and all(due[b] == self.oracle.due()[b] for b in self.check)
         if self.recompute:
             return self.compress_recompute(due)
         for b in np.flatnonzero(due):
+            if b not in self.check:
+                continue
             n = self.oracle.seq[b].n
             assert np.array_equal(self.gpu_record(b, n), self.oracle.importance(b)), \
                 "sequence %d: importance records differ before its compression" % b
         self.evicted.fill_(-1)
         self.cache.compress_ragged(self.evicted)
-        ev_ref = self.oracle.compress()  # -1 rows for the sequences that were not due
-        assert np.array_equal(self.evicted.cpu().numpy(), ev_ref), "evicted slots differ"
+        ev_gpu = self.evicted.cpu().numpy()
+        for b in range(self.batch):
+            u = self._units(b)
+            if not due[b]:
+                assert np.all(ev_gpu[u] == -1)  # untouched
+            elif b in self.check:
+                assert np.array_equal(ev_gpu[u], self.oracle.seq[b].compress()), \
+                    "sequence %d: evicted slots differ" % b
         self.check_state()
         self.stats["compressions"] += 1
         self.stats["seq_compressions"] += int(due.sum())
@@ -184,7 +207,7 @@ class RaggedParityRun:
         pos = self.cache.pos()
         planes = self.cache.ring() if self.cache.ring_words else self.cache.cnt()
         Kg_all, Vg_all = self.cache.kv_rows()
-        for b in range(self.batch):
+        for b in self.check:
             u = self._units(b)
             seq = self.oracle.seq[b]
             n, t, _ = seq.lengths()

@@ -72,3 +72,22 @@ def test_recomputed_record_at_full_size():
     st = run.run(check_rows_every=2)
     print(st, flush=True)
     assert st["compressions"] == 3
+
+
+def test_ragged_batch_at_full_size():
+    """The headline shape with prompts of different lengths (the mix `bench.py --ragged` times:
+    256 ... 1024 positions) through one sc_prefill_ragged call, then 400 decode steps with every
+    sequence on its own clock; the shortest, a middle and the longest sequence (all their heads)
+    are followed by their oracles at every position, step and compression."""
+    from bench import ragged_prompt_lengths
+
+    from .ragged_util import RaggedParityRun
+
+    wl = CONFIGS[1]
+    plens = ragged_prompt_lengths(wl)
+    steps = 400
+    run = RaggedParityRun(wl, plens, [0] * wl.batch, [steps] * wl.batch, check_seqs=[0, 7, wl.batch - 1])
+    run.prefill()
+    st = run.run()
+    print(st, flush=True)
+    assert st["seq_steps"] == steps * wl.batch and st["seq_compressions"] >= 12
