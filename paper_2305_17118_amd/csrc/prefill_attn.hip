@@ -166,16 +166,17 @@ __device__ __forceinline__ uint32_t quantise_octet(const half8_t x, uint32_t& me
     return word;
 }
 
-// Quantise the run's rows into slots n0.. : 16 lanes per row (8 channels each), 16 rows per
-// workgroup; grid (U, rows/16).
+// Quantise the run's rows into slots n0.. : D/8 lanes per row (8 channels each), 2048/D rows
+// per workgroup; grid (U, rows / (2048/D)).
+template <int D>
 __global__ void __launch_bounds__(256)
 append_rows_i4_kernel(const _Float16* __restrict__ k, const _Float16* __restrict__ v, long unit_stride,
                       unsigned char* __restrict__ K, unsigned char* __restrict__ V,
                       uint32_t* __restrict__ Km, uint32_t* __restrict__ Vm, int32_t* __restrict__ pos,
                       int C, int n0, int c, int t0) {
-    constexpr int D = 128;
-    const int u = blockIdx.x, l8 = threadIdx.x & 15;
-    int row = blockIdx.y * 16 + (threadIdx.x >> 4);
+    constexpr int LPR = D / 8;  // lanes per row
+    const int u = blockIdx.x, l8 = threadIdx.x & (LPR - 1);
+    int row = blockIdx.y * (256 / LPR) + (threadIdx.x / LPR);
     const bool live = row < c;
     row = live ? row : c - 1;  // idle lanes shadow the last row (the reductions need every lane)
     const size_t src = (size_t)u * unit_stride + (size_t)row * D + 8 * l8;
@@ -237,7 +238,7 @@ __device__ __forceinline__ void codes_to_half(uint32_t w, half2_t (&h)[4]) {
 template <int D, bool WITH_PV, int SB, bool I4>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SB == 1 ? 3 : 2)))
 prefill_chunk_kernel(PrefillArgs a) {
-    static_assert(!I4 || D == 128, "4-bit rows: two groups of 64 channels");
+    constexpr int GPR = D / 64;   // 4-bit rows: groups of 64 channels, each with its own scale and zero
     constexpr int KB = 64;        // cache rows per tile
     constexpr int WQ = 16 * SB;   // queries per wave
     constexpr int QB = 4 * WQ;    // queries per workgroup
@@ -323,8 +324,8 @@ prefill_chunk_kernel(PrefillArgs a) {
     // 4-bit rows: codes, and one meta word per row and group
     const unsigned char* Kc = static_cast<const unsigned char*>(a.K) + (size_t)u * a.C * (D / 2);
     const unsigned char* Vc = static_cast<const unsigned char*>(a.V) + (size_t)u * a.C * (D / 2);
-    const uint32_t* Kmb = I4 ? a.K_meta + (size_t)u * a.C * 2 : nullptr;
-    const uint32_t* Vmb = I4 ? a.V_meta + (size_t)u * a.C * 2 : nullptr;
+    const uint32_t* Kmb = I4 ? a.K_meta + (size_t)u * a.C * GPR : nullptr;
+    const uint32_t* Vmb = I4 ? a.V_meta + (size_t)u * a.C * GPR : nullptr;
 
     // Query operand.  4-bit: channels 32*ks + 8*g + {0,4,1,5,2,6,3,7} (the order the codes are
     // unpacked in), plus the sums of q over the two groups for the zero points.
@@ -375,13 +376,14 @@ prefill_chunk_kernel(PrefillArgs a) {
     auto fetch = [&](int kt, bool with_v) {
         const int r0 = kt * KB;
         if constexpr (I4) {
+            if (sp >= D / 32) return;  // rows of 64 channels: two of a row's four threads carry it
             int grow = r0 + srow;
             grow = grow < hi ? grow : hi - 1;  // stay inside rows that hold data
             kcodes = *reinterpret_cast<const u32x4_t*>(Kc + (size_t)grow * (D / 2) + sp * 16);
-            kmreg = Kmb[(size_t)grow * 2 + (sp >> 1)];
+            kmreg = Kmb[(size_t)grow * GPR + (sp >> 1)];
             if (with_v) {
                 vcodes = *reinterpret_cast<const u32x4_t*>(Vc + (size_t)grow * (D / 2) + sp * 16);
-                vmreg = Vmb[(size_t)grow * 2 + (sp >> 1)];
+                vmreg = Vmb[(size_t)grow * GPR + (sp >> 1)];
             }
             return;
         }
@@ -428,6 +430,7 @@ prefill_chunk_kernel(PrefillArgs a) {
     auto stage = [&](bool with_v, int kt) {
         const int r0 = kt * KB;
         if constexpr (I4) {
+            if (sp >= D / 32) return;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 half2_t h[4];
@@ -441,6 +444,7 @@ prefill_chunk_kernel(PrefillArgs a) {
                 MetaWord kw;
                 kw.u32 = kmreg;
                 *reinterpret_cast<float2*>(&Kmeta[srow * 4 + (sp >> 1) * 2]) = make_float2((float)kw.h[0], (float)kw.h[1]);
+                if (GPR == 1) *reinterpret_cast<float2*>(&Kmeta[srow * 4 + 2]) = make_float2(0.f, 0.f);  // no second group
             }
             if (with_v) {
                 MetaWord mw;
@@ -529,9 +533,9 @@ prefill_chunk_kernel(PrefillArgs a) {
         if constexpr (I4) {
 #pragma unroll
             for (int rb = 0; rb < 4; ++rb) {
-                half8_t kf[4];
+                half8_t kf[KS];
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
+                for (int ks = 0; ks < KS; ++ks)
                     kf[ks] = *reinterpret_cast<const half8_t*>(&Ks[(16 * rb + li) * LDK + 32 * ks + 8 * g]);
                 float4_t meta[4];  // transposed: rows 4g + r of the block; plain: row li (entry 0)
                 if constexpr (TRANSPOSED) {
@@ -548,10 +552,12 @@ prefill_chunk_kernel(PrefillArgs a) {
                     for (int ks = 0; ks < 2; ++ks) {
                         if constexpr (TRANSPOSED) {
                             g0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[ks], qB[sb][ks], g0, 0, 0, 0);
-                            g1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[2 + ks], qB[sb][2 + ks], g1, 0, 0, 0);
+                            if constexpr (GPR == 2)
+                                g1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[2 + ks], qB[sb][2 + ks], g1, 0, 0, 0);
                         } else {
                             g0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(qB[sb][ks], kf[ks], g0, 0, 0, 0);
-                            g1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(qB[sb][2 + ks], kf[2 + ks], g1, 0, 0, 0);
+                            if constexpr (GPR == 2)
+                                g1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(qB[sb][2 + ks], kf[2 + ks], g1, 0, 0, 0);
                         }
                     }
 #pragma unroll
@@ -792,8 +798,10 @@ prefill_chunk_kernel(PrefillArgs a) {
 hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t stream) {
     const bool i4 = L.kv_dtype == KV_I4G64;
     if (i4) {
-        const dim3 grid_a(L.U, (c.c + 15) / 16);
-        append_rows_i4_kernel<<<grid_a, 256, 0, stream>>>(
+        const int rows_per_wg = 2048 / L.d;
+        const dim3 grid_a(L.U, (c.c + rows_per_wg - 1) / rows_per_wg);
+        auto* append = L.d == 64 ? append_rows_i4_kernel<64> : append_rows_i4_kernel<128>;
+        append<<<grid_a, 256, 0, stream>>>(
             static_cast<const _Float16*>(c.k), static_cast<const _Float16*>(c.v), c.unit_stride,
             static_cast<unsigned char*>(L.K), static_cast<unsigned char*>(L.V),
             static_cast<uint32_t*>(L.K_meta), static_cast<uint32_t*>(L.V_meta), L.pos, L.C, c.n0, c.c,
@@ -817,7 +825,7 @@ hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t
     a.C = L.C;
     a.n0 = c.n0;
     a.c = c.c;
-    const bool wide = !i4 && c.c > 64;  // two blocks of 16 queries per wave
+    const bool wide = !i4 && c.c > 64;  // two blocks of 16 queries per wave (4-bit: too many registers)
     a.nqb = wide ? (c.c + 127) / 128 : (c.c + 63) / 64;
     a.t0 = c.t0;
     a.counted = c.counted;
@@ -835,8 +843,8 @@ hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t
     a.ring_bits = L.W32 ? L.w : (1 << 30);
     const size_t lds = (size_t)L.C * sizeof(int);
     const unsigned grid = (unsigned)L.U * (unsigned)a.nqb;
-    if (i4 && wide)
-        prefill_chunk_kernel<128, true, 2, true><<<grid, 256, lds, stream>>>(a);
+    if (i4 && L.d == 64)
+        prefill_chunk_kernel<64, true, 1, true><<<grid, 256, lds, stream>>>(a);
     else if (i4)
         prefill_chunk_kernel<128, true, 1, true><<<grid, 256, lds, stream>>>(a);
     else if (L.d == 64 && wide)
@@ -902,7 +910,9 @@ hipError_t launch_recompute_record(const Layout& L, const ReplayArgs& r, hipStre
     a.ring_bits = 1 << 30;
     const size_t lds = (size_t)L.C * sizeof(int);
     const unsigned grid = (unsigned)L.U * (unsigned)a.nqb;
-    if (L.kv_dtype == KV_I4G64)
+    if (L.kv_dtype == KV_I4G64 && L.d == 64)
+        prefill_chunk_kernel<64, false, 1, true><<<grid, 256, lds, stream>>>(a);
+    else if (L.kv_dtype == KV_I4G64)
         prefill_chunk_kernel<128, false, 1, true><<<grid, 256, lds, stream>>>(a);
     else if (L.d == 64 && wide)
         prefill_chunk_kernel<64, false, 2, false><<<grid, 256, lds, stream>>>(a);

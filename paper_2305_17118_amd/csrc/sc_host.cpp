@@ -65,10 +65,8 @@ sc_status derive(const sc_config* cfg, Sizes* s) {
     if (cfg->window_mode != SC_WINDOW_AUTO && cfg->window_mode != SC_WINDOW_RING) return SC_ERR_INVALID_ARG;
     if (cfg->record_mode != SC_RECORD_ONLINE && cfg->record_mode != SC_RECORD_RECOMPUTE)
         return SC_ERR_INVALID_ARG;
-    // The replay kernel exists for fp16 rows and for 4-bit rows of 128 channels.
-    if (cfg->record_mode == SC_RECORD_RECOMPUTE &&
-        !(cfg->kv_dtype == SC_KV_F16 || (cfg->kv_dtype == SC_KV_I4G64 && cfg->head_dim == 128)))
-        return SC_ERR_UNSUPPORTED;
+    // The replay kernel exists for fp16 and 4-bit rows.
+    if (cfg->record_mode == SC_RECORD_RECOMPUTE && cfg->kv_dtype == SC_KV_F32) return SC_ERR_UNSUPPORTED;
     if (cfg->history > 8192) return SC_ERR_UNSUPPORTED;
     const int64_t n_trig =
         cfg->trigger == SC_TRIGGER_HIGH_WATER ? (int64_t)cfg->budget + cfg->drop : (int64_t)cfg->budget + 1;

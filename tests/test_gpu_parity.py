@@ -191,7 +191,9 @@ DENSE_PREFILL = [
     _wl("pf-i4", 1, 4, 128, KV_I4G64, 400, 70, 150, 8, 96, 48, 0.05),       # 4-bit rows quantised by the run
     _wl("pf-i4-long-runs", 2, 2, 128, KV_I4G64, 700, 120, 300, 16, 400, 200, 0.03),
     _wl("pf-i4-ragged", 1, 3, 128, KV_I4G64, 260, 60, 77, 7, 51, 17, 0.1),
-    _wl("pf-i4-d64-streamed", 1, 2, 64, KV_I4G64, 150, 40, 60, 4, 32, 16),  # no dense kernel: streamed inside AUTO
+    _wl("pf-i4-d64", 1, 2, 64, KV_I4G64, 150, 40, 60, 4, 32, 16),           # 4-bit rows of one 64-channel group
+    _wl("pf-i4-d64-long-runs", 2, 3, 64, KV_I4G64, 700, 120, 300, 16, 400, 200, 0.03),
+    _wl("pf-f32-streamed", 1, 2, 64, KV_F32, 150, 40, 60, 4, 32, 16),       # no dense kernel: streamed inside AUTO
 ]
 
 
@@ -218,6 +220,7 @@ RING_PREFILL = [
     _wl("pf-ring-i4", 1, 4, 128, KV_I4G64, 400, 70, 150, 8, 100, 48, 0.05),        # 4-bit rows, ring record
     _wl("pf-ring-i4-paper", 1, 2, 128, KV_I4G64, 700, 300, 400, 10, 400, 200, 0.05),
     _wl("pf-ring-i4-window-33", 2, 2, 128, KV_I4G64, 350, 80, 120, 8, 33, 64, 0.1),
+    _wl("pf-ring-i4-d64", 2, 2, 64, KV_I4G64, 333, 50, 100, 6, 45, 32, 0.05),
 ]
 
 
@@ -290,6 +293,7 @@ RECOMPUTE = [
     _wl("re-i4", 1, 4, 128, KV_I4G64, 150, 100, 100, 7, 32, 16, 0.05),             # 4-bit rows replayed from their codes
     _wl("re-i4-paper-params", 1, 2, 128, KV_I4G64, 300, 400, 200, 10, 400, 100, 0.05),
     _wl("re-i4-window-longer-than-cache", 2, 2, 128, KV_I4G64, 90, 80, 20, 2, 64, 8),
+    _wl("re-i4-d64", 2, 3, 64, KV_I4G64, 120, 90, 50, 4, 70, 10, 0.05),
 ]
 
 
