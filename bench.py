@@ -29,6 +29,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 matrix peak
+MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
 # HBM bytes per decode-attention launch measured with rocprofv3 counters (FETCH_SIZE x 2.000 +
@@ -118,9 +119,10 @@ def prefill_work(wl):
              row when the run counts (4-bit storage: plus the run's fp16 rows read to be
              quantised).
     The traffic of the compressions between runs is not counted (it depends on which rows go)."""
-    from paper_2305_17118_amd.workloads import KV_F16
+    from paper_2305_17118_amd.workloads import KV_F16, KV_F32
     d = wl.head_dim
-    row = d * 2 if wl.kv_dtype == KV_F16 else d // 2 + (d // 64) * 4
+    e_io = 4 if wl.kv_dtype == KV_F32 else 2
+    row = d * 4 if wl.kv_dtype == KV_F32 else d * 2 if wl.kv_dtype == KV_F16 else d // 2 + (d // 64) * 4
     n_trig, m, E = wl.budget + 1, wl.drop, wl.history // wl.drop
     t = n = 0
     rows_attended = 0
@@ -130,8 +132,8 @@ def prefill_work(wl):
         epoch = (a + m - 1) // m if a >= 0 else -((-a) // m)
         c = min(wl.prompt - t, n_trig + epoch * m - t)
         rows_attended += c * n + c * (c + 1) // 2
-        nbytes += (n + c) * 2 * row + c * 2 * row + c * d * 2 * 2
-        if wl.kv_dtype != KV_F16:
+        nbytes += (n + c) * 2 * row + c * 2 * row + c * d * e_io * 2
+        if wl.kv_dtype not in (KV_F16, KV_F32):
             nbytes += c * 2 * d * 2  # the run's fp16 rows are read once more, to be quantised
         if epoch > -E:
             nbytes += (n + c) * 4
@@ -150,16 +152,14 @@ def bench_prefill(args, wl, dev) -> int:
     from paper_2305_17118_amd import binding as B
     from paper_2305_17118_amd.workloads import KV_F16, KV_F32, streams
 
-    if wl.kv_dtype == KV_F32:
-        print("bench.py: the dense prompt phase exists for fp16 and 4-bit storage only", file=sys.stderr)
-        return 2
     cfg = B.make_config(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.budget, wl.recent, wl.history,
                         wl.drop)
     P, d, U = wl.prompt, wl.head_dim, wl.units
     K, W = min(args.steps, 50), min(args.warmup, 3)
     q, k, v = (torch.from_numpy(a).to(dev) for a in streams(wl, steps=P, threads=16))
-    out = torch.empty(U, P, d, dtype=torch.float16, device=dev)
     cache = B.BudgetCache(cfg, dev)
+    out = torch.empty(U, P, d, dtype=cache.io_dtype, device=dev)
+    mfma_peak = MFMA_F32_PEAK_TFLOPS if wl.kv_dtype == KV_F32 else MFMA_F16_PEAK_TFLOPS
 
     def one_pass():
         cache.reset()
@@ -180,7 +180,7 @@ def bench_prefill(args, wl, dev) -> int:
     flops, nbytes = prefill_work(wl)
     # which roofline binds: a run offers only m queries per K/V row read, so with per-unit caches
     # the prompt phase is bound by HBM unless m is large
-    t_mfma, t_hbm = flops / (MFMA_F16_PEAK_TFLOPS * 1e12), nbytes / (HBM_PEAK_GBS * 1e9)
+    t_mfma, t_hbm = flops / (mfma_peak * 1e12), nbytes / (HBM_PEAK_GBS * 1e9)
     hbm_bound = t_hbm >= t_mfma
     tflops = flops / (dev_ms * 1e-3) / 1e12
     gbs = nbytes / (dev_ms * 1e-3) / 1e9
@@ -188,7 +188,7 @@ def bench_prefill(args, wl, dev) -> int:
         "metric": "prompt tokens/s into a budgeted KV cache", "value": wl.batch * P * K / wall,
         "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": wall / K * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16" if wl.kv_dtype == KV_F16 else "i4+f16", "data": "synthetic",
+        "dtype": {KV_F32: "f32", KV_F16: "f16"}.get(wl.kv_dtype, "i4+f16"), "data": "synthetic",
         "config": {"workload": wl.name, "phase": "prefill", "batch": wl.batch, "heads": wl.heads,
                    "head_dim": d, "prompt": P, "budget": wl.budget, "recent": wl.recent,
                    "history": wl.history, "drop": wl.drop, "trigger": "hard_cap"},
@@ -196,14 +196,14 @@ def bench_prefill(args, wl, dev) -> int:
         # this is a lower bound on the attention kernel's own rate
         "roofline": {"bound": "hbm" if hbm_bound else "mfma",
                      "achieved": gbs if hbm_bound else tflops,
-                     "peak": HBM_PEAK_GBS if hbm_bound else MFMA_F16_PEAK_TFLOPS,
+                     "peak": HBM_PEAK_GBS if hbm_bound else mfma_peak,
                      "unit": "GB/s" if hbm_bound else "TFLOP/s",
-                     "frac": gbs / HBM_PEAK_GBS if hbm_bound else tflops / MFMA_F16_PEAK_TFLOPS,
+                     "frac": gbs / HBM_PEAK_GBS if hbm_bound else tflops / mfma_peak,
                      "traffic": None,
                      "kernel": "prefill_chunk_kernel (whole sc_prefill call timed)",
                      "call_ms_avg": dev_ms, "algorithmic_flops_per_call": flops,
                      "algorithmic_bytes_per_call": nbytes, "tflops": tflops,
-                     "mfma_frac": tflops / MFMA_F16_PEAK_TFLOPS, "gbs": gbs,
+                     "mfma_frac": tflops / mfma_peak, "gbs": gbs,
                      "hbm_frac": gbs / HBM_PEAK_GBS},
     }
     print(json.dumps(res))

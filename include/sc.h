@@ -88,7 +88,7 @@ typedef enum {
     SC_RECORD_RECOMPUTE = 1  /* the last w queries are kept; at a compression each is replayed
                                 over the rows resident then that its step could see (stream
                                 position <= its own), softmax over exactly those rows, low =
-                                below that step's threshold.  fp16 and 4-bit storage.           */
+                                below that step's threshold                                     */
 } sc_record;
 
 /* Problem statement of Def. 4.1 / inputs of Alg. 1 and Alg. 2. */
@@ -174,8 +174,8 @@ sc_status sc_compress(sc_cache *c, int32_t *evicted_out, float *probs_out, void 
 /* How sc_prefill computes.  The result is the same function of the inputs either way; the
  * floating-point rounding differs (summation order, fp16 probabilities in P.V). */
 typedef enum {
-    SC_PREFILL_AUTO = 0,     /* dense causal blocks on the matrix cores where supported (fp16 or
-                                4-bit storage, runs of >= 16 positions), else streamed            */
+    SC_PREFILL_AUTO = 0,     /* dense causal blocks on the matrix cores where supported (runs of
+                                >= 16 positions, capacity <= 6144 slots), else streamed           */
     SC_PREFILL_STREAMED = 1  /* one decode step per position: bit-identical to calling
                                 sc_decode_step / sc_compress in a loop                            */
 } sc_prefill_mode;

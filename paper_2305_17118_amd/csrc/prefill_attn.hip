@@ -45,13 +45,13 @@ store_queries_kernel(const char* __restrict__ q, long unit_stride_bytes, char* _
 }
 
 struct PrefillArgs {
-    const _Float16* q;
+    const void* q;  // fp16, or fp32 with fp32 rows
     long unit_stride;
     const void* K;  // fp16 rows, or 4-bit codes
     const void* V;
     const uint32_t* K_meta;  // 4-bit only: {fp16 scale, fp16 zero} per row and 64 channels
     const uint32_t* V_meta;
-    _Float16* out;
+    void* out;  // same element type as q
     long out_unit_stride;
     float* probs;
     long probs_unit_stride;
@@ -69,8 +69,8 @@ struct PrefillArgs {
     // Prompt run with the row copy fused in (fp16): the run's key/value rows as handed in
     // (unit 0; units are unit_stride elements apart) and where their positions go; null
     // when the rows are already in their slots.
-    const _Float16* k_run;
-    const _Float16* v_run;
+    const void* k_run;
+    const void* v_run;
     int32_t* pos_w;
     // Exact one-bit-per-step record instead of counters: uint32 [U][ring_words][C], step i owns
     // bit i mod ring_bits of every row; null with bucket counters.
@@ -235,20 +235,33 @@ __device__ __forceinline__ void codes_to_half(uint32_t w, half2_t (&h)[4]) {
 //
 // I4 = true: 4-bit rows (see above); the rows are already in their slots (quantised by
 // append_rows_i4_kernel), so nothing is read from the caller's arrays or written here.
-template <int D, bool WITH_PV, int SB, bool I4>
+//
+// F32 = true: fp32 rows, queries and outputs.  The same two passes on the fp32 matrix
+// instruction (16x16x4: lane l holds A[l%16][l/16], B[l/16][l%16], D[4(l/16)+r][l%16]):
+// probabilities stay fp32, V is staged row-major (its operand is one float per lane), and
+// tiles go from global memory straight into LDS without a register stage (a path kept for
+// completeness: fp32 rows cost twice the traffic of fp16 ones).
+template <int D, bool WITH_PV, int SB, bool I4, bool F32 = false>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SB == 1 ? 3 : 2)))
 prefill_chunk_kernel(PrefillArgs a) {
+    static_assert(!(I4 && F32) && (!F32 || SB == 1), "fp32 rows: one query block per wave");
     constexpr int GPR = D / 64;   // 4-bit rows: groups of 64 channels, each with its own scale and zero
     constexpr int KB = 64;        // cache rows per tile
     constexpr int WQ = 16 * SB;   // queries per wave
     constexpr int QB = 4 * WQ;    // queries per workgroup
-    constexpr int LDK = D + 8;    // halfs per staged K row (padding keeps 16-byte reads conflict-free)
+    constexpr int LDK = F32 ? D + 4 : D + 8;  // elements per staged K row (the padding keeps operand reads conflict-free)
     constexpr int LDV = KB + 4;   // halfs per channel of the transposed V tile
+    constexpr int LDVF = D + 4;   // fp32: floats per row of the row-major V tile
+    constexpr int KS4 = D / 4;    // fp32: matrix instructions per 16 scores
     constexpr int KS = D / 32;    // matrix instructions per 16 scores
     constexpr int CB = D / 16;    // 16-channel blocks of the output
     constexpr int PIECES = KB * D / 8 / 256;  // 16-byte pieces of a tile per thread
-    __shared__ __align__(16) _Float16 Ks[KB * LDK];
-    __shared__ __align__(16) _Float16 Vt[D * LDV];
+    __shared__ __align__(16) unsigned char ks_raw[KB * LDK * (F32 ? 4 : 2)];
+    __shared__ __align__(16) unsigned char vt_raw[F32 ? KB * LDVF * 4 : D * LDV * 2];
+    _Float16* const Ks = reinterpret_cast<_Float16*>(ks_raw);
+    _Float16* const Vt = reinterpret_cast<_Float16*>(vt_raw);
+    float* const Ksf = reinterpret_cast<float*>(ks_raw);
+    float* const Vsf = reinterpret_cast<float*>(vt_raw);
     __shared__ float stat_m[QB], stat_inv[QB];  // per query: final maximum, 1/sum (pass 1 -> pass 2)
     __shared__ __align__(16) float Kmeta[I4 ? KB * 4 : 4];  // 4-bit: per tile row scale, zero of group 0; of group 1
     __shared__ float stat_q0[I4 ? QB : 1], stat_q1[I4 ? QB : 1];  // 4-bit: per query, sum of q over each group
@@ -318,8 +331,13 @@ prefill_chunk_kernel(PrefillArgs a) {
     const _Float16* Kb = static_cast<const _Float16*>(a.K) + (size_t)u * a.C * D;
     const _Float16* Vb = static_cast<const _Float16*>(a.V) + (size_t)u * a.C * D;
     // rows n0.. of a fused run are read from the caller's arrays
-    const _Float16* Krun = fused ? a.k_run + (size_t)u * a.unit_stride : nullptr;
-    const _Float16* Vrun = fused ? a.v_run + (size_t)u * a.unit_stride : nullptr;
+    const _Float16* Krun = fused ? static_cast<const _Float16*>(a.k_run) + (size_t)u * a.unit_stride : nullptr;
+    const _Float16* Vrun = fused ? static_cast<const _Float16*>(a.v_run) + (size_t)u * a.unit_stride : nullptr;
+    // fp32 rows
+    const float* Kbf = static_cast<const float*>(a.K) + (size_t)u * a.C * D;
+    const float* Vbf = static_cast<const float*>(a.V) + (size_t)u * a.C * D;
+    const float* Krunf = fused ? static_cast<const float*>(a.k_run) + (size_t)u * a.unit_stride : nullptr;
+    const float* Vrunf = fused ? static_cast<const float*>(a.v_run) + (size_t)u * a.unit_stride : nullptr;
 
     // 4-bit rows: codes, and one meta word per row and group
     const unsigned char* Kc = static_cast<const unsigned char*>(a.K) + (size_t)u * a.C * (D / 2);
@@ -330,11 +348,19 @@ prefill_chunk_kernel(PrefillArgs a) {
     // Query operand.  4-bit: channels 32*ks + 8*g + {0,4,1,5,2,6,3,7} (the order the codes are
     // unpacked in), plus the sums of q over the two groups for the zero points.
     half8_t qB[SB][KS];
+    float qF[F32 ? KS4 : 1];  // fp32: q[query li][4*ks + g]
     float qsum0[SB], qsum1[SB];
+    if constexpr (F32) {
+        const long qslot = a.ring_w ? (a.t0 + qc[0]) % a.ring_w : qc[0];
+        const float* qrow = static_cast<const float*>(a.q) + (size_t)u * a.unit_stride + (size_t)qslot * D + g;
 #pragma unroll
-    for (int sb = 0; sb < SB; ++sb) {
+        for (int ks = 0; ks < KS4; ++ks) qF[ks] = qrow[4 * ks];
+        qsum0[0] = qsum1[0] = 0.f;
+    }
+#pragma unroll
+    for (int sb = 0; sb < (F32 ? 0 : SB); ++sb) {
         const long qslot = a.ring_w ? (a.t0 + qc[sb]) % a.ring_w : qc[sb];
-        const _Float16* qrow = a.q + (size_t)u * a.unit_stride + (size_t)qslot * D + 8 * g;
+        const _Float16* qrow = static_cast<const _Float16*>(a.q) + (size_t)u * a.unit_stride + (size_t)qslot * D + 8 * g;
         float part[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -375,6 +401,7 @@ prefill_chunk_kernel(PrefillArgs a) {
     uint32_t kmreg = 0, vmreg = 0;
     auto fetch = [&](int kt, bool with_v) {
         const int r0 = kt * KB;
+        if constexpr (F32) return;  // fp32 tiles go straight to LDS in stage()
         if constexpr (I4) {
             if (sp >= D / 32) return;  // rows of 64 channels: two of a row's four threads carry it
             int grow = r0 + srow;
@@ -429,6 +456,34 @@ prefill_chunk_kernel(PrefillArgs a) {
     _Float16* Vw = const_cast<_Float16*>(Vb);
     auto stage = [&](bool with_v, int kt) {
         const int r0 = kt * KB;
+        if constexpr (F32) {
+            constexpr int P4 = D / 4;  // 16-byte pieces per row
+            const bool keep = writer && with_v && r0 + KB > a.n0;
+            float* Kwf = const_cast<float*>(Kbf);
+            float* Vwf = const_cast<float*>(Vbf);
+#pragma unroll 4
+            for (int p = tid; p < KB * P4; p += 256) {
+                const int row = p / P4, c4 = p - row * P4;
+                int grow = r0 + row;
+                const bool real = grow < hi;
+                grow = real ? grow : hi - 1;  // rows past the data shadow the last one that holds some
+                const bool cached = !fused || grow < a.n0;
+                const size_t off = cached ? (size_t)grow * D + 4 * c4 : (size_t)(grow - a.n0) * D + 4 * c4;
+                const float4_t kv = *reinterpret_cast<const float4_t*>((cached ? Kbf : Krunf) + off);
+                *reinterpret_cast<float4_t*>(&Ksf[row * LDK + 4 * c4]) = kv;
+                const bool store = keep && real && !cached;
+                if (store) {
+                    *reinterpret_cast<float4_t*>(Kwf + (size_t)grow * D + 4 * c4) = kv;
+                    if (c4 == 0) a.pos_w[(size_t)u * a.C + grow] = (int)a.t0 + grow - a.n0;
+                }
+                if (with_v) {
+                    const float4_t vv = *reinterpret_cast<const float4_t*>((cached ? Vbf : Vrunf) + off);
+                    *reinterpret_cast<float4_t*>(&Vsf[row * LDVF + 4 * c4]) = vv;
+                    if (store) *reinterpret_cast<float4_t*>(Vwf + (size_t)grow * D + 4 * c4) = vv;
+                }
+            }
+            return;
+        }
         if constexpr (I4) {
             if (sp >= D / 32) return;
 #pragma unroll
@@ -530,6 +585,21 @@ prefill_chunk_kernel(PrefillArgs a) {
     };
     auto scores = [&](auto transposed, float4_t (&d)[SB][4]) {
         constexpr bool TRANSPOSED = decltype(transposed)::value;
+        if constexpr (F32) {
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) {
+                float4_t acc4 = {0.f, 0.f, 0.f, 0.f};
+                const float* krow = &Ksf[(16 * rb + li) * LDK + g];
+#pragma unroll
+                for (int ks = 0; ks < KS4; ++ks) {
+                    const float kv = krow[4 * ks];  // K[row 16rb+li][channel 4ks+g]: A of S^T, B of S
+                    acc4 = TRANSPOSED ? __builtin_amdgcn_mfma_f32_16x16x4f32(kv, qF[ks], acc4, 0, 0, 0)
+                                      : __builtin_amdgcn_mfma_f32_16x16x4f32(qF[ks], kv, acc4, 0, 0, 0);
+                }
+                d[0][rb] = acc4;
+            }
+            return;
+        }
         if constexpr (I4) {
 #pragma unroll
             for (int rb = 0; rb < 4; ++rb) {
@@ -612,6 +682,7 @@ prefill_chunk_kernel(PrefillArgs a) {
         float4_t d[SB][4];
         scores(Transposed{}, d);
         half4_t ph[SB][4];
+        float4_t pf[F32 ? 4 : 1];  // fp32 rows: the probabilities stay fp32
 #pragma unroll
         for (int sb = 0; sb < SB; ++sb) {
             if (kt * KB + KB - 1 > sub_first_lim[sb]) {  // the causal boundary crosses this tile
@@ -644,10 +715,24 @@ prefill_chunk_kernel(PrefillArgs a) {
                     p[r] = fast_exp2(fmaf(d[sb][rb][r], c2, -m[sb]));
                     lsum[sb] += p[r];
                 }
-                ph[sb][rb] = __builtin_convertvector(p, half4_t);
+                if constexpr (F32) pf[rb] = p;
+                else ph[sb][rb] = __builtin_convertvector(p, half4_t);
             }
         }
-        if constexpr (WITH_PV) {
+        if constexpr (WITH_PV && F32) {
+            // out^T = V^T P^T four cache rows at a time: for rows 16rb + 4g' + r (g' = 0..3) the A
+            // operand is V[that row][channel 16cb + li] and the B operand this lane's p[rb][r].
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float* vrow = &Vsf[(16 * rb + 4 * g + r) * LDVF + li];
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb)
+                        acc[0][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(vrow[16 * cb], pf[rb][r], acc[0][cb], 0, 0, 0);
+                }
+        }
+        if constexpr (WITH_PV && !F32) {
 #pragma unroll
             for (int kp = 0; kp < 2; ++kp) {
                 // The swizzle of the transposed tile decides which of the two 4-row groups of a
@@ -683,10 +768,16 @@ prefill_chunk_kernel(PrefillArgs a) {
         lsum[sb] += __shfl_xor(lsum[sb], 32);
         invL[sb] = 1.0f / lsum[sb];
         if (WITH_PV && a.out && valid[sb]) {
-            _Float16* orow = a.out + (size_t)u * a.out_unit_stride + (size_t)qi[sb] * D + 4 * g;
+            if constexpr (F32) {
+                float* orow = static_cast<float*>(a.out) + (size_t)u * a.out_unit_stride + (size_t)qi[sb] * D + 4 * g;
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
-                *reinterpret_cast<half4_t*>(orow + 16 * cb) = __builtin_convertvector(acc[sb][cb] * invL[sb], half4_t);
+                for (int cb = 0; cb < CB; ++cb) *reinterpret_cast<float4_t*>(orow + 16 * cb) = acc[sb][cb] * invL[sb];
+            } else {
+                _Float16* orow = static_cast<_Float16*>(a.out) + (size_t)u * a.out_unit_stride + (size_t)qi[sb] * D + 4 * g;
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    *reinterpret_cast<half4_t*>(orow + 16 * cb) = __builtin_convertvector(acc[sb][cb] * invL[sb], half4_t);
+            }
         }
     }
     if (!pass2) return;
@@ -810,13 +901,13 @@ hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     PrefillArgs a;
-    a.q = static_cast<const _Float16*>(c.q);
+    a.q = c.q;
     a.unit_stride = c.unit_stride;
     a.K = L.K;
     a.V = L.V;
     a.K_meta = static_cast<const uint32_t*>(L.K_meta);
     a.V_meta = static_cast<const uint32_t*>(L.V_meta);
-    a.out = static_cast<_Float16*>(c.out);
+    a.out = c.out;
     a.out_unit_stride = c.out_unit_stride;
     a.probs = c.probs;
     a.probs_unit_stride = c.probs_unit_stride;
@@ -825,7 +916,8 @@ hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t
     a.C = L.C;
     a.n0 = c.n0;
     a.c = c.c;
-    const bool wide = !i4 && c.c > 64;  // two blocks of 16 queries per wave (4-bit: too many registers)
+    const bool f32 = L.kv_dtype == KV_F32;
+    const bool wide = !i4 && !f32 && c.c > 64;  // two blocks of 16 queries per wave (4-bit: too many registers)
     a.nqb = wide ? (c.c + 127) / 128 : (c.c + 63) / 64;
     a.t0 = c.t0;
     a.counted = c.counted;
@@ -835,15 +927,19 @@ hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t
     a.n_rows = 0;
     a.ring_w = 0;
     // fp16: the run's rows are written into their slots by the attention kernel itself
-    a.k_run = i4 ? nullptr : static_cast<const _Float16*>(c.k);
-    a.v_run = i4 ? nullptr : static_cast<const _Float16*>(c.v);
+    a.k_run = i4 ? nullptr : c.k;
+    a.v_run = i4 ? nullptr : c.v;
     a.pos_w = L.pos;
     a.ring = L.W32 ? reinterpret_cast<uint32_t*>(L.cnt) : nullptr;
     a.ring_words = L.W32;
     a.ring_bits = L.W32 ? L.w : (1 << 30);
     const size_t lds = (size_t)L.C * sizeof(int);
     const unsigned grid = (unsigned)L.U * (unsigned)a.nqb;
-    if (i4 && L.d == 64)
+    if (f32 && L.d == 64)
+        prefill_chunk_kernel<64, true, 1, false, true><<<grid, 256, lds, stream>>>(a);
+    else if (f32)
+        prefill_chunk_kernel<128, true, 1, false, true><<<grid, 256, lds, stream>>>(a);
+    else if (i4 && L.d == 64)
         prefill_chunk_kernel<64, true, 1, true><<<grid, 256, lds, stream>>>(a);
     else if (i4)
         prefill_chunk_kernel<128, true, 1, true><<<grid, 256, lds, stream>>>(a);
@@ -860,15 +956,16 @@ hipError_t launch_prefill_chunk(const Layout& L, const ChunkArgs& c, hipStream_t
 
 hipError_t launch_store_queries(const Layout& L, const void* q, long unit_stride, int count, long t0,
                                 hipStream_t stream) {
-    const int row16 = L.d * 2 / 16;
+    const int eb = L.kv_dtype == KV_F32 ? 4 : 2;
+    const int row16 = L.d * eb / 16;
     const char* src = static_cast<const char*>(q);
     if (count > L.w) {  // only the last w matter
-        src += (size_t)(count - L.w) * L.d * 2;
+        src += (size_t)(count - L.w) * L.d * eb;
         t0 += count - L.w;
         count = L.w;
     }
     const dim3 grid(L.U, (count * row16 + 255) / 256);
-    store_queries_kernel<<<grid, 256, 0, stream>>>(src, unit_stride * 2, static_cast<char*>(L.Qh), L.w, row16,
+    store_queries_kernel<<<grid, 256, 0, stream>>>(src, unit_stride * eb, static_cast<char*>(L.Qh), L.w, row16,
                                                    count, t0);
     return hipGetLastError();
 }
@@ -878,7 +975,7 @@ hipError_t launch_recompute_record(const Layout& L, const ReplayArgs& r, hipStre
     if (err != hipSuccess) return err;
     const int W = r.t < (long)L.w ? (int)r.t : L.w;
     PrefillArgs a;
-    a.q = static_cast<const _Float16*>(L.Qh);
+    a.q = L.Qh;
     a.unit_stride = (long)L.w * L.d;
     a.K = L.K;
     a.V = L.V;
@@ -893,7 +990,7 @@ hipError_t launch_recompute_record(const Layout& L, const ReplayArgs& r, hipStre
     a.C = L.C;
     a.n0 = 0;
     a.c = W;
-    const bool wide = L.kv_dtype != KV_I4G64 && W > 64;
+    const bool wide = L.kv_dtype == KV_F16 && W > 64;
     a.nqb = wide ? (W + 127) / 128 : (W + 63) / 64;
     a.t0 = r.t - W;
     a.counted = 1;
@@ -910,7 +1007,11 @@ hipError_t launch_recompute_record(const Layout& L, const ReplayArgs& r, hipStre
     a.ring_bits = 1 << 30;
     const size_t lds = (size_t)L.C * sizeof(int);
     const unsigned grid = (unsigned)L.U * (unsigned)a.nqb;
-    if (L.kv_dtype == KV_I4G64 && L.d == 64)
+    if (L.kv_dtype == KV_F32 && L.d == 64)
+        prefill_chunk_kernel<64, false, 1, false, true><<<grid, 256, lds, stream>>>(a);
+    else if (L.kv_dtype == KV_F32)
+        prefill_chunk_kernel<128, false, 1, false, true><<<grid, 256, lds, stream>>>(a);
+    else if (L.kv_dtype == KV_I4G64 && L.d == 64)
         prefill_chunk_kernel<64, false, 1, true><<<grid, 256, lds, stream>>>(a);
     else if (L.kv_dtype == KV_I4G64)
         prefill_chunk_kernel<128, false, 1, true><<<grid, 256, lds, stream>>>(a);

@@ -65,8 +65,6 @@ sc_status derive(const sc_config* cfg, Sizes* s) {
     if (cfg->window_mode != SC_WINDOW_AUTO && cfg->window_mode != SC_WINDOW_RING) return SC_ERR_INVALID_ARG;
     if (cfg->record_mode != SC_RECORD_ONLINE && cfg->record_mode != SC_RECORD_RECOMPUTE)
         return SC_ERR_INVALID_ARG;
-    // The replay kernel exists for fp16 and 4-bit rows.
-    if (cfg->record_mode == SC_RECORD_RECOMPUTE && cfg->kv_dtype == SC_KV_F32) return SC_ERR_UNSUPPORTED;
     if (cfg->history > 8192) return SC_ERR_UNSUPPORTED;
     const int64_t n_trig =
         cfg->trigger == SC_TRIGGER_HIGH_WATER ? (int64_t)cfg->budget + cfg->drop : (int64_t)cfg->budget + 1;
@@ -94,7 +92,8 @@ sc_status derive(const sc_config* cfg, Sizes* s) {
     s->off_cnt = off;   off = align_up(off + rows * ((size_t)s->E * 2 + (size_t)s->W32 * 4));
     s->off_qh = off;
     if (s->recompute)
-        off = align_up(off + (size_t)cfg->batch * cfg->heads * (size_t)cfg->history * d * 2);
+        off = align_up(off + (size_t)cfg->batch * cfg->heads * (size_t)cfg->history * d *
+                                 (cfg->kv_dtype == SC_KV_F32 ? 4 : 2));
     s->off_map = off;   off = align_up(off + rows * 4);
     s->off_first = off; off = align_up(off + (size_t)cfg->batch * cfg->heads * 4);
     s->off_seq = off;   off = align_up(off + (size_t)cfg->batch * 4);
@@ -218,7 +217,7 @@ sc::Layout view_of(const sc_cache* c, const sc::Layout& whole, int b0, int b1) {
     L.pos = whole.pos + u0 * C;
     L.cnt = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(whole.cnt) +
                                         u0 * C * ((size_t)whole.E * 2 + (size_t)whole.W32 * 4));
-    if (whole.Qh) L.Qh = static_cast<char*>(whole.Qh) + u0 * (size_t)whole.w * whole.d * 2;
+    if (whole.Qh) L.Qh = static_cast<char*>(whole.Qh) + u0 * (size_t)whole.w * whole.d * elem_bytes(c->cfg);
     L.srcmap = whole.srcmap + u0 * C;
     L.first = whole.first + u0;
     return L;

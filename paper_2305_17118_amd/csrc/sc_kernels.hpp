@@ -164,8 +164,9 @@ struct ChunkArgs {
 // per-slot LDS array that fits beside the tiles.
 inline bool prefill_chunk_supported(int kv_dtype, int d, int E, int W32, int C) {
     if (C > 6144) return false;
-    if (kv_dtype == KV_F16) return E > 0 || W32 > 0;
-    return kv_dtype == KV_I4G64 && (E > 0 || W32 > 0);
+    (void)kv_dtype;
+    (void)d;
+    return E > 0 || W32 > 0;
 }
 
 // Two launches on `stream`: append the run's rows, then attention + counting.

@@ -193,7 +193,10 @@ DENSE_PREFILL = [
     _wl("pf-i4-ragged", 1, 3, 128, KV_I4G64, 260, 60, 77, 7, 51, 17, 0.1),
     _wl("pf-i4-d64", 1, 2, 64, KV_I4G64, 150, 40, 60, 4, 32, 16),           # 4-bit rows of one 64-channel group
     _wl("pf-i4-d64-long-runs", 2, 3, 64, KV_I4G64, 700, 120, 300, 16, 400, 200, 0.03),
-    _wl("pf-f32-streamed", 1, 2, 64, KV_F32, 150, 40, 60, 4, 32, 16),       # no dense kernel: streamed inside AUTO
+    _wl("pf-f32-d64", 1, 2, 64, KV_F32, 150, 40, 60, 4, 32, 16),            # fp32 rows on the fp32 matrix instruction
+    _wl("pf-f32-d128", 2, 2, 128, KV_F32, 400, 70, 150, 8, 96, 48, 0.05),
+    _wl("pf-f32-long-runs", 1, 3, 64, KV_F32, 700, 120, 300, 16, 400, 200, 0.03),
+    _wl("pf-f32-ragged", 1, 3, 128, KV_F32, 260, 60, 77, 7, 51, 17, 0.1),
 ]
 
 
@@ -221,6 +224,8 @@ RING_PREFILL = [
     _wl("pf-ring-i4-paper", 1, 2, 128, KV_I4G64, 700, 300, 400, 10, 400, 200, 0.05),
     _wl("pf-ring-i4-window-33", 2, 2, 128, KV_I4G64, 350, 80, 120, 8, 33, 64, 0.1),
     _wl("pf-ring-i4-d64", 2, 2, 64, KV_I4G64, 333, 50, 100, 6, 45, 32, 0.05),
+    _wl("pf-ring-f32", 2, 2, 64, KV_F32, 333, 50, 100, 6, 45, 32, 0.05),
+    _wl("pf-ring-f32-d128", 1, 2, 128, KV_F32, 350, 80, 120, 8, 33, 64, 0.1),
 ]
 
 
@@ -237,7 +242,7 @@ def test_dense_prefill_with_ring_record_matches_oracle(wl):
 
 @pytest.mark.parametrize("kv,window", [(KV_F16, B.SC_WINDOW_AUTO), (KV_I4G64, B.SC_WINDOW_AUTO),
                                        (KV_F16, B.SC_WINDOW_RING), (KV_F32, B.SC_WINDOW_AUTO)],
-                         ids=["f16", "i4", "f16-ring", "f32-streamed"])
+                         ids=["f16", "i4", "f16-ring", "f32"])
 def test_prefill_continues_a_cache_that_is_not_empty(kv, window):
     """A prompt handed over in chunks, decode steps, then a later turn's prompt: every sc_prefill
     call continues the stream from wherever the cache stands (chunks that start in the middle of
@@ -294,6 +299,8 @@ RECOMPUTE = [
     _wl("re-i4-paper-params", 1, 2, 128, KV_I4G64, 300, 400, 200, 10, 400, 100, 0.05),
     _wl("re-i4-window-longer-than-cache", 2, 2, 128, KV_I4G64, 90, 80, 20, 2, 64, 8),
     _wl("re-i4-d64", 2, 3, 64, KV_I4G64, 120, 90, 50, 4, 70, 10, 0.05),
+    _wl("re-f32-d64", 2, 2, 64, KV_F32, 120, 60, 50, 4, 20, 10),
+    _wl("re-f32-d128", 1, 3, 128, KV_F32, 150, 100, 100, 7, 32, 16, 0.05),
 ]
 
 
@@ -308,7 +315,7 @@ def test_recomputed_record_matches_oracle(wl, thresh):
     assert st["steps"] == wl.total and st["compressions"] >= 3
 
 
-@pytest.mark.parametrize("kv", [KV_F16, KV_I4G64], ids=["f16", "i4"])
+@pytest.mark.parametrize("kv", [KV_F16, KV_I4G64, KV_F32], ids=["f16", "i4", "f32"])
 def test_recomputed_record_after_dense_prefill(kv):
     """The queries of a prompt that went through sc_prefill are kept too: the compressions
     during the decode steps that follow replay them."""

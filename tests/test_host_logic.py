@@ -166,7 +166,7 @@ def test_compression_ratio_of_the_workloads():
     (dict(history=40), 200),                                              # ring record, fp16: dense too
     (dict(history=40, kv_dtype=B.SC_KV_I4G64), 200),                      # ring record, 4-bit: dense too
     (dict(history=40, kv_dtype=B.SC_KV_I4G64, head_dim=64), 200),         # 4-bit rows of 64 channels too
-    (dict(kv_dtype=B.SC_KV_F32, head_dim=64), 200),                       # fp32 rows: streamed
+    (dict(kv_dtype=B.SC_KV_F32, head_dim=64), 200),                       # fp32 rows (fp32 matrix instruction)
 ])
 def test_prefill_plan_follows_the_schedule(kw, prompt):
     """The runs sc_prefill cuts a prompt into, against a position-by-position simulation of
@@ -177,8 +177,7 @@ def test_prefill_plan_follows_the_schedule(kw, prompt):
     n_trig, cap, E, W32 = B.sc_config_sizes(cfg)
     plan = B.sc_prefill_plan(cfg, prompt)
     assert sum(r[0] for r in plan) == prompt and all(r[0] >= 1 for r in plan)
-    dense_capable = (cfg.kv_dtype == B.SC_KV_F16 and (E > 0 or W32 > 0)) or \
-                    (cfg.kv_dtype == B.SC_KV_I4G64 and (E > 0 or W32 > 0))
+    dense_capable = E > 0 or W32 > 0
     t = n = 0
     for length, dense, compress in plan:
         epochs = {B.sc_schedule(cfg, t + 1 + i)[0] for i in range(length)}
@@ -209,7 +208,7 @@ def test_prefill_plan_rejects_bad_arguments():
 
 def test_recomputed_record_configuration():
     """Record rebuilt at compression time: one 16-bit count per slot, a ring of w queries in the
-    workspace, any w (no bucket constraint), fp16 or 4-bit rows."""
+    workspace, any w (no bucket constraint), every storage type."""
     cfg = _cfg(record_mode=B.SC_RECORD_RECOMPUTE, history=37)
     n_trig, cap, E, W32 = B.sc_config_sizes(cfg)
     assert (E, W32) == (1, 0)
@@ -217,13 +216,12 @@ def test_recomputed_record_configuration():
     extra = B.sc_workspace_bytes(cfg) - B.sc_workspace_bytes(online)
     U = 8
     assert abs(extra - (U * 37 * 128 * 2 - U * cap * 2)) <= 4 * 256
-    for kv, d in ((B.SC_KV_F32, 128), (B.SC_KV_F32, 64)):
-        with pytest.raises(B.ScError) as e:
-            B.sc_config_sizes(_cfg(record_mode=B.SC_RECORD_RECOMPUTE, kv_dtype=kv, head_dim=d))
-        assert e.value.status == B.SC_ERR_UNSUPPORTED
-    for d in (64, 128):
-        assert B.sc_config_sizes(_cfg(record_mode=B.SC_RECORD_RECOMPUTE, kv_dtype=B.SC_KV_I4G64,
-                                      head_dim=d))[2:] == (1, 0)
+    for kv in (B.SC_KV_F32, B.SC_KV_I4G64):
+        for d in (64, 128):
+            assert B.sc_config_sizes(_cfg(record_mode=B.SC_RECORD_RECOMPUTE, kv_dtype=kv, head_dim=d))[2:] == (1, 0)
+    f32 = _cfg(record_mode=B.SC_RECORD_RECOMPUTE, history=37, kv_dtype=B.SC_KV_F32)  # fp32 queries: 4 bytes
+    extra32 = B.sc_workspace_bytes(f32) - B.sc_workspace_bytes(_cfg(history=32, kv_dtype=B.SC_KV_F32))
+    assert abs(extra32 - (U * 37 * 128 * 4 - U * cap * 2)) <= 4 * 256
     with pytest.raises(B.ScError) as e:
         B.sc_config_sizes(_cfg(record_mode=3))
     assert e.value.status == B.SC_ERR_INVALID_ARG
