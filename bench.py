@@ -276,22 +276,31 @@ def main() -> int:
 
     cursor = [wl.prompt] * R
     n_log = []
+    # The loop below talks to the C ABI with raw addresses (no tensor views per step): on the
+    # small workload the host would otherwise be slower than the kernel.
+    eb = q.element_size()
+    qp, kp, vp = q.data_ptr(), k.data_ptr(), v.data_ptr()
+    handles = [c.handle for c in caches]
+    out_ptrs = [o.data_ptr() for o in outs]
+    stream = int(torch.cuda.current_stream(dev).cuda_stream)
+    step_ragged, step_lock = B.sc_decode_step_ragged, B.sc_decode_step
+    compress_ragged, compress_lock = B.sc_compress_ragged, B.sc_compress
 
     def one_step(i):
         r = i % R
         s = cursor[r]
         cursor[r] = s + 1
-        c = caches[r]
+        off = s * d * eb
         if args.ragged:  # all sequences take part, each at its own t_b and n_b
-            due = c.decode_step_ragged(q[:, s], k[:, s], v[:, s], outs[r], None, in_stride=T * d)
+            due = step_ragged(handles[r], qp + off, kp + off, vp + off, T * d, out_ptrs[r], None, None, stream)
             n_log.append([rows_after_step(wl, p + s - wl.prompt + 1) for p in plens])
             if due:
-                c.compress_ragged()
+                compress_ragged(handles[r], None, None, stream)
             return 1 if due else 0
-        due = c.decode_step(q[:, s], k[:, s], v[:, s], outs[r], None, in_stride=T * d)
-        n_log.append(c.n)
+        due = step_lock(handles[r], qp + off, kp + off, vp + off, T * d, out_ptrs[r], None, stream)
+        n_log.append(rows_after_step(wl, s + 1))
         if due:
-            c.compress()
+            compress_lock(handles[r], None, None, stream)
         return due
 
     for i in range(W):
