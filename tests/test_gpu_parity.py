@@ -563,3 +563,50 @@ def test_in_place_compaction_equals_out_of_place_gather(kv, d, pattern):
     c1 = cache.cnt()
     assert int(c1[:, live, :nn].abs().max().item()) == 0  # every marked row is gone
     assert int(c1[:, :, nn:].abs().max().item()) == 0 and int(c1[:, 1 - live].abs().max().item()) == 0
+
+
+@pytest.mark.parametrize("kv", [KV_F16, KV_I4G64], ids=["f16", "i4"])
+def test_prefill_can_be_captured_in_a_graph_and_replayed(kv):
+    """The library only enqueues kernels on the caller's stream (no allocation, no memset node,
+    no synchronisation), so a reset + prompt pass can be captured in a HIP graph.  The graph is
+    replayed several times with eager work and synchronisations in between and the cache's own
+    memory scrambled before each replay; every replay must reproduce the eager result bit for bit."""
+    wl = _wl("graph", 2, 3, 128, kv, 0, 330, 100, 8, 64, 32, 0.05)
+    P, U, d = wl.total, wl.units, wl.head_dim
+    q, k, v = (torch.from_numpy(a).cuda() for a in streams(wl))
+    cfg = B.make_config(wl.batch, wl.heads, d, kv, wl.budget, wl.recent, wl.history, wl.drop)
+    eager = B.BudgetCache(cfg)
+    out_e = torch.empty(U, P, d, dtype=torch.float16, device="cuda")
+    eager.prefill(q, k, v, P, 0, out_e)
+    torch.cuda.synchronize()
+    n = eager.n
+
+    def state(c):
+        K, V = c.kv_rows()
+        return [K[:, :n].clone(), V[:, :n].clone(), c.pos()[:, :n].clone(), c.cnt().clone()]
+
+    want = state(eager)
+    cache = B.BudgetCache(cfg)
+    out_g = torch.zeros_like(out_e)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        cache.reset()
+        cache.prefill(q, k, v, P, 0, out_g)
+    assert (cache.n, cache.t) == (eager.n, eager.t)
+    other = B.BudgetCache(cfg)  # eager work between the replays
+    step_out = torch.empty(U, d, dtype=torch.float16, device="cuda")
+    for rep in range(4):
+        cache.workspace.random_(0, 255)  # whatever the previous replay left is gone
+        out_g.fill_(float("nan"))
+        for s in range(5):
+            if other.decode_step(q[:, s], k[:, s], v[:, s], step_out, in_stride=P * d):
+                other.compress()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_e), "replay %d: outputs differ" % rep
+        got = state(cache)
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), "replay %d: cache state differs" % rep
