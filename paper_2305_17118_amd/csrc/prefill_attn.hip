@@ -242,7 +242,8 @@ __device__ __forceinline__ void codes_to_half(uint32_t w, half2_t (&h)[4]) {
 // tiles go from global memory straight into LDS without a register stage (a path kept for
 // completeness: fp32 rows cost twice the traffic of fp16 ones).
 template <int D, bool WITH_PV, int SB, bool I4, bool F32 = false>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SB == 1 ? 3 : 2)))
+__global__ void __launch_bounds__(256)
+__attribute__((amdgpu_waves_per_eu(SB == 1 && !(F32 && D == 128) ? 3 : 2)))  // fp32, d = 128: 67 KB of LDS allow two anyway
 prefill_chunk_kernel(PrefillArgs a) {
     static_assert(!(I4 && F32) && (!F32 || SB == 1), "fp32 rows: one query block per wave");
     constexpr int GPR = D / 64;   // 4-bit rows: groups of 64 channels, each with its own scale and zero
