@@ -114,7 +114,10 @@ typedef struct {
  *   buckets  : E = w/m 16-bit counter buckets kept per row (0 when the exact ring is used;
  *              1 with SC_RECORD_RECOMPUTE: the record itself, rebuilt at every compression)
  *   ring_words : ceil(w/32) 32-bit ring words kept per row (0 when buckets are used)
- * Returns SC_ERR_INVALID_ARG / SC_ERR_UNSUPPORTED for a bad configuration. */
+ * Returns SC_ERR_INVALID_ARG for an inconsistent configuration (m > n_trig - r, sizes < 1,
+ * unknown enum values, more than 2^24 units) and SC_ERR_UNSUPPORTED for one outside what the
+ * kernels cover: head_dim other than 64 or 128, w > 8192, n_trig > 12288 (a unit's scores are
+ * held in LDS during a step), capacity > 6144 with SC_RECORD_RECOMPUTE (the replay's LDS). */
 sc_status sc_config_sizes(const sc_config *cfg, int32_t *n_trig, int32_t *capacity, int32_t *buckets,
                           int32_t *ring_words);
 
