@@ -761,7 +761,9 @@ prefill_chunk_kernel(PrefillArgs a) {
         }
     }
     const bool pass2 = a.counted || a.probs;
-    if (pass2) fetch(0, false);  // in flight while the outputs are written
+    // Pass 2 runs backwards and starts on the K tile that pass 1 left staged; the tile before it
+    // is in flight while the outputs are written.
+    if (pass2 && ntiles > 1) fetch(ntiles - 2, false);
     float invL[SB];
 #pragma unroll
     for (int sb = 0; sb < SB; ++sb) {
@@ -828,11 +830,15 @@ prefill_chunk_kernel(PrefillArgs a) {
             qtau[sb][r] = (qbase + r < a.c && qlim[sb][r] >= 0) ? __fdiv_rn(1.0f, (float)tq) : -1.0f;
         }
     }
-    for (int kt = 0; kt < ntiles; ++kt) {
-        __syncthreads();
-        stage(false, kt);
-        __syncthreads();
-        if (kt + 1 < ntiles) fetch(kt + 1, false);
+    // Last tile first: it is still staged in LDS, and the K rows that pass 1 read last are the
+    // ones most likely still in L2.
+    for (int kt = ntiles - 1; kt >= 0; --kt) {
+        if (kt != ntiles - 1) {
+            __syncthreads();
+            stage(false, kt);
+            __syncthreads();
+            if (kt > 0) fetch(kt - 1, false);
+        }
         if (kt * KB > wave_lim) continue;
         float4_t d[SB][4];
         scores(Plain{}, d);
