@@ -263,3 +263,35 @@ def test_layer_set_workspace_is_the_sum_of_its_layers():
     assert lib.sc_layers_workspace_bytes(ctypes.byref(cfg), 2, arr([64, 0]), None) == 0
     assert lib.sc_layers_workspace_bytes(ctypes.byref(cfg), 0, arr([64]), None) == 0
     assert lib.sc_layers_count(None) == 0 and not lib.sc_layers_get(None, 0)
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/sc.h is the boundary: it must compile as C99 on its own (no C++, no HIP or torch
+    types), and every declared function must be callable with the documented argument types."""
+    import shutil
+    import subprocess
+
+    if shutil.which("gcc") is None:
+        pytest.skip("needs gcc")
+    src = tmp_path / "use_sc.c"
+    src.write_text(
+        '#include "sc.h"\n'
+        "int use(void) {\n"
+        "    sc_config cfg = {1, 1, 64, SC_KV_F16, 8, 1, 4, 2, SC_TRIGGER_HARD_CAP, SC_THRESH_INV_POS,\n"
+        "                     SC_WINDOW_AUTO, SC_RECORD_ONLINE, 0.0f};\n"
+        "    int32_t a, b, c, d;\n"
+        "    sc_cache *h = 0;\n"
+        "    sc_layers *ls = 0;\n"
+        "    int32_t lens[1] = {3};\n"
+        "    uint8_t act[1] = {1};\n"
+        "    if (sc_config_sizes(&cfg, &a, &b, &c, &d) != SC_OK) return 1;\n"
+        "    if (sc_cache_create(&cfg, 0, sc_workspace_bytes(&cfg), 0, &h) == SC_OK) return 2;\n"
+        "    (void)sc_prefill_ragged(h, 0, 0, 0, lens, 0, 0, 0, SC_PREFILL_AUTO, 0);\n"
+        "    (void)sc_decode_step_ragged(h, 0, 0, 0, 0, 0, 0, act, &a, 0);\n"
+        "    (void)sc_compress_ragged(h, 0, 0, 0);\n"
+        "    (void)sc_layers_create(&cfg, 1, lens, 0, 0, 0, 0, &ls);\n"
+        "    return sc_status_str(SC_ERR_FULL) != 0;\n"
+        "}\n")
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
+                        "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
