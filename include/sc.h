@@ -228,6 +228,13 @@ sc_status sc_cache_len(const sc_cache *c, int32_t *n, int64_t *t);
  * sc_compress, sc_prefill, sc_cache_len, sc_diag_kept_mass) return SC_ERR_STATE until
  * sc_cache_reset. */
 
+/* Empty the cache of sequence b alone (n_b = 0, t_b = 0) so that a new request can take its
+ * place in the batch while the other sequences go on (the Alg. 1 loop of that sequence starts
+ * over; a compression it had pending is dropped with it).  Enqueues a clear of that
+ * sequence's counters on `stream`.  Switches the handle to per-sequence counters like the
+ * other ragged calls. */
+sc_status sc_cache_reset_seq(sc_cache *c, int32_t b, void *stream);
+
 /* Host only: the resident rows of a sequence right after its step t (t >= 1, counting the row
  * that step appended, before the compression that may then be due) and whether a compression is
  * due after it, given that every due compression was carried out (Alg. 1).  This closed form is

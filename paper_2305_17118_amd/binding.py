@@ -27,7 +27,7 @@ EXPORTS = (
     "sc_decode_step", "sc_compress", "sc_prefill", "sc_prefill_plan", "sc_cache_len", "sc_cache_view", "sc_status_str",
     "sc_diag_persistence", "sc_diag_kept_mass",
     "sc_prefill_ragged", "sc_decode_step_ragged", "sc_compress_ragged", "sc_cache_len_seq",
-    "sc_schedule_rows",
+    "sc_schedule_rows", "sc_cache_reset_seq",
     "sc_layers_workspace_bytes", "sc_layers_create", "sc_layers_get", "sc_layers_count", "sc_layers_destroy",
 )
 
@@ -80,6 +80,7 @@ def lib():
     l.sc_compress_ragged.argtypes = [vp, vp, vp, vp]
     l.sc_cache_len_seq.argtypes = [vp, C.c_int32, i32p, i64p]
     l.sc_schedule_rows.argtypes = [cfgp, C.c_int64, i32p, i32p]
+    l.sc_cache_reset_seq.argtypes = [vp, C.c_int32, vp]
     l.sc_layers_workspace_bytes.argtypes = [cfgp, C.c_int32, i32p, i32p]
     l.sc_layers_workspace_bytes.restype = C.c_size_t
     l.sc_layers_create.argtypes = [cfgp, C.c_int32, i32p, i32p, vp, C.c_size_t, vp, C.POINTER(vp)]
@@ -192,6 +193,10 @@ def sc_schedule_rows(cfg: sc_config, t: int):
     n, due = C.c_int32(), C.c_int32()
     _check(lib().sc_schedule_rows(C.byref(cfg), int(t), C.byref(n), C.byref(due)), "sc_schedule_rows")
     return n.value, bool(due.value)
+
+
+def sc_cache_reset_seq(handle, b: int, stream=0) -> None:
+    _check(lib().sc_cache_reset_seq(handle, int(b), stream), "sc_cache_reset_seq")
 
 
 def sc_cache_len_seq(handle, b: int):
@@ -314,6 +319,9 @@ class BudgetCache:
     # -- ragged batches: every sequence on its own clock --
     def len_seq(self, b: int):
         return sc_cache_len_seq(self.handle, b)
+
+    def reset_seq(self, b: int) -> None:
+        sc_cache_reset_seq(self.handle, b, self._stream())
 
     def prefill_ragged(self, q, k, v, prompt_len, unit_stride=0, out=None, probs_out=None,
                        mode=SC_PREFILL_AUTO) -> None:

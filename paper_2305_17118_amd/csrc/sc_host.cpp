@@ -518,6 +518,17 @@ sc_status sc_cache_len_seq(const sc_cache* c, int32_t b, int32_t* n, int64_t* t)
     return SC_OK;
 }
 
+sc_status sc_cache_reset_seq(sc_cache* c, int32_t b, void* stream) {
+    if (!c || b < 0 || b >= c->cfg.batch) return SC_ERR_INVALID_ARG;
+    const sc_status st0 = enter_ragged(c);
+    if (st0 != SC_OK) return st0;
+    if (sc::launch_clear_counters(view_of(c, c->L, b, b + 1), static_cast<hipStream_t>(stream)) != hipSuccess)
+        return SC_ERR_DEVICE;
+    c->ts[b] = 0;
+    c->ns[b] = 0;
+    return SC_OK;
+}
+
 sc_status sc_prefill_ragged(sc_cache* c, const void* q, const void* k, const void* v,
                             const int32_t* prompt_len, int64_t unit_stride, void* out, float* probs_out,
                             int32_t mode, void* stream) {

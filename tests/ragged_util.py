@@ -92,6 +92,17 @@ class RaggedParityRun:
         del out, probs
         self.check_state()
 
+    def restart(self, b):
+        """Sequence b has finished: its slot is emptied for a new request (the other sequences
+        keep their state); the oracle side starts a fresh single-sequence oracle."""
+        import dataclasses
+
+        from oracle.sco import Oracle
+
+        self.cache.reset_seq(b)
+        self.oracle.seq[b] = Oracle(dataclasses.replace(self.oracle.cfg, batch=1))
+        assert self.cache.len_seq(b) == (0, 0)
+
     # -- one ragged decode step ------------------------------------------------------------
     def step(self, s):
         active = [self.starts[b] <= s < self.starts[b] + self.decodes[b] for b in range(self.batch)]

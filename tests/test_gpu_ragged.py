@@ -84,6 +84,30 @@ def test_ragged_batch_with_recomputed_record(kv, d, thresh):
     assert st["seq_steps"] == 370 and st["seq_compressions"] >= 8
 
 
+@pytest.mark.parametrize("kv,window", [(KV_F16, B.SC_WINDOW_AUTO), (KV_I4G64, B.SC_WINDOW_RING)],
+                         ids=["f16", "i4-ring"])
+def test_finished_sequence_is_replaced_by_a_new_request(kv, window):
+    """Continuous batching: a sequence that has finished is emptied with sc_cache_reset_seq (while
+    one of them even has a compression pending) and a new request is prefilled into its slot;
+    the other sequences decode on undisturbed, before, between and after."""
+    wl = _wl("rag-reuse", 3, 2, 128, kv, 40, 4, 24, 12, 0.05)
+    # sequence 1 stops after 35 steps; a second request of 52 prompt positions then takes its slot
+    run = RaggedParityRun(wl, [30, 20, 0], [0, 0, 0], [140, 35 + 52 + 60, 140], window_mode=window)
+    run.prefill()
+    run.decodes = [140, 35, 140]
+    for s in range(45):          # sequence 1 is idle from step 35 on
+        if run.step(s):
+            run.compress()
+    run.restart(1)
+    run.prefill(lengths=[0, 52, 0])
+    run.starts, run.decodes = [0, 45, 0], [140, 60, 140]
+    for s in range(45, 140):
+        if run.step(s):
+            run.compress()
+    run.check_state()
+    assert run.stats["seq_compressions"] >= 15
+
+
 def test_ragged_calls_with_equal_lengths_equal_the_lock_step_calls():
     """All sequences active with equal counters: the ragged calls must leave exactly the state and
     outputs of sc_decode_step / sc_compress (same kernels, per-sequence values derived on the device)."""
@@ -140,6 +164,19 @@ def test_ragged_state_machine_errors():
     assert e.value.status == B.SC_ERR_STATE
     c.prefill_ragged(x, x, x, [1, 0])  # a prompt may continue a sequence that is not empty
     assert c.len_seq(0) == (14, 18)
+    for _ in range(3):  # sequence 0 due again (14 + 3 = 17 rows) ...
+        due = c.decode_step_ragged(x, x, x, out, active=[1, 0])
+    assert due == 1
+    c.reset_seq(0)      # ... and dropped with its compression pending: nothing is due any more
+    assert c.len_seq(0) == (0, 0)
+    with pytest.raises(B.ScError) as e:
+        c.compress_ragged()
+    assert e.value.status == B.SC_ERR_STATE
+    assert c.decode_step_ragged(x, x, x, out, active=[1, 1]) == 0
+    assert c.len_seq(0) == (1, 1) and c.len_seq(1) == (1, 1)
+    with pytest.raises(B.ScError) as e:
+        c.reset_seq(2)
+    assert e.value.status == B.SC_ERR_INVALID_ARG
     c.reset()  # back to lock step, empty
     assert (c.n, c.t) == (0, 0)
     assert c.decode_step(x, x, x, out) is False
