@@ -106,6 +106,11 @@ class RaggedParityRun:
     # -- one ragged decode step ------------------------------------------------------------
     def step(self, s):
         active = [self.starts[b] <= s < self.starts[b] + self.decodes[b] for b in range(self.batch)]
+        return self.step_active(active, s)
+
+    def step_active(self, active, s=-1):
+        """One decode step of the sequences flagged in `active`, each consuming its next stream
+        position."""
         if not any(active):
             return 0
         idx = torch.tensor([self.consumed[b] if active[b] else 0 for b in range(self.batch)],

@@ -264,3 +264,53 @@ def test_layer_set_with_growing_budgets_matches_standalone_caches_and_oracle():
     wl = Workload("layer-2", 1300, base.batch, base.heads, d, base.kv_dtype, 0, T, 96, base.recent, base.history, 48, 0.05)
     run = ParityRun(wl)
     run.run()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_serving_trace_matches_oracle(seed):
+    """A serving trace with continuous batching: requests with random prompt lengths arrive in free
+    slots (their prompt sometimes handed over in two chunks), decode for a random number of
+    steps, sit out steps at random, finish and are replaced; every sequence is followed by its
+    own oracle through all of it."""
+    rng = np.random.default_rng(8100 + seed)
+    kv = int(rng.choice([KV_F16, KV_I4G64, KV_F32]))
+    d = 64 if kv == KV_F32 else int(rng.choice([64, 128]))
+    m = int(rng.integers(4, 24))
+    budget = int(rng.integers(2 * m + 4, 2 * m + 60))
+    ring = bool(rng.integers(0, 2))
+    w = int(rng.integers(3, 90)) if ring else m * int(rng.integers(1, 4))
+    r = int(rng.integers(1, budget - m))
+    batch, heads = int(rng.integers(2, 5)), int(rng.integers(1, 4))
+    wl = _wl("rag-serve-%d" % seed, batch, heads, d, kv, budget, r, w, m, 0.05, 1500 + seed)
+    T = 900  # stream positions available per sequence slot
+    run = RaggedParityRun(wl, [0] * batch, [0] * batch, [T] * batch,
+                          trigger=int(rng.choice([B.SC_TRIGGER_HARD_CAP, B.SC_TRIGGER_HIGH_WATER])),
+                          thresh=int(rng.choice([B.SC_THRESH_INV_POS, B.SC_THRESH_INV_LEN])),
+                          window_mode=B.SC_WINDOW_RING if ring else B.SC_WINDOW_AUTO)
+    print("\n", wl, "ring" if ring else "buckets", flush=True)
+    remaining = [0] * batch   # decode steps the request in each slot still wants (0: slot free)
+    requests = 0
+    for step in range(160):
+        for b in range(batch):
+            if remaining[b] == 0 and rng.random() < 0.35 and run.consumed[b] < T - 330:
+                if run.cache.len_seq(b) != (0, 0):
+                    run.restart(b)
+                plen = int(rng.integers(1, 2 * budget))
+                lens = [0] * batch
+                if plen > 3 and rng.random() < 0.5:   # the prompt arrives in two chunks
+                    cut = int(rng.integers(1, plen))
+                    lens[b] = cut
+                    run.prefill(lengths=lens)
+                    lens[b] = plen - cut
+                else:
+                    lens[b] = plen
+                run.prefill(lengths=lens)
+                remaining[b] = int(rng.integers(1, 70))
+                requests += 1
+        active = [remaining[b] > 0 and rng.random() < 0.9 for b in range(batch)]
+        if run.step_active(active, step):
+            run.compress()
+        for b in range(batch):
+            remaining[b] -= int(active[b])
+    run.check_state()
+    assert requests >= batch and run.stats["seq_steps"] > 100
