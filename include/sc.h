@@ -268,6 +268,34 @@ sc_status sc_decode_step_ragged(sc_cache *c, const void *q, const void *k_new, c
                                 int64_t in_stride, void *out, float *probs_out, const uint8_t *active,
                                 int32_t *n_due, void *stream);
 
+/* Replaying a decode step (HIP graphs).  By default the step count travels to the kernels as an
+ * argument, so the work a call enqueues is only valid once.  With the device clock enabled the
+ * count lives in the workspace: sc_decode_step_ragged then enqueues the attention launch, whose
+ * arguments no longer change from step to step, followed by a one-thread launch that advances
+ * the count.  That pair can be captured in a graph and replayed for as long as the same
+ * sequences take part and no compression becomes due, across compressions and prompts handled
+ * by eager calls in between (the caller rewrites q, k_new, v_new in place before each replay):
+ *   1. make one eager call with the active set to be captured (it brings the device table up
+ *      to date, so the captured call contains no table write);
+ *   2. capture one sc_decode_step_ragged call: the handle counts it as a step although nothing
+ *      runs; the first replay executes it;
+ *   3. after every further replay call sc_cache_note_replays(c, 1, ...) (or once with k for k
+ *      replays) so that the host counters follow; sc_steps_until_due says how many steps may
+ *      be taken before a compression (SC_ERR_FULL from sc_cache_note_replays beyond that).
+ * Enabling or disabling switches the handle to per-sequence counters like the other ragged calls. */
+sc_status sc_cache_device_clock(sc_cache *c, int32_t enable);
+
+/* Steps the sequences with active[b] != 0 (all when NULL) can still take before one of them
+ * reaches its trigger size (0: a compression is due now).  Host only. */
+sc_status sc_steps_until_due(const sc_cache *c, const uint8_t *active, int32_t *steps);
+
+/* The work enqueued by the most recent sc_decode_step_ragged call has been executed k more
+ * times (graph replays): advance the counters of the sequences that took part in it.
+ *   n_due : host int or NULL; number of sequences now due
+ * SC_ERR_STATE without the device clock or before any ragged decode step; SC_ERR_FULL (nothing
+ * changed) if k steps would pass a due compression. */
+sc_status sc_cache_note_replays(sc_cache *c, int32_t k, int32_t *n_due);
+
 /* Alg. 2 on the units of every sequence that is due (one launch pair for all of them; with
  * SC_RECORD_RECOMPUTE preceded by one replay of the kept queries per range of due sequences
  * with equal token counts).

@@ -27,7 +27,8 @@ EXPORTS = (
     "sc_decode_step", "sc_compress", "sc_prefill", "sc_prefill_plan", "sc_cache_len", "sc_cache_view", "sc_status_str",
     "sc_diag_persistence", "sc_diag_kept_mass",
     "sc_prefill_ragged", "sc_decode_step_ragged", "sc_compress_ragged", "sc_cache_len_seq",
-    "sc_schedule_rows", "sc_cache_reset_seq",
+    "sc_schedule_rows", "sc_cache_reset_seq", "sc_cache_device_clock", "sc_steps_until_due",
+    "sc_cache_note_replays",
     "sc_layers_workspace_bytes", "sc_layers_create", "sc_layers_get", "sc_layers_count", "sc_layers_destroy",
 )
 
@@ -81,6 +82,9 @@ def lib():
     l.sc_cache_len_seq.argtypes = [vp, C.c_int32, i32p, i64p]
     l.sc_schedule_rows.argtypes = [cfgp, C.c_int64, i32p, i32p]
     l.sc_cache_reset_seq.argtypes = [vp, C.c_int32, vp]
+    l.sc_cache_device_clock.argtypes = [vp, C.c_int32]
+    l.sc_steps_until_due.argtypes = [vp, C.POINTER(C.c_uint8), i32p]
+    l.sc_cache_note_replays.argtypes = [vp, C.c_int32, i32p]
     l.sc_layers_workspace_bytes.argtypes = [cfgp, C.c_int32, i32p, i32p]
     l.sc_layers_workspace_bytes.restype = C.c_size_t
     l.sc_layers_create.argtypes = [cfgp, C.c_int32, i32p, i32p, vp, C.c_size_t, vp, C.POINTER(vp)]
@@ -322,6 +326,20 @@ class BudgetCache:
 
     def reset_seq(self, b: int) -> None:
         sc_cache_reset_seq(self.handle, b, self._stream())
+
+    def device_clock(self, enable: bool = True) -> None:
+        _check(lib().sc_cache_device_clock(self.handle, 1 if enable else 0), "sc_cache_device_clock")
+
+    def steps_until_due(self, active=None) -> int:
+        arr = None if active is None else (C.c_uint8 * len(active))(*[1 if x else 0 for x in active])
+        k = C.c_int32()
+        _check(lib().sc_steps_until_due(self.handle, arr, C.byref(k)), "sc_steps_until_due")
+        return k.value
+
+    def note_replays(self, k: int = 1) -> int:
+        due = C.c_int32()
+        _check(lib().sc_cache_note_replays(self.handle, int(k), C.byref(due)), "sc_cache_note_replays")
+        return due.value
 
     def prefill_ragged(self, q, k, v, prompt_len, unit_stride=0, out=None, probs_out=None,
                        mode=SC_PREFILL_AUTO) -> None:

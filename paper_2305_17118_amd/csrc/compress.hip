@@ -230,6 +230,8 @@ __global__ void __launch_bounds__(256) write_seq_table_kernel(int32_t* __restric
     if ((int)threadIdx.x < count) dst[threadIdx.x] = c.v[threadIdx.x];
 }
 
+__global__ void tick_kernel(int32_t* counter) { *counter += 1; }
+
 }  // namespace
 
 hipError_t launch_write_seq_table(int32_t* dst, const int32_t* host_values, int count, hipStream_t stream) {
@@ -242,6 +244,11 @@ hipError_t launch_write_seq_table(int32_t* dst, const int32_t* host_values, int 
         if (err != hipSuccess) return err;
     }
     return hipSuccess;
+}
+
+hipError_t launch_tick(int32_t* counter, hipStream_t stream) {
+    tick_kernel<<<1, 1, 0, stream>>>(counter);
+    return hipGetLastError();
 }
 
 hipError_t launch_compress(const Layout& L, const CompressArgs& c, hipStream_t stream) {

@@ -72,7 +72,8 @@ struct AttnArgs {
 __device__ __forceinline__ bool seq_apply(AttnArgs& a, int u) {
     const int off = a.seq.off[u / a.seq.heads];
     if (off == kSeqIdle) return false;
-    const SeqStep s = sched_step(a.seq, (long)off + a.seq.step);
+    const int step = a.seq.step_dev ? *a.seq.step_dev + 1 : a.seq.step;
+    const SeqStep s = sched_step(a.seq, (long)off + step);
     a.n = s.n;
     a.pos_value = s.pos_value;
     a.tau = s.tau;

@@ -27,7 +27,10 @@ struct sc_cache {
     std::vector<int32_t> wanted;   // scratch for building the next table
     bool table_known;              // false until the first upload
     int32_t step;                  // ragged decode calls made so far
-    int32_t* seq_off;              // device [batch]
+    int32_t* seq_off;              // device [batch], followed by the device-side step count
+    bool device_clock;             // ragged decode launches read the step count from the device
+    bool step_dev_known;           // the device-side count equals `step`
+    std::vector<uint8_t> last_active;  // sequences of the most recent ragged decode step
     size_t row_bytes, meta_bytes;  // per K (or V) row, for views of a range of sequences
 };
 
@@ -96,7 +99,7 @@ sc_status derive(const sc_config* cfg, Sizes* s) {
                                  (cfg->kv_dtype == SC_KV_F32 ? 4 : 2));
     s->off_map = off;   off = align_up(off + rows * 4);
     s->off_first = off; off = align_up(off + (size_t)cfg->batch * cfg->heads * 4);
-    s->off_seq = off;   off = align_up(off + (size_t)cfg->batch * 4);
+    s->off_seq = off;   off = align_up(off + ((size_t)cfg->batch + 1) * 4);
     s->total = off;
     return SC_OK;
 }
@@ -234,6 +237,8 @@ sc_status enter_ragged(sc_cache* c) {
     c->wanted.assign(B, sc::kSeqIdle);
     c->table_known = false;
     c->step = 0;
+    c->step_dev_known = false;
+    c->last_active.assign(B, 0);
     c->ragged = true;
     return SC_OK;
 }
@@ -250,6 +255,7 @@ sc::SeqSched make_sched(const sc_cache* c, int32_t step) {
     q.W32 = c->L.W32;
     q.thresh_len = c->cfg.thresh_mode == SC_THRESH_INV_LEN;
     q.recompute = c->L.Qh != nullptr;
+    q.step_dev = nullptr;
     return q;
 }
 
@@ -403,6 +409,8 @@ sc_status sc_cache_create(const sc_config* cfg, void* dev_workspace, size_t byte
     c->ragged = false;
     c->table_known = false;
     c->step = 0;
+    c->device_clock = false;
+    c->step_dev_known = false;
     c->seq_off = reinterpret_cast<int32_t*>(base + s.off_seq);
     c->row_bytes = s.row_bytes;
     c->meta_bytes = s.meta_bytes;
@@ -427,6 +435,7 @@ sc_status sc_cache_reset(sc_cache* c, void* stream) {
     c->ragged = false;
     c->table_known = false;
     c->step = 0;
+    c->step_dev_known = false;
     return SC_OK;
 }
 
@@ -630,15 +639,66 @@ sc_status sc_decode_step_ragged(sc_cache* c, const void* q, const void* k_new, c
     a.tau = 0.f;
     a.q_keep = c->L.Qh;  // kept queries: the kernels pick each sequence's own ring slot
     a.seq = make_sched(c, c->step + 1);
+    if (c->device_clock) {
+        int32_t* step_dev = c->seq_off + B;
+        if (!c->step_dev_known) {
+            if (sc::launch_write_seq_table(step_dev, &c->step, 1, s) != hipSuccess) return SC_ERR_DEVICE;
+            c->step_dev_known = true;
+        }
+        a.seq.step_dev = step_dev;
+        a.seq.step = 0;
+    }
     if (sc::launch_decode_step(c->L, a, s) != hipSuccess) return SC_ERR_DEVICE;
+    if (c->device_clock && sc::launch_tick(c->seq_off + B, s) != hipSuccess) return SC_ERR_DEVICE;
     c->step += 1;
     int32_t due = 0;
     for (int b = 0; b < B; ++b) {
+        c->last_active[b] = c->wanted[b] != sc::kSeqIdle;
         if (c->wanted[b] == sc::kSeqIdle) continue;
         c->ts[b] += 1;
         c->ns[b] += 1;
         due += c->ns[b] == c->n_trig;
     }
+    if (n_due) *n_due = due;
+    return SC_OK;
+}
+
+sc_status sc_cache_device_clock(sc_cache* c, int32_t enable) {
+    if (!c) return SC_ERR_INVALID_ARG;
+    const sc_status st0 = enter_ragged(c);
+    if (st0 != SC_OK) return st0;
+    c->device_clock = enable != 0;
+    c->step_dev_known = false;
+    return SC_OK;
+}
+
+sc_status sc_steps_until_due(const sc_cache* c, const uint8_t* active, int32_t* steps) {
+    if (!c || !steps) return SC_ERR_INVALID_ARG;
+    int32_t least = INT32_MAX;
+    for (int b = 0; b < c->cfg.batch; ++b) {
+        if (active && !active[b]) continue;
+        least = std::min<int32_t>(least, c->n_trig - (c->ragged ? c->ns[b] : c->n));
+    }
+    if (least == INT32_MAX) return SC_ERR_INVALID_ARG;
+    *steps = least;
+    return SC_OK;
+}
+
+sc_status sc_cache_note_replays(sc_cache* c, int32_t k, int32_t* n_due) {
+    if (!c || k < 0) return SC_ERR_INVALID_ARG;
+    if (!c->ragged || !c->device_clock || c->step == 0) return SC_ERR_STATE;
+    const int B = c->cfg.batch;
+    for (int b = 0; b < B; ++b)
+        if (c->last_active[b] && c->ns[b] + k > c->n_trig) return SC_ERR_FULL;
+    int32_t due = 0;
+    for (int b = 0; b < B; ++b) {
+        if (c->last_active[b]) {
+            c->ts[b] += k;
+            c->ns[b] += k;
+        }
+        due += c->ns[b] == c->n_trig;
+    }
+    c->step += k;
     if (n_due) *n_due = due;
     return SC_OK;
 }

@@ -40,6 +40,9 @@ constexpr int32_t kSeqIdle = INT32_MIN;  // table entry of a sequence that does 
 struct SeqSched {
     const int32_t* off;  // device [batch], or null: all units in lock step (scalar arguments apply)
     int step;            // t_b = off[b] + step is the step being computed (decode) or just computed (compress)
+    const int32_t* step_dev;  // decode only: when not null the device keeps the count of completed
+                              // steps and t_b = off[b] + *step_dev + 1 (`step` is ignored); a launch
+                              // whose arguments do not change from step to step can be replayed
     int heads;           // units per sequence
     int n_trig, m, w;    // trigger size, rows dropped per compression, history window
     int E, W32;          // record layout (buckets, or ring words)
@@ -102,6 +105,9 @@ __host__ __device__ inline SeqStep sched_step(const SeqSched& s, long t1) {
 
 // Write `count` table entries (host values) to device memory on `stream`.
 hipError_t launch_write_seq_table(int32_t* dst, const int32_t* host_values, int count, hipStream_t stream);
+
+// *counter += 1 on `stream` (the device-side step count of ragged batches).
+hipError_t launch_tick(int32_t* counter, hipStream_t stream);
 
 struct StepArgs {
     const void* q;

@@ -314,3 +314,68 @@ def test_random_serving_trace_matches_oracle(seed):
             remaining[b] -= int(active[b])
     run.check_state()
     assert requests >= batch and run.stats["seq_steps"] > 100
+
+
+@pytest.mark.parametrize("kv", [KV_F16, KV_I4G64], ids=["f16", "i4"])
+def test_decode_step_replayed_from_a_graph_with_the_device_clock(kv):
+    """With the step count kept on the device one captured sc_decode_step_ragged call is replayed
+    for every step between compressions, and again after each (eager) compression, with the
+    inputs rewritten in place; outputs and the final cache must equal, bit for bit, those of a
+    twin cache stepped eagerly with the step count passed as an argument."""
+    wl = _wl("rag-graph", 3, 2, 128, kv, 40, 4, 24, 12, 0.05)
+    T, U, d = 260, wl.units, wl.head_dim
+    q, k, v = (torch.from_numpy(a).cuda() for a in streams(wl, steps=T))
+    cfg = B.make_config(wl.batch, wl.heads, d, kv, wl.budget, wl.recent, wl.history, wl.drop)
+    eager, graphed = B.BudgetCache(cfg), B.BudgetCache(cfg)
+    plens = [30, 0, 17]
+    for c in (eager, graphed):
+        c.prefill_ragged(q, k, v, plens, T * d, None)
+    graphed.device_clock(True)
+    qs, ks, vs = (torch.empty(U, d, dtype=torch.float16, device="cuda") for _ in range(3))  # static inputs
+    out_e = torch.empty(U, d, dtype=torch.float16, device="cuda")
+    out_g = torch.empty_like(out_e)
+    start = 40  # stream position of the first decode step (past every prompt)
+
+    def load(s):
+        qs.copy_(q[:, s]); ks.copy_(k[:, s]); vs.copy_(v[:, s])
+
+    # 1. an eager step brings the device table up to date
+    load(start)
+    assert eager.decode_step_ragged(qs, ks, vs, out_e) == graphed.decode_step_ragged(qs, ks, vs, out_g)
+    assert torch.equal(out_e, out_g)
+    # 2. capture one call (counted as a step; the first replay executes it)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        due_g = graphed.decode_step_ragged(qs, ks, vs, out_g)
+    pending_first_replay = True
+    comps = 0
+    for s in range(start + 1, T):
+        load(s)
+        due_e = eager.decode_step_ragged(qs, ks, vs, out_e)
+        if pending_first_replay:
+            pending_first_replay = False
+        else:
+            assert graphed.steps_until_due() >= 1
+            due_g = graphed.note_replays(1)
+        g.replay()
+        torch.cuda.synchronize()
+        assert due_g == due_e and torch.equal(out_e, out_g), "step %d" % s
+        if due_e:
+            with pytest.raises(B.ScError) as e:
+                graphed.note_replays(1)  # not past a due compression
+            assert e.value.status == B.SC_ERR_FULL
+            eager.compress_ragged()
+            graphed.compress_ragged()   # eager; the same graph goes on afterwards
+            comps += 1
+    assert comps >= 10
+    for b in range(wl.batch):
+        assert eager.len_seq(b) == graphed.len_seq(b)
+    assert torch.equal(eager.cnt(), graphed.cnt())
+    Ka, Va = eager.kv_rows()
+    Kb, Vb = graphed.kv_rows()
+    for b in range(wl.batch):
+        u, nb = slice(b * wl.heads, (b + 1) * wl.heads), eager.len_seq(b)[0]
+        assert torch.equal(eager.pos()[u, :nb], graphed.pos()[u, :nb])
+        assert torch.equal(Ka[u, :nb], Kb[u, :nb]) and torch.equal(Va[u, :nb], Vb[u, :nb])
