@@ -610,3 +610,20 @@ def test_prefill_can_be_captured_in_a_graph_and_replayed(kv):
         got = state(cache)
         for a, b in zip(got, want):
             assert torch.equal(a, b), "replay %d: cache state differs" % rep
+
+
+@pytest.mark.parametrize("batch,heads,kv,d,budget", [
+    (1, 1, KV_F16, 128, 700),     # a single unit
+    (1, 32, KV_F16, 128, 520),    # batch 1 of the headline shape
+    (3, 24, KV_F32, 64, 300),
+    (2, 80, KV_F16, 64, 290),
+    (1, 5, KV_F32, 128, 255),
+])
+def test_few_units_with_many_rows(batch, heads, kv, d, budget):
+    """Small batches with long caches (the shape of low-latency serving): a streamed prompt, then
+    decode steps and compressions, over row counts that are no multiple of anything."""
+    wl = _wl("few-units", batch, heads, d, kv, 0, budget + 150, budget, 9, 70, 35, 0.05)
+    run = ParityRun(wl)
+    run.prefill(budget - 40, mode=B.SC_PREFILL_STREAMED)
+    st = run.run()
+    assert st["steps"] == wl.total and st["compressions"] >= 4

@@ -27,6 +27,23 @@ CASES = [
 ]
 
 
+LONG_CASES = [
+    # few units with long caches
+    (_wl("rag-long-f16", 3, 4, 128, KV_F16, 330, 8, 64, 32, 0.05), [300, 40, 0], [0, 0, 10], [120, 150, 100]),
+    (_wl("rag-long-f32", 2, 3, 64, KV_F32, 280, 6, 40, 20), [270, 5], [0, 0], [90, 110]),
+]
+
+
+@pytest.mark.parametrize("wl,prompts,starts,decodes", LONG_CASES, ids=[c[0].name for c in LONG_CASES])
+@pytest.mark.parametrize("window", [B.SC_WINDOW_AUTO, B.SC_WINDOW_RING], ids=["buckets", "ring"])
+def test_ragged_batch_of_few_units_with_long_caches(wl, prompts, starts, decodes, window):
+    """Ragged batches of few units whose sequences hold hundreds of rows of very different counts."""
+    run = RaggedParityRun(wl, prompts, starts, decodes, window_mode=window)
+    run.prefill()
+    st = run.run()
+    assert st["seq_steps"] == sum(decodes) and st["seq_compressions"] >= 3
+
+
 @pytest.mark.parametrize("wl,prompts,starts,decodes", CASES, ids=[c[0].name for c in CASES])
 @pytest.mark.parametrize("trigger", [B.SC_TRIGGER_HARD_CAP, B.SC_TRIGGER_HIGH_WATER], ids=["cap", "hw"])
 def test_ragged_batch_matches_per_sequence_oracles(wl, prompts, starts, decodes, trigger):
