@@ -136,6 +136,27 @@ select_evict_kernel(const uint16_t* __restrict__ cnt, int32_t* __restrict__ srcm
 // row of slot srcmap[i], for i in [first, n_new).  In place: elements are handled in
 // ascending chunks, a chunk is loaded completely before any of it is stored, and a row's
 // source never lies below its destination, so no store can hit data still to be read.
+// Rows are read once and written once per compression: non-temporal accesses keep them from
+// displacing anything in the caches.
+typedef uint32_t u32x4_nt __attribute__((ext_vector_type(4)));
+template <typename VT>
+__device__ __forceinline__ VT nt_load(const VT* p) {
+    if constexpr (sizeof(VT) == 16) {
+        const u32x4_nt v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(p));
+        return __builtin_bit_cast(VT, v);
+    } else {
+        return __builtin_nontemporal_load(p);
+    }
+}
+template <typename VT>
+__device__ __forceinline__ void nt_store(VT* p, VT v) {
+    if constexpr (sizeof(VT) == 16) {
+        __builtin_nontemporal_store(__builtin_bit_cast(u32x4_nt, v), reinterpret_cast<u32x4_nt*>(p));
+    } else {
+        __builtin_nontemporal_store(v, p);
+    }
+}
+
 template <typename VT, int UNR>
 __device__ __forceinline__ void compact_array(VT* base, int lanes_per_row, const int32_t* srcmap,
                                               int first, int n_new) {
@@ -151,14 +172,14 @@ __device__ __forceinline__ void compact_array(VT* base, int lanes_per_row, const
             if (e < total) {
                 const int row = first + e / lanes_per_row;
                 const int ln = e - (row - first) * lanes_per_row;
-                val[x] = base[(size_t)srcmap[row] * lanes_per_row + ln];
+                val[x] = nt_load(&base[(size_t)srcmap[row] * lanes_per_row + ln]);
                 dst_idx[x] = row * lanes_per_row + ln;
             }
         }
         __syncthreads();
 #pragma unroll
         for (int x = 0; x < UNR; ++x)
-            if (dst_idx[x] >= 0) base[dst_idx[x]] = val[x];
+            if (dst_idx[x] >= 0) nt_store(&base[dst_idx[x]], val[x]);
     }
     __syncthreads();
 }
