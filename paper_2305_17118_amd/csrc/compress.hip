@@ -204,7 +204,7 @@ struct CompactArgs {
 // grid (U, 3): part 0 moves K (+K_meta), part 1 moves V (+V_meta), part 2 moves positions and
 // counters, then clears the counters of the freed tail slots and of the bucket that the next
 // epoch counts into.
-__global__ void __launch_bounds__(256) compact_kernel(CompactArgs a) {
+__global__ void __launch_bounds__(1024) compact_kernel(CompactArgs a) {
     const int u = blockIdx.x, part = blockIdx.y;
     if (a.seq.off) {  // ragged batch: only due sequences, each clearing the bucket its next epoch counts into
         if (!seq_due(a.seq, u)) return;
@@ -304,7 +304,10 @@ hipError_t launch_compress(const Layout& L, const CompressArgs& c, hipStream_t s
     a.n_new = c.n - c.m;
     a.zero_bucket = c.zero_bucket;
     a.seq = c.seq;
-    compact_kernel<<<dim3(L.U, 3), 256, 0, stream>>>(a);
+    // Lock step: every unit compacts, 256 threads per workgroup keep eight of them on a CU.  Ragged
+    // batches: only the units of the due sequences work, often a single sequence's; a workgroup
+    // then needs all the loads in flight it can have (1024 threads) to move its unit quickly.
+    compact_kernel<<<dim3(L.U, 3), c.seq.off ? 1024 : 256, 0, stream>>>(a);
     return hipGetLastError();
 }
 
