@@ -305,9 +305,10 @@ hipError_t launch_compress(const Layout& L, const CompressArgs& c, hipStream_t s
     a.zero_bucket = c.zero_bucket;
     a.seq = c.seq;
     // Lock step: every unit compacts, 256 threads per workgroup keep eight of them on a CU.  Ragged
-    // batches: only the units of the due sequences work, often a single sequence's; a workgroup
-    // then needs all the loads in flight it can have (1024 threads) to move its unit quickly.
-    compact_kernel<<<dim3(L.U, 3), c.seq.off ? 1024 : 256, 0, stream>>>(a);
+    // batches (only the units of the due sequences work, often a single sequence's) and small
+    // ones: a workgroup then needs all the loads in flight it can have (1024 threads) to move its
+    // unit quickly.
+    compact_kernel<<<dim3(L.U, 3), (c.seq.off || L.U <= 256) ? 1024 : 256, 0, stream>>>(a);
     return hipGetLastError();
 }
 
