@@ -48,7 +48,9 @@ typedef enum {
     SC_ERR_FULL = 3,        /* sc_decode_step while a compression is due                      */
     SC_ERR_STATE = 4,       /* sc_compress when none is due; lock-step call on a ragged handle */
     SC_ERR_UNSUPPORTED = 5, /* head_dim / kv_dtype / sizes this build does not cover          */
-    SC_ERR_DEVICE = 6       /* a kernel launch failed (hipGetLastError)                       */
+    SC_ERR_DEVICE = 6,      /* a kernel launch failed (hipGetLastError)                       */
+    SC_ERR_SCRATCH = 7      /* sc_compress_static: the cache needs more scratch than the
+                               library's static array holds (SC_STATIC_SCRATCH_BYTES)          */
 } sc_status;
 
 /* Storage format of the cached K/V rows. */
@@ -173,6 +175,27 @@ sc_status sc_decode_step(sc_cache *c, const void *q, const void *k_new, const vo
  *                 test was applied to; other elements are untouched
  * SC_ERR_STATE unless the previous step reported compress_due. */
 sc_status sc_compress(sc_cache *c, int32_t *evicted_out, float *probs_out, void *stream);
+
+/* sc_compress for callers that can neither allocate device memory nor hand over scratch of
+ * their own: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same result, same kernels as sc_compress; the only difference is
+ * where the hand-over between selection and compaction lives (per unit: the source slot of
+ * every surviving row and the first slot that moves).  sc_compress keeps it in the caller's
+ * workspace; this call keeps it in a file-scope device array of SC_STATIC_SCRATCH_BYTES that is
+ * part of the library's code object (every GPU the library runs on holds its own copy until
+ * the process ends).  The call allocates and frees nothing, on the host or on the device.
+ *   Limit.    256*ceil(4*U/256) + 4*U*capacity bytes must fit in SC_STATIC_SCRATCH_BYTES
+ *             (cfg4's 9216 units x 704 slots need 24.8 MiB); otherwise SC_ERR_SCRATCH and
+ *             nothing is enqueued or changed.
+ *   Sharing.  Every call on a GPU uses that GPU's one array, on whatever cache: two calls that
+ *             may run at the same time on one GPU (different streams, or graphs replayed
+ *             concurrently) race.  Calls ordered on one stream are safe.  Nothing in the array
+ *             has to start at zero: selection writes every element compaction reads.
+ *   Device.   The array is looked up on the device that is current (hipGetDevice) when the
+ *             call is made; that must be the device of `stream` and of the cache.
+ * SC_ERR_STATE unless the previous step reported compress_due, or on a ragged handle. */
+#define SC_STATIC_SCRATCH_BYTES (32u << 20)
+sc_status sc_compress_static(sc_cache *c, int32_t *evicted_out, float *probs_out, void *stream);
 
 /* How sc_prefill computes.  The result is the same function of the inputs either way; the
  * floating-point rounding differs (summation order, fp16 probabilities in P.V). */

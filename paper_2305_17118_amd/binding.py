@@ -13,7 +13,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libsc.so")
 
 SC_OK, SC_ERR_INVALID_ARG, SC_ERR_WORKSPACE, SC_ERR_FULL, SC_ERR_STATE, SC_ERR_UNSUPPORTED, \
-    SC_ERR_DEVICE = range(7)
+    SC_ERR_DEVICE, SC_ERR_SCRATCH = range(8)
+SC_STATIC_SCRATCH_BYTES = 32 << 20
 SC_KV_F32, SC_KV_F16, SC_KV_I4G64 = 0, 1, 2
 SC_TRIGGER_HARD_CAP, SC_TRIGGER_HIGH_WATER = 0, 1
 SC_THRESH_INV_POS, SC_THRESH_INV_LEN = 0, 1
@@ -24,7 +25,7 @@ SC_RECORD_ONLINE, SC_RECORD_RECOMPUTE = 0, 1
 EXPORTS = (
     "sc_config_sizes", "sc_workspace_bytes", "sc_schedule", "sc_cache_create", "sc_cache_reset",
     "sc_cache_destroy",
-    "sc_decode_step", "sc_compress", "sc_prefill", "sc_prefill_plan", "sc_cache_len", "sc_cache_view", "sc_status_str",
+    "sc_decode_step", "sc_compress", "sc_compress_static", "sc_prefill", "sc_prefill_plan", "sc_cache_len", "sc_cache_view", "sc_status_str",
     "sc_diag_persistence", "sc_diag_kept_mass",
     "sc_prefill_ragged", "sc_decode_step_ragged", "sc_compress_ragged", "sc_cache_len_seq",
     "sc_schedule_rows", "sc_cache_reset_seq", "sc_cache_device_clock", "sc_steps_until_due",
@@ -70,6 +71,7 @@ def lib():
     l.sc_cache_destroy.restype = None
     l.sc_decode_step.argtypes = [vp, vp, vp, vp, C.c_int64, vp, vp, i32p, vp]
     l.sc_compress.argtypes = [vp, vp, vp, vp]
+    l.sc_compress_static.argtypes = [vp, vp, vp, vp]
     l.sc_prefill.argtypes = [vp, vp, vp, vp, C.c_int32, C.c_int64, vp, vp, C.c_int32, vp]
     l.sc_prefill_plan.argtypes = [cfgp, C.c_int32, C.c_int32, C.c_int32, i32p, i32p, i32p, i32p]
     l.sc_cache_len.argtypes = [vp, i32p, i64p]
@@ -166,6 +168,10 @@ def sc_decode_step(handle, q_ptr, k_ptr, v_ptr, in_stride, out_ptr, probs_ptr=No
 
 def sc_compress(handle, evicted_ptr=None, probs_ptr=None, stream=0) -> None:
     _check(lib().sc_compress(handle, evicted_ptr, probs_ptr, stream), "sc_compress")
+
+
+def sc_compress_static(handle, evicted_ptr=None, probs_ptr=None, stream=0) -> None:
+    _check(lib().sc_compress_static(handle, evicted_ptr, probs_ptr, stream), "sc_compress_static")
 
 
 def sc_prefill(handle, q_ptr, k_ptr, v_ptr, prompt_len, unit_stride, out_ptr=None, probs_ptr=None,
@@ -313,6 +319,10 @@ class BudgetCache:
     def compress(self, evicted_out=None, probs_out=None) -> None:
         sc_compress(self.handle, None if evicted_out is None else evicted_out.data_ptr(),
                     None if probs_out is None else probs_out.data_ptr(), self._stream())
+
+    def compress_static(self, evicted_out=None, probs_out=None) -> None:
+        sc_compress_static(self.handle, None if evicted_out is None else evicted_out.data_ptr(),
+                           None if probs_out is None else probs_out.data_ptr(), self._stream())
 
     def prefill(self, q, k, v, prompt_len, unit_stride=0, out=None, probs_out=None,
                 mode=SC_PREFILL_AUTO) -> None:

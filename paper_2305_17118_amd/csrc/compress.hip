@@ -3,8 +3,20 @@
 // per-row array.  All of it is integer / byte work and exact.
 #include "sc_kernels.hpp"
 
+#include <mutex>
+
 namespace sc {
 namespace {
+
+// Scratch owned by the library (select -> compact hand-over: `first` then `srcmap`), for the
+// one entry point whose callers cannot provide or allocate any.  In host code this name is
+// only a handle for hipGetSymbolAddress; every device holds its own copy at its own address,
+// looked up once per device in static_scratch() below.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, null until looked up
 
 constexpr int SEL_THREADS = 256;
 constexpr int SEL_WAVES = SEL_THREADS / 64;
@@ -254,6 +266,23 @@ __global__ void __launch_bounds__(256) write_seq_table_kernel(int32_t* __restric
 __global__ void tick_kernel(int32_t* counter) { *counter += 1; }
 
 }  // namespace
+
+hipError_t static_scratch(void** ptr) {
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess) return err;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 hipError_t launch_write_seq_table(int32_t* dst, const int32_t* host_values, int count, hipStream_t stream) {
     for (int base = 0; base < count; base += 256) {

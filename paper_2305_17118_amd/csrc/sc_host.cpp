@@ -40,6 +40,8 @@ struct sc_layers {
 
 namespace {
 
+static_assert(SC_STATIC_SCRATCH_BYTES == sc::kStaticScratchBytes, "sc.h and the kernels disagree");
+
 constexpr size_t kAlign = 256;
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -467,6 +469,25 @@ sc_status sc_compress(sc_cache* c, int32_t* evicted_out, float* probs_out, void*
     return compress_impl(c, evicted_out, probs_out, static_cast<hipStream_t>(stream));
 }
 
+sc_status sc_compress_static(sc_cache* c, int32_t* evicted_out, float* probs_out, void* stream) {
+    if (!c) return SC_ERR_INVALID_ARG;
+    if (c->ragged || c->n != c->n_trig) return SC_ERR_STATE;
+    // `first` [U] then `srcmap` [U][C], both 256-byte aligned inside the library's array.
+    const size_t first_bytes = align_up((size_t)c->L.U * sizeof(int32_t));
+    const size_t need = first_bytes + (size_t)c->L.U * (size_t)c->L.C * sizeof(int32_t);
+    if (need > sc::kStaticScratchBytes) return SC_ERR_SCRATCH;
+    void* base = nullptr;
+    if (sc::static_scratch(&base) != hipSuccess) return SC_ERR_DEVICE;
+    int32_t* const ws_map = c->L.srcmap;
+    int32_t* const ws_first = c->L.first;
+    c->L.first = static_cast<int32_t*>(base);
+    c->L.srcmap = reinterpret_cast<int32_t*>(static_cast<char*>(base) + first_bytes);
+    const sc_status st = compress_impl(c, evicted_out, probs_out, static_cast<hipStream_t>(stream));
+    c->L.srcmap = ws_map;
+    c->L.first = ws_first;
+    return st;
+}
+
 sc_status sc_prefill(sc_cache* c, const void* q, const void* k, const void* v, int32_t prompt_len,
                      int64_t unit_stride, void* out, float* probs_out, int32_t mode, void* stream) {
     if (!c || !q || !k || !v || prompt_len < 1) return SC_ERR_INVALID_ARG;
@@ -858,6 +879,7 @@ const char* sc_status_str(sc_status s) {
         case SC_ERR_STATE: return "call not legal in the current cache state";
         case SC_ERR_UNSUPPORTED: return "configuration not supported by this build";
         case SC_ERR_DEVICE: return "kernel launch failed";
+        case SC_ERR_SCRATCH: return "cache needs more scratch than the library's static array holds";
     }
     return "unknown status";
 }

@@ -145,6 +145,13 @@ struct CompressArgs {
 
 hipError_t launch_compress(const Layout& L, const CompressArgs& a, hipStream_t stream);
 
+// Scratch for select -> compact that belongs to the library instead of the caller's workspace: a
+// file-scope device array of kStaticScratchBytes, one copy per device.  Returns its address on
+// the current device (looked up with hipGetSymbolAddress the first time a device asks, kept
+// afterwards); allocates nothing.
+constexpr size_t kStaticScratchBytes = 32u << 20;
+hipError_t static_scratch(void** ptr);
+
 // A run of `c` consecutive prompt positions with no compression inside and a single counter
 // bucket (the host cuts the prompt accordingly), processed as one dense causal block.
 struct ChunkArgs {
