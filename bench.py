@@ -3,18 +3,21 @@
 
 A "step" is one pass of the whole hot path over one batch: sc_decode_step (append + budgeted
 attention + importance-record update, one kernel) followed by sc_compress whenever the cache
-has reached its trigger size.  The workload is the OPT-6.7B-shaped single layer (batch 16,
-32 heads, head_dim 128, fp16, 1024-token prompt put through sc_prefill, then decoding
-under budget 1024).  Because one layer's cache (269 MB) is about the size of the chip's
-last-level cache and is re-read every step, R independent cache instances are stepped
-round-robin (as the layers of a model would be), so every step finds its cache cold in HBM.
+has reached its trigger size.  The headline workload is the largest of the five that fits one
+GPU, the OPT-66B-shaped single layer (batch 128, 72 heads, head_dim 128, fp16, 2048-token
+prompt, then decoding under budget 683); `per_config` carries the same measurement for all
+five workloads.  R >= 4 independent cache instances are stepped round-robin (as the layers of
+a model would be), enough of them that every step finds its cache cold in HBM, and before the
+timed region each instance is advanced (untimed) to a different phase of the m-step
+compression cycle, so that a short run sees the same mix of resident rows as a long one.
 tokens/s = batch * steps / wall time, a step being one layer-instance step.
 
 Prints ONE JSON line: metric / value / unit (whole-job decode tokens/s, inputs resident in
 HBM), ms_per_step, config (the workload), roofline (algorithmic bytes per decode-attention
 launch / its average duration from HIP events on the launch stream, against the 8 TB/s HBM
-peak; traffic = HBM bytes per launch from rocprofv3 counters where measured) and cpu_baseline
-(the CPU oracle timed on the host cores on the same decode phase).
+peak; traffic = HBM bytes per launch from rocprofv3 counters when they were taken on exactly
+these launches, else null), per_config (the five workloads) and cpu_baseline (the CPU oracle
+timed on the host cores on a sample of the same decode phase).
 """
 from __future__ import annotations
 
@@ -33,9 +36,12 @@ MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
 # HBM bytes per decode-attention launch measured with rocprofv3 counters (FETCH_SIZE x 2.000 +
-# WRITE_SIZE x 1.000, factors from a copy of known size) for the headline workload in this
-# launch configuration; see profiles/attn_rows_fp16_cfg2_hbm_traffic.md.  Other workloads: null.
-MEASURED_TRAFFIC_BYTES = {"cfg2-opt6.7b-fp16": 253.59e6}
+# WRITE_SIZE x 1.000, factors from a copy of known size), keyed by workload and by the exact
+# timed region they were taken on (steps, warmup, average resident rows): reported only when the
+# current run timed the same launches, else `traffic` is null.  Sources: profiles/*hbm_traffic*.
+MEASURED_TRAFFIC = {
+    # workload: (steps, warmup, resident_rows_avg, bytes per launch)
+}
 
 
 def algorithmic_bytes(wl, n: int) -> int:
@@ -210,72 +216,78 @@ def bench_prefill(args, wl, dev) -> int:
     return 0
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1500)
-    ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = headline)")
-    ap.add_argument("--rotate", type=int, default=0, help="cache instances stepped round-robin "
-                    "(0 = enough to cover three times the 256 MB last-level cache)")
-    ap.add_argument("--phase", choices=("decode", "prefill"), default="decode",
-                    help="decode = the headline metric; prefill = the prompt phase (fp16 workloads)")
-    ap.add_argument("--window", choices=("auto", "ring"), default="auto",
-                    help="importance record: bucket counters (auto, when w is a multiple of m) or "
-                         "the exact one-bit-per-step ring")
-    ap.add_argument("--record", choices=("online", "recompute"), default="online",
-                    help="importance record kept during the steps (headline) or rebuilt at each "
-                         "compression by replaying the last w queries (fp16 workloads)")
-    ap.add_argument("--ragged", action="store_true",
-                    help="decode phase with prompts of different lengths (every sequence on its own "
-                         "clock: sc_prefill_ragged / sc_decode_step_ragged / sc_compress_ragged)")
-    ap.add_argument("--no-events", action="store_true", help="skip the per-launch HIP events")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-units", type=int, default=512)
-    ap.add_argument("--cpu-steps", type=int, default=1024)
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (units are independent, so sharding over "
-              "GPUs needs no collective and is not part of this build); run with --gpus 1",
-              file=sys.stderr)
-        return 2
+def copy_probe(args, dev) -> int:
+    """Plain device copies of known size (torch's own copy kernel, one dispatch each, reading
+    and writing exactly --copy-mib MiB), for calibrating HBM traffic counters: run under
+    `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` it shows what the counters report for a
+    known number of bytes, the scale factor applied to the decode kernel's counters."""
+    import torch
 
+    n = args.copy_mib * 2 ** 20
+    src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    reps = max(1, min(args.steps, 20))
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    print(json.dumps({"probe": "device copy", "mib": args.copy_mib, "dispatches": reps + 1,
+                      "us_per_dispatch": dt * 1e6, "read_gbs": n / dt / 1e9, "write_gbs": n / dt / 1e9}))
+    return 0
+
+
+def pick_instances(ws_bytes: int, rotate: int) -> int:
+    """Cache instances stepped round-robin: at least four (phases of the compression cycle), and
+    enough that their total footprint is three times the 256 MB last-level cache."""
+    return rotate or min(8, max(4, -(-3 * 256 * 2 ** 20 // ws_bytes)))
+
+
+def run_decode(wl, args, K, W, dev, streams_dev=None):
+    """Time K decode steps (after W untimed ones) of workload `wl`; -> dict of measurements."""
     import torch
 
     from paper_2305_17118_amd import binding as B
-    from paper_2305_17118_amd.workloads import CONFIGS, KV_F32, KV_F16, streams
+    from paper_2305_17118_amd.workloads import KV_F32, KV_F16, streams
 
-    wl = CONFIGS[args.config - 1]
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    if args.phase == "prefill":
-        return bench_prefill(args, wl, dev)
     cfg = B.make_config(wl.batch, wl.heads, wl.head_dim, wl.kv_dtype, wl.budget, wl.recent, wl.history,
                         wl.drop, window_mode=B.SC_WINDOW_RING if args.window == "ring" else B.SC_WINDOW_AUTO,
                         record_mode=B.SC_RECORD_RECOMPUTE if args.record == "recompute" else B.SC_RECORD_ONLINE)
-    ws_bytes = B.sc_workspace_bytes(cfg)
-    R = args.rotate or min(8, max(1, -(-3 * 256 * 2 ** 20 // ws_bytes)))
-    T, d, U = wl.total, wl.head_dim, wl.units
-    steps_avail = R * wl.decode
-    K, W = args.steps, args.warmup
-    if W + K > steps_avail:
-        K = steps_avail - W
-        print("bench.py: only %d decode steps exist for %d instances; timing %d" % (steps_avail, R, K),
-              file=sys.stderr)
+    R = pick_instances(B.sc_workspace_bytes(cfg), args.rotate)
+    T, d, U, m = wl.total, wl.head_dim, wl.units, wl.drop
+    # Phase offsets: instance r is advanced by floor(r*span/R) decode steps before the timed
+    # region; span covers one compression cycle where the decode phase is long enough.
+    need = -(-(K + W) // R)
+    if need > wl.decode:
+        K = R * wl.decode - W
+        need = wl.decode
+        print("bench.py: %s has only %d decode steps for %d instances; timing %d"
+              % (wl.name, R * wl.decode, R, K), file=sys.stderr)
+    span = 0 if args.ragged else max(0, min(m, wl.decode - need))
+    offsets = [r * span // R for r in range(R)]
 
-    q, k, v = (torch.from_numpy(a).to(dev) for a in streams(wl, threads=16))
+    if streams_dev is None:
+        streams_dev = tuple(torch.from_numpy(a).to(dev) for a in streams(wl, threads=16))
+    q, k, v = streams_dev
     caches = [B.BudgetCache(cfg, dev) for _ in range(R)]
     outs = [torch.empty(U, d, dtype=caches[0].io_dtype, device=dev) for _ in range(R)]
     plens = ragged_prompt_lengths(wl) if args.ragged else None
+    # The prompt goes through sc_prefill except for its last m positions, which are stepped one
+    # by one like the decode steps that follow (the prompt is the first part of one stream), so
+    # that the compression inside them can be timed on its own.
+    tail = 0 if args.ragged else min(m, wl.prompt - 1)
     for c in caches:
         if args.ragged:
             c.prefill_ragged(q, k, v, plens, T * d, None)
         else:
-            c.prefill(q, k, v, wl.prompt, T * d, None)
+            c.prefill(q, k, v, wl.prompt - tail, T * d, None)
     torch.cuda.synchronize()
 
-    cursor = [wl.prompt] * R
+    cursor = [wl.prompt - tail] * R
     n_log = []
+    compress_pairs = []  # HIP events around sc_compress calls outside the timed region
     # The loop below talks to the C ABI with raw addresses (no tensor views per step): on the
     # small workload the host would otherwise be slower than the kernel.
     eb = q.element_size()
@@ -286,8 +298,7 @@ def main() -> int:
     step_ragged, step_lock = B.sc_decode_step_ragged, B.sc_decode_step
     compress_ragged, compress_lock = B.sc_compress_ragged, B.sc_compress
 
-    def one_step(i):
-        r = i % R
+    def one_step(r, time_compress=False):
         s = cursor[r]
         cursor[r] = s + 1
         off = s * d * eb
@@ -300,11 +311,21 @@ def main() -> int:
         due = step_lock(handles[r], qp + off, kp + off, vp + off, T * d, out_ptrs[r], None, stream)
         n_log.append(rows_after_step(wl, s + 1))
         if due:
-            compress_lock(handles[r], None, None, stream)
+            if time_compress:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                compress_lock(handles[r], None, None, stream)
+                e1.record()
+                compress_pairs.append((e0, e1))
+            else:
+                compress_lock(handles[r], None, None, stream)
         return due
 
+    for r in range(R):  # untimed: rest of the prompt, then this instance's phase offset
+        for _ in range(tail + offsets[r]):
+            one_step(r, time_compress=True)
     for i in range(W):
-        one_step(i)
+        one_step(i % R)
     n_log.clear()
     # HIP events on the launch stream bracket groups of GROUP consecutive decode-attention
     # launches; groups in which a compression ran are left out of the kernel average.
@@ -322,7 +343,7 @@ def main() -> int:
             e0.record()
         dirty = 0
         for j in range(g):
-            dirty += one_step(W + i + j)
+            dirty += one_step((W + i + j) % R)
         if use_events:
             e1.record()
             groups.append((e0, e1, g, dirty == 0, list(n_log[-g:])))
@@ -340,18 +361,127 @@ def main() -> int:
     else:
         alg = sum(algorithmic_bytes(wl, n) for n in n_log) / len(n_log)
         kern_ms, achieved = None, None
+    compress_ms = (sum(a.elapsed_time(b) for a, b in compress_pairs) / len(compress_pairs)
+                   if compress_pairs else None)
+    # Compressions per decode step over the workload's whole decode phase (hard-cap trigger:
+    # due after steps t = n_trig + k*m), and the throughput with their measured cost spread over
+    # the steps between them.
+    n_trig = wl.budget + 1
+    in_decode = sum(1 for t in range(wl.prompt + 1, wl.total + 1) if t >= n_trig and (t - n_trig) % m == 0)
+    per_step = in_decode / wl.decode
+    step_ms = kern_ms if kern_ms is not None else wall / K * 1e3
+    amortised = (wl.batch / ((step_ms + (compress_ms or 0.0) * per_step) * 1e-3)
+                 if (compress_ms is not None or per_step == 0) else None)
     if wl.kv_dtype in (KV_F32, KV_F16):
         kernel_name = "attn_rows_kernel"
     else:
         kernel_name = "attn_i4_mfma_kernel" if wl.head_dim == 128 else "attn_i4_kernel"
+    rows_avg = (sum(sum(x) / len(x) for x in n_log) if args.ragged else sum(n_log)) / len(n_log)
+    for c in caches:
+        c.close()
+    return {
+        "workload": wl.name, "wl": wl, "K": K, "W": W, "R": R, "wall": wall, "offsets": offsets,
+        "tokens_per_s": wl.batch * K / wall, "ms_per_step": wall / K * 1e3,
+        "kernel": kernel_name, "kernel_ms_avg": kern_ms, "alg": alg, "achieved": achieved,
+        "frac": None if achieved is None else achieved / HBM_PEAK_GBS,
+        "compress_events": compress_events, "rows_avg": rows_avg, "plens": plens,
+        "compress_ms_avg": compress_ms, "compress_samples": len(compress_pairs),
+        "compressions_per_decode_step": per_step, "tokens_per_s_amortised": amortised,
+    }
+
+
+def config_summary(m) -> dict:
+    """One entry of `per_config`."""
+    return {
+        "workload": m["workload"], "steps": m["K"], "cache_instances_round_robin": m["R"],
+        "kernel": m["kernel"], "kernel_ms_avg": m["kernel_ms_avg"],
+        "algorithmic_bytes_per_launch": m["alg"], "achieved_gbs": m["achieved"], "frac": m["frac"],
+        "resident_rows_avg": m["rows_avg"], "tokens_per_s": m["tokens_per_s"],
+        "ms_per_step": m["ms_per_step"], "compress_ms_avg": m["compress_ms_avg"],
+        "compressions_per_decode_step": m["compressions_per_decode_step"],
+        "tokens_per_s_amortised": m["tokens_per_s_amortised"],
+        "compressions_in_timed_region": m["compress_events"],
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=96)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--config", type=int, default=4, help="headline workload 1..5 (4 = the largest)")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size "
+                    "(few-unit batches; the line is then not the workload's own)")
+    ap.add_argument("--rotate", type=int, default=0, help="cache instances stepped round-robin "
+                    "(0 = at least 4 and enough to cover three times the 256 MB last-level cache)")
+    ap.add_argument("--phase", choices=("decode", "prefill", "copy"), default="decode",
+                    help="decode = the headline metric; prefill = the prompt phase; copy = plain "
+                         "device copies of --copy-mib MiB (calibration of HBM traffic counters)")
+    ap.add_argument("--copy-mib", type=int, default=1024)
+    ap.add_argument("--window", choices=("auto", "ring"), default="auto",
+                    help="importance record: bucket counters (auto, when w is a multiple of m) or "
+                         "the exact one-bit-per-step ring")
+    ap.add_argument("--record", choices=("online", "recompute"), default="online",
+                    help="importance record kept during the steps (headline) or rebuilt at each "
+                         "compression by replaying the last w queries")
+    ap.add_argument("--ragged", action="store_true",
+                    help="decode phase with prompts of different lengths (every sequence on its own "
+                         "clock: sc_prefill_ragged / sc_decode_step_ragged / sc_compress_ragged)")
+    ap.add_argument("--no-events", action="store_true", help="skip the per-launch HIP events")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true", help="time the headline workload only")
+    ap.add_argument("--per-config-steps", type=int, default=200,
+                    help="timed steps of each per_config entry other than the headline's")
+    ap.add_argument("--cpu-units", type=int, default=0, help="units of the oracle sample (0 = sized "
+                    "for about 20 s of CPU work)")
+    ap.add_argument("--cpu-steps", type=int, default=1024)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (units are independent, so sharding over "
+              "GPUs needs no collective and is not part of this build); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2305_17118_amd.workloads import CONFIGS
+
+    wl = CONFIGS[args.config - 1]
+    if args.batch:
+        wl = wl.scaled(batch=args.batch, name="%s-batch%d" % (wl.name, args.batch))
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    if args.phase == "prefill":
+        return bench_prefill(args, wl, dev)
+    if args.phase == "copy":
+        return copy_probe(args, dev)
+
+    head = run_decode(wl, args, args.steps, args.warmup, dev)
+    K, W = head["K"], head["W"]
+    torch.cuda.empty_cache()
+    variant = args.batch or args.ragged or args.window != "auto" or args.record != "online"
+    per_config = []
+    if not args.no_per_config and not variant:
+        for other in CONFIGS:
+            if other.name == wl.name:
+                per_config.append(config_summary(head))
+                continue
+            m = run_decode(other, args, args.per_config_steps, args.warmup, dev)
+            per_config.append(config_summary(m))
+            del m
+            torch.cuda.empty_cache()
+    traffic = None
+    known = MEASURED_TRAFFIC.get(wl.name)
+    if known and not variant and (K, W) == known[:2] and abs(head["rows_avg"] - known[2]) < 0.05:
+        traffic = known[3]
     res = {
         "metric": "decode tokens/s with budgeted KV cache",
-        "value": wl.batch * K / wall,
+        "value": head["tokens_per_s"],
         "unit": "tokens/s",
         "n_gpus": 1,
         "steps": K,
         "warmup": W,
-        "ms_per_step": wall / K * 1e3,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -361,20 +491,30 @@ def main() -> int:
             "workload": wl.name, "batch": wl.batch, "heads": wl.heads, "head_dim": wl.head_dim,
             "prompt": wl.prompt, "decode": wl.decode, "budget": wl.budget, "recent": wl.recent,
             "history": wl.history, "drop": wl.drop, "trigger": "hard_cap", "window": args.window, "record": args.record,
-            "cache_instances_round_robin": R, "compressions_in_timed_region": compress_events,
-            "resident_rows_avg": (sum(sum(x) / len(x) for x in n_log) if args.ragged else sum(n_log)) / len(n_log),
+            "cache_instances_round_robin": head["R"], "instance_phase_offsets": head["offsets"],
+            "compressions_in_timed_region": head["compress_events"],
+            "resident_rows_avg": head["rows_avg"],
         },
         "roofline": {
-            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": None if achieved is None else achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if R == 3 and not args.ragged else None,
-            "kernel": kernel_name, "kernel_ms_avg": kern_ms, "algorithmic_bytes_per_launch": alg,
+            "bound": "hbm", "achieved": head["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": head["frac"], "traffic": traffic,
+            "kernel": head["kernel"], "kernel_ms_avg": head["kernel_ms_avg"],
+            "algorithmic_bytes_per_launch": head["alg"],
         },
+        # sc_compress (select + compact) timed with HIP events on the compressions of the untimed
+        # set-up phase; amortised = batch / (attention launch + compress_ms_avg * compressions per
+        # decode step of the workload's decode phase)
+        "compress_ms_avg": head["compress_ms_avg"], "compress_samples": head["compress_samples"],
+        "compressions_per_decode_step": head["compressions_per_decode_step"],
+        "tokens_per_s_amortised": head["tokens_per_s_amortised"],
     }
+    if per_config:
+        res["per_config"] = per_config
     if args.ragged:
-        res["config"]["ragged_prompt_lengths"] = plens
+        res["config"]["ragged_prompt_lengths"] = head["plens"]
     if not args.no_cpu_baseline and not args.ragged:
-        res["cpu_baseline"] = cpu_baseline(wl, args.cpu_units, args.cpu_steps)
+        units = args.cpu_units or {1: 12, 2: 512, 3: 128, 4: 64, 5: 64}[wl.config_id]
+        res["cpu_baseline"] = cpu_baseline(wl, units, args.cpu_steps)
     print(json.dumps(res))
     return 0
 
