@@ -377,6 +377,9 @@ def run_decode(wl, args, K, W, dev, streams_dev=None):
     else:
         kernel_name = "attn_i4_mfma_kernel" if wl.head_dim == 128 else "attn_i4_kernel"
     rows_avg = (sum(sum(x) / len(x) for x in n_log) if args.ragged else sum(n_log)) / len(n_log)
+    lifetimes = None
+    if args.lifetimes and cursor[0] < T:
+        lifetimes = workgroup_lifetimes(B, handles[0], U, dev, lambda: one_step(0), args.lifetimes_dump)
     for c in caches:
         c.close()
     return {
@@ -387,6 +390,56 @@ def run_decode(wl, args, K, W, dev, streams_dev=None):
         "compress_events": compress_events, "rows_avg": rows_avg, "plens": plens,
         "compress_ms_avg": compress_ms, "compress_samples": len(compress_pairs),
         "compressions_per_decode_step": per_step, "tokens_per_s_amortised": amortised,
+        "lifetimes": lifetimes,
+    }
+
+
+def workgroup_lifetimes(B, handle, U, dev, step, dump=None) -> dict:
+    """One more decode step with sc_diag_trace switched on: when every workgroup of the launch
+    started, ended its K/V stream and finished (microseconds after the first start), overall and
+    per XCD."""
+    import torch
+
+    buf = torch.zeros(U, 4, dtype=torch.int64, device=dev)
+    B.sc_diag_trace(handle, buf.data_ptr())
+    step()
+    torch.cuda.synchronize()
+    B.sc_diag_trace(handle, None)
+    t = buf.cpu().numpy()
+    if dump:
+        import numpy
+        numpy.save(dump, t)
+    t = t[t[:, 2] > 0]
+    if len(t) == 0:
+        return None
+    import numpy as np
+    origin = t[:, 0].min()
+    us = (t[:, :3] - origin) / 100.0  # 100 MHz clock
+    q = lambda x: [round(float(v), 2) for v in np.percentile(x, [0, 5, 50, 95, 100])]
+    where = t[:, 3] & 0xFFFFFFFF
+    xcd = where >> 6
+    # Waves that shared a SIMD (same XCD / shader engine / CU / SIMD id): does the one that
+    # started first also finish first?  (rank correlation of start order and end order)
+    simd = (where << 2) | ((t[:, 3] >> 36) & 3)
+    same_order = pairs = 0
+    for sid in np.unique(simd):
+        rows = us[simd == sid]
+        for a in range(len(rows)):
+            for b in range(a + 1, len(rows)):
+                if rows[a, 0] != rows[b, 0]:
+                    pairs += 1
+                    same_order += (rows[a, 0] < rows[b, 0]) == (rows[a, 2] < rows[b, 2])
+    spread_in_simd = [float(us[simd == sid, 2].max() - us[simd == sid, 2].min()) for sid in np.unique(simd)]
+    return {
+        "workgroups": int(len(t)), "percentiles": [0, 5, 50, 95, 100],
+        "start_us": q(us[:, 0]), "stream_end_us": q(us[:, 1]), "end_us": q(us[:, 2]),
+        "lifetime_us": q(us[:, 2] - us[:, 0]), "after_stream_us": q(us[:, 2] - us[:, 1]),
+        "per_xcd_end_us_median": {int(x): round(float(np.median(us[xcd == x, 2])), 2) for x in np.unique(xcd)},
+        "per_xcd_workgroups": {int(x): int((xcd == x).sum()) for x in np.unique(xcd)},
+        "cus_used": int(len(np.unique(where))),
+        "simds_used": int(len(np.unique(simd))),
+        "pairs_on_one_simd_finishing_in_start_order": [int(same_order), int(pairs)],
+        "end_spread_within_simd_us_median": round(float(np.median(spread_in_simd)), 2),
     }
 
 
@@ -428,6 +481,10 @@ def main() -> int:
                     help="decode phase with prompts of different lengths (every sequence on its own "
                          "clock: sc_prefill_ragged / sc_decode_step_ragged / sc_compress_ragged)")
     ap.add_argument("--no-events", action="store_true", help="skip the per-launch HIP events")
+    ap.add_argument("--lifetimes", action="store_true",
+                    help="after the timed region, one more step with sc_diag_trace: start / end of "
+                         "stream / end of every workgroup of the decode-attention launch")
+    ap.add_argument("--lifetimes-dump", default=None, help="also save the raw readings (.npy)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true", help="time the headline workload only")
     ap.add_argument("--per-config-steps", type=int, default=200,
@@ -508,6 +565,8 @@ def main() -> int:
         "compressions_per_decode_step": head["compressions_per_decode_step"],
         "tokens_per_s_amortised": head["tokens_per_s_amortised"],
     }
+    if head["lifetimes"]:
+        res["workgroup_lifetimes"] = head["lifetimes"]
     if per_config:
         res["per_config"] = per_config
     if args.ragged:

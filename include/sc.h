@@ -399,6 +399,17 @@ sc_status sc_diag_persistence(const float *probs, int32_t units, int32_t length,
 sc_status sc_diag_kept_mass(const sc_cache *c, const float *probs_full, int64_t unit_stride,
                             float *mass_out, void *stream);
 
+/* Diagnostic of the decode-attention launch itself (where the time of a step goes): while a
+ * buffer is set, every workgroup of the launches made by sc_decode_step / sc_decode_step_ragged
+ * (one workgroup per unit; units of idle sequences write nothing) records
+ *   trace_out[u] = { clock at its start, clock when its K/V stream ended, clock at its end,
+ *                    where it ran: low word (XCD << 6) | (shader engine << 4) | CU, high word
+ *                    the wave's raw hardware-id register (wave slot, SIMD, ...) }
+ * with `clock` the GPU's constant-rate counter (100 MHz, shared by all workgroups).  Each launch
+ * overwrites the previous one's readings; results of the step are not affected.
+ *   trace_out : device uint64 [U][4], 8-byte aligned; NULL switches the recording off */
+sc_status sc_diag_trace(sc_cache *c, uint64_t *trace_out);
+
 /* Static description of a status code. */
 const char *sc_status_str(sc_status s);
 

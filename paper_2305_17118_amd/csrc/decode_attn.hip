@@ -65,6 +65,29 @@ struct AttnArgs {
     SeqSched seq;         // ragged batches (seq.off != null): the fields above that depend on the
     uint16_t* cnt_base;   // step are derived per sequence; cnt_base = bucket (ring word) 0 of unit 0
     long q_keep_slot_bytes;  // ragged + kept queries: q_keep = slot 0 of unit 0, slots this far apart
+    unsigned long long* trace;  // diagnostics, normally null: [U][4] clock readings per workgroup
+};
+
+// Diagnostics (a.trace set): every workgroup reports when it started, when its K/V stream ended
+// and when it finished (constant-rate 100 MHz clock) and where it ran (XCD, shader engine, CU).
+struct TraceClock {
+    long long t0 = 0, t1 = 0;
+    __device__ __forceinline__ void start(const AttnArgs& a) {
+        if (a.trace) t0 = wall_clock64();
+    }
+    __device__ __forceinline__ void streamed(const AttnArgs& a) {
+        if (a.trace) t1 = wall_clock64();
+    }
+    __device__ __forceinline__ void finish(const AttnArgs& a, int u) {
+        if (a.trace && threadIdx.x == 0) {
+            unsigned long long* o = a.trace + 4 * (size_t)u;
+            o[0] = (unsigned long long)t0;
+            o[1] = (unsigned long long)t1;
+            o[2] = (unsigned long long)wall_clock64();
+            const unsigned hw = __builtin_amdgcn_s_getreg(GETREG_IMMED(31, 0, HW_ID));
+            o[3] = ((unsigned long long)hw << 32) | __smid();
+        }
+    }
 };
 
 // Ragged batches: replace the lock-step scalars by those of unit u's sequence.  False when the
@@ -223,6 +246,8 @@ __device__ __forceinline__ uint4 load_stream16(const void* base, uint32_t byte_o
 
 template <typename T, int D, int NW, int UNR>
 __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
+    TraceClock clk;
+    clk.start(a);
     if (a.seq.off && !seq_apply(a, blockIdx.x)) return;
     constexpr int EPL = 16 / (int)sizeof(T);  // elements per lane
     constexpr int LPR = D / EPL;              // lanes per row
@@ -320,6 +345,7 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
         if (c == 0) a.pos[(size_t)u * a.C + nc] = a.pos_value;
     }
     if (wv == 0) take_row(k_own, v_own, nc, owner);
+    clk.streamed(a);
 
 #pragma unroll
     for (int off = LPR; off < 64; off <<= 1) run.merge_xor(off);
@@ -333,6 +359,7 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
     }
     __syncthreads();
     finish_unit<T, D, NW * 64, NW>(a, u, s_lds, part_m, part_l, part_acc, cpre);
+    clk.finish(a, u);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -403,6 +430,8 @@ __device__ __forceinline__ float row_groups_max(float v) {
 // their partial sums merge with plain DPP adds.
 template <int D, int NW, int UNR>
 __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
+    TraceClock clk;
+    clk.start(a);
     if (a.seq.off && !seq_apply(a, blockIdx.x)) return;
     constexpr int LPR = D / 32;   // lanes per cache row (16 bytes = 32 codes per lane)
     constexpr int RPW = 64 / LPR; // cache rows per wave load
@@ -584,6 +613,7 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
             }
         }
     }
+    clk.streamed(a);
     __syncthreads();  // the quantised new row is in LDS
     if (wv == 0) {
         const uint4 kr = *reinterpret_cast<const uint4*>(&new_codes[0][c * 16]);
@@ -615,6 +645,7 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
     }
     __syncthreads();
     finish_unit<_Float16, D, NW * 64, NP>(a, u, s_lds, part_m, part_l, part_acc, cpre);
+    clk.finish(a, u);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -655,8 +686,23 @@ __device__ __forceinline__ float row16_max(float v) {
     return dpp_max<0x140>(v);
 }
 
+// The waves that share a SIMD do not get equal shares of its issue slots by themselves (one of
+// them can end a third later than another although their work is identical), and a launch is
+// only over when its slowest wave is.  Each wave therefore walks through the priority levels
+// as it advances, offset by its slot on the SIMD, so that over any few tiles every wave has
+// held every level.
+__device__ __forceinline__ void rotate_priority(int k) {
+    switch (k % 3) {
+        case 0: __builtin_amdgcn_s_setprio(0); break;
+        case 1: __builtin_amdgcn_s_setprio(1); break;
+        default: __builtin_amdgcn_s_setprio(2); break;
+    }
+}
+
 template <int NW, int UNR>
 __global__ void __launch_bounds__(NW * 64) attn_i4_mfma_kernel(AttnArgs a) {
+    TraceClock clk;
+    clk.start(a);
     if (a.seq.off && !seq_apply(a, blockIdx.x)) return;
     constexpr int D = 128;
     constexpr int RPW = 16;           // cache rows per tile (one wave load)
@@ -852,7 +898,30 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_mfma_kernel(AttnArgs a) {
     using Full = std::integral_constant<bool, false>;
     using Ragged = std::integral_constant<bool, true>;
 
-    for (int t = wv; t < ntiles; t += UNR * NW) {
+    // Steady state: rounds of UNR full tiles whose refills are full tiles too, with no
+    // condition anywhere in the round, so that the number of loads issued after the ones a
+    // tile waits for is a compile-time constant (the wait then covers that tile only and the
+    // other UNR-1 tiles stay in flight; behind a condition the compiler has to wait for
+    // everything outstanding).  The last rounds, whose refills may be ragged or absent, take
+    // the general path below.
+    const int slot = (int)(__builtin_amdgcn_s_getreg(GETREG_IMMED(3, 0, HW_ID)) % 3u);  // slot on the SIMD
+    int turn = slot;
+    int t = wv;
+    for (; t + (2 * UNR - 1) * NW < nfull; t += UNR * NW) {
+#pragma unroll
+        for (int x = 0; x < UNR; ++x) {
+            rotate_priority(x == UNR - 1 ? slot : slot + x);
+            take_tile(Full{}, kr[x], vr[x], km[x], vm[x], (t + x * NW) * RPW + r, true);
+            kr[x] = load_stream16(Kb, code_off);
+            vr[x] = load_stream16(Vb, code_off);
+            km[x] = *reinterpret_cast<const uint2*>(Kmb + meta_off);
+            vm[x] = Vmb[meta_off + gi];
+            code_off += NW * RPW * ROWB;
+            meta_off += NW * RPW * GPR;
+        }
+    }
+    for (; t < ntiles; t += UNR * NW) {
+        rotate_priority(turn++);
 #pragma unroll
         for (int x = 0; x < UNR; ++x) {
             const int tc = t + x * NW;
@@ -866,6 +935,8 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_mfma_kernel(AttnArgs a) {
             }
         }
     }
+    __builtin_amdgcn_s_setprio(0);
+    clk.streamed(a);
     __syncthreads();  // the quantised new row is in LDS
     if (wv == 0) {
         const uint4 nk = *reinterpret_cast<const uint4*>(&new_codes[0][kb * 16]);
@@ -898,6 +969,7 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_mfma_kernel(AttnArgs a) {
     }
     __syncthreads();
     finish_unit<_Float16, D, NW * 64, NW>(a, u, s_lds, part_m, part_l, part_acc, cpre);
+    clk.finish(a, u);
 }
 
 __global__ void clear_u32_kernel(uint32_t* p, size_t n) {
@@ -992,6 +1064,7 @@ hipError_t launch_decode_step(const Layout& L, const StepArgs& s, hipStream_t st
     a.seq = s.seq;
     a.cnt_base = L.cnt;
     a.q_keep_slot_bytes = (long)L.d * (L.kv_dtype == KV_F32 ? 4 : 2);
+    a.trace = s.trace;
     const int nw = pick_waves(L.U);
     if (L.kv_dtype == KV_F32)
         return L.d == 64 ? launch_rows<float, 64, 2>(a, L.U, nw, stream)

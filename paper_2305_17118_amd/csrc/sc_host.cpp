@@ -32,6 +32,7 @@ struct sc_cache {
     bool step_dev_known;           // the device-side count equals `step`
     std::vector<uint8_t> last_active;  // sequences of the most recent ragged decode step
     size_t row_bytes, meta_bytes;  // per K (or V) row, for views of a range of sequences
+    unsigned long long* trace;     // diagnostics buffer of the decode launches, or null
 };
 
 struct sc_layers {
@@ -175,6 +176,7 @@ sc_status step_impl(sc_cache* c, const void* q, const void* k_new, const void* v
     a.q_keep = c->L.Qh ? static_cast<char*>(c->L.Qh) +
                              (size_t)((t1 - 1) % c->cfg.history) * c->cfg.head_dim * elem_bytes(c->cfg)
                        : nullptr;
+    a.trace = c->trace;
     if (sc::launch_decode_step(c->L, a, stream) != hipSuccess) return SC_ERR_DEVICE;
     c->t = t1;
     c->n = n1;
@@ -416,6 +418,7 @@ sc_status sc_cache_create(const sc_config* cfg, void* dev_workspace, size_t byte
     c->seq_off = reinterpret_cast<int32_t*>(base + s.off_seq);
     c->row_bytes = s.row_bytes;
     c->meta_bytes = s.meta_bytes;
+    c->trace = nullptr;
     c->n_trig = s.n_trig;
     c->n = 0;
     c->t = 0;
@@ -669,6 +672,7 @@ sc_status sc_decode_step_ragged(sc_cache* c, const void* q, const void* k_new, c
         a.seq.step_dev = step_dev;
         a.seq.step = 0;
     }
+    a.trace = c->trace;
     if (sc::launch_decode_step(c->L, a, s) != hipSuccess) return SC_ERR_DEVICE;
     if (c->device_clock && sc::launch_tick(c->seq_off + B, s) != hipSuccess) return SC_ERR_DEVICE;
     c->step += 1;
@@ -793,6 +797,13 @@ sc_status sc_cache_view(const sc_cache* c, const void** K, const void** V, const
     if (cnt) *cnt = c->L.cnt;
     if (capacity) *capacity = c->L.C;
     if (buckets) *buckets = c->L.E ? c->L.E : c->L.W32;
+    return SC_OK;
+}
+
+sc_status sc_diag_trace(sc_cache* c, uint64_t* trace_out) {
+    if (!c) return SC_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(trace_out) % 8 != 0) return SC_ERR_INVALID_ARG;
+    c->trace = reinterpret_cast<unsigned long long*>(trace_out);
     return SC_OK;
 }
 

@@ -128,6 +128,7 @@ struct StepArgs {
     void* q_keep;     // ring slot of this step for unit 0 (units are w*d elements apart), or null
     SeqSched seq{};   // seq.off != null: n, pos_value, bucket, counted, ring_bit and tau above are
                       // ignored and derived per sequence on the device
+    unsigned long long* trace = nullptr;  // diagnostics: [U][4] clock readings per workgroup, or null
 };
 
 // One launch on `stream`: append the new row and attend.
