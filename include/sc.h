@@ -357,6 +357,46 @@ sc_cache *sc_layers_get(sc_layers *ls, int32_t layer);
 /* Number of layers. */
 int32_t sc_layers_count(const sc_layers *ls);
 
+/* One decode step of every layer in ONE call: layer l runs sc_decode_step_ragged on its own
+ * cache with its own inputs and outputs (a model's layers step one after another on one stream;
+ * the launches are independent, the set only spares the caller L round trips through the ABI
+ * and gives a HIP graph one call to capture).
+ *   q, k_new, v_new  : device; layer l's rows start layer_stride elements after layer l-1's
+ *                      (>= U*head_dim, or (U-1)*in_stride + head_dim with in_stride != 0), inside a
+ *                      layer units are in_stride elements apart (0 = densely packed)
+ *   out              : device; layer l's dense [U][head_dim] block starts out_layer_stride elements
+ *                      after layer l-1's
+ *   active           : host uint8 [batch] or NULL (all), the same sequences in every layer
+ *   n_due            : host int or NULL; receives the number of (layer, sequence) pairs whose
+ *                      cache has reached its trigger size; when not 0 call sc_layers_compress
+ * SC_ERR_FULL, with nothing enqueued or changed, if a compression is due in any layer.  A device
+ * error in layer l leaves layers < l one step ahead of the others.
+ * Replaying it from a HIP graph works exactly as for one cache (sc_cache_device_clock):
+ * sc_layers_device_clock(1), one eager call, capture one call, then per replay
+ * sc_layers_note_replays(ls, 1, ...); sc_layers_steps_until_due says how far the graph may run
+ * (layers with different budgets become due at different steps; compress eagerly, then go on
+ * replaying the same graph). */
+sc_status sc_layers_decode_step(sc_layers *ls, const void *q, const void *k_new, const void *v_new,
+                                int64_t layer_stride, int64_t in_stride, void *out,
+                                int64_t out_layer_stride, const uint8_t *active, int32_t *n_due,
+                                void *stream);
+
+/* sc_cache_device_clock for every layer of the set. */
+sc_status sc_layers_device_clock(sc_layers *ls, int32_t enable);
+
+/* sc_cache_note_replays for every layer: the work enqueued by the most recent
+ * sc_layers_decode_step has been executed k more times.  SC_ERR_FULL (nothing changed) if k steps
+ * would pass a due compression in any layer. */
+sc_status sc_layers_note_replays(sc_layers *ls, int32_t k, int32_t *n_due);
+
+/* The smallest sc_steps_until_due over the layers. */
+sc_status sc_layers_steps_until_due(const sc_layers *ls, const uint8_t *active, int32_t *steps);
+
+/* Alg. 2 on every layer in which a compression is due (sc_compress / sc_compress_ragged as the
+ * layer's handle requires, no outputs).  n_compressed: host int or NULL, the number of layers
+ * compressed.  SC_ERR_STATE when no layer is due. */
+sc_status sc_layers_compress(sc_layers *ls, int32_t *n_compressed, void *stream);
+
 /* Free the host metadata of the set and of its caches. */
 void sc_layers_destroy(sc_layers *ls);
 

@@ -31,6 +31,8 @@ EXPORTS = (
     "sc_schedule_rows", "sc_cache_reset_seq", "sc_cache_device_clock", "sc_steps_until_due",
     "sc_cache_note_replays",
     "sc_layers_workspace_bytes", "sc_layers_create", "sc_layers_get", "sc_layers_count", "sc_layers_destroy",
+    "sc_layers_decode_step", "sc_layers_device_clock", "sc_layers_note_replays", "sc_layers_steps_until_due",
+    "sc_layers_compress",
 )
 
 
@@ -97,6 +99,12 @@ def lib():
     l.sc_layers_count.restype = C.c_int32
     l.sc_layers_destroy.argtypes = [vp]
     l.sc_layers_destroy.restype = None
+    l.sc_layers_decode_step.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int64, vp, C.c_int64, C.POINTER(C.c_uint8),
+                                        i32p, vp]
+    l.sc_layers_device_clock.argtypes = [vp, C.c_int32]
+    l.sc_layers_note_replays.argtypes = [vp, C.c_int32, i32p]
+    l.sc_layers_steps_until_due.argtypes = [vp, C.POINTER(C.c_uint8), i32p]
+    l.sc_layers_compress.argtypes = [vp, i32p, vp]
     l.sc_status_str.argtypes = [C.c_int]
     l.sc_status_str.restype = C.c_char_p
     for name in EXPORTS:
@@ -449,6 +457,38 @@ class LayerSet:
 
     def __len__(self):
         return len(self.layers)
+
+    def _stream(self) -> int:
+        import torch
+        return int(torch.cuda.current_stream(self.device).cuda_stream)
+
+    def decode_step(self, q, k_new, v_new, out, in_stride=0, active=None) -> int:
+        """q, k_new, v_new, out: [L, U, d] tensors (a layer's block may be strided).  -> pairs now due."""
+        arr = None if active is None else (C.c_uint8 * len(active))(*[1 if x else 0 for x in active])
+        due = C.c_int32(0)
+        _check(lib().sc_layers_decode_step(self.handle, q.data_ptr(), k_new.data_ptr(), v_new.data_ptr(),
+                                           q.stride(0), in_stride, out.data_ptr(), out.stride(0), arr,
+                                           C.byref(due), self._stream()), "sc_layers_decode_step")
+        return due.value
+
+    def device_clock(self, enable: bool = True) -> None:
+        _check(lib().sc_layers_device_clock(self.handle, 1 if enable else 0), "sc_layers_device_clock")
+
+    def note_replays(self, k: int = 1) -> int:
+        due = C.c_int32(0)
+        _check(lib().sc_layers_note_replays(self.handle, int(k), C.byref(due)), "sc_layers_note_replays")
+        return due.value
+
+    def steps_until_due(self, active=None) -> int:
+        arr = None if active is None else (C.c_uint8 * len(active))(*[1 if x else 0 for x in active])
+        k = C.c_int32()
+        _check(lib().sc_layers_steps_until_due(self.handle, arr, C.byref(k)), "sc_layers_steps_until_due")
+        return k.value
+
+    def compress(self) -> int:
+        n = C.c_int32(0)
+        _check(lib().sc_layers_compress(self.handle, C.byref(n), self._stream()), "sc_layers_compress")
+        return n.value
 
     def __getitem__(self, l):
         return self.layers[l]

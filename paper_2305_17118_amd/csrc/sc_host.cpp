@@ -875,6 +875,97 @@ sc_cache* sc_layers_get(sc_layers* ls, int32_t layer) {
 
 int32_t sc_layers_count(const sc_layers* ls) { return ls ? (int32_t)ls->layer.size() : 0; }
 
+sc_status sc_layers_device_clock(sc_layers* ls, int32_t enable) {
+    if (!ls) return SC_ERR_INVALID_ARG;
+    for (sc_cache* h : ls->layer) {
+        const sc_status st = sc_cache_device_clock(h, enable);
+        if (st != SC_OK) return st;
+    }
+    return SC_OK;
+}
+
+sc_status sc_layers_decode_step(sc_layers* ls, const void* q, const void* k_new, const void* v_new,
+                                int64_t layer_stride, int64_t in_stride, void* out, int64_t out_layer_stride,
+                                const uint8_t* active, int32_t* n_due, void* stream) {
+    if (!ls || ls->layer.empty() || !q || !k_new || !v_new || !out) return SC_ERR_INVALID_ARG;
+    const sc_cache* c0 = ls->layer[0];
+    const size_t eb = elem_bytes(c0->cfg);
+    const int64_t row = in_stride ? in_stride : c0->cfg.head_dim;
+    const int64_t units = (int64_t)c0->cfg.batch * c0->cfg.heads;
+    if (layer_stride < (units - 1) * row + c0->cfg.head_dim || (layer_stride * (int64_t)eb) % 16 != 0)
+        return SC_ERR_INVALID_ARG;
+    if (out_layer_stride < units * c0->cfg.head_dim || (out_layer_stride * (int64_t)eb) % 16 != 0)
+        return SC_ERR_INVALID_ARG;
+    // nothing is enqueued unless every layer can take the step
+    for (const sc_cache* h : ls->layer)
+        for (int b = 0; b < h->cfg.batch; ++b)
+            if ((!active || active[b]) && (h->ragged ? h->ns[b] : h->n) >= h->n_trig) return SC_ERR_FULL;
+    int32_t total = 0;
+    for (size_t l = 0; l < ls->layer.size(); ++l) {
+        const size_t in_off = l * (size_t)layer_stride * eb, out_off = l * (size_t)out_layer_stride * eb;
+        int32_t due = 0;
+        const sc_status st = sc_decode_step_ragged(
+            ls->layer[l], static_cast<const char*>(q) + in_off, static_cast<const char*>(k_new) + in_off,
+            static_cast<const char*>(v_new) + in_off, in_stride, static_cast<char*>(out) + out_off, nullptr,
+            active, &due, stream);
+        if (st != SC_OK) return st;
+        total += due;
+    }
+    if (n_due) *n_due = total;
+    return SC_OK;
+}
+
+sc_status sc_layers_note_replays(sc_layers* ls, int32_t k, int32_t* n_due) {
+    if (!ls || k < 0) return SC_ERR_INVALID_ARG;
+    for (const sc_cache* h : ls->layer) {  // checked for every layer before any layer advances
+        if (!h->ragged || !h->device_clock || h->step == 0) return SC_ERR_STATE;
+        for (int b = 0; b < h->cfg.batch; ++b)
+            if (h->last_active[b] && h->ns[b] + k > h->n_trig) return SC_ERR_FULL;
+    }
+    int32_t total = 0;
+    for (sc_cache* h : ls->layer) {
+        int32_t due = 0;
+        const sc_status st = sc_cache_note_replays(h, k, &due);
+        if (st != SC_OK) return st;
+        total += due;
+    }
+    if (n_due) *n_due = total;
+    return SC_OK;
+}
+
+sc_status sc_layers_steps_until_due(const sc_layers* ls, const uint8_t* active, int32_t* steps) {
+    if (!ls || ls->layer.empty() || !steps) return SC_ERR_INVALID_ARG;
+    int32_t least = INT32_MAX;
+    for (const sc_cache* h : ls->layer) {
+        int32_t k = 0;
+        const sc_status st = sc_steps_until_due(h, active, &k);
+        if (st != SC_OK) return st;
+        least = std::min(least, k);
+    }
+    *steps = least;
+    return SC_OK;
+}
+
+sc_status sc_layers_compress(sc_layers* ls, int32_t* n_compressed, void* stream) {
+    if (!ls) return SC_ERR_INVALID_ARG;
+    int32_t count = 0;
+    for (sc_cache* h : ls->layer) {
+        bool due = false;
+        if (h->ragged) {
+            for (int b = 0; b < h->cfg.batch; ++b) due = due || h->ns[b] == h->n_trig;
+        } else {
+            due = h->n == h->n_trig;
+        }
+        if (!due) continue;
+        const sc_status st = h->ragged ? sc_compress_ragged(h, nullptr, nullptr, stream)
+                                       : sc_compress(h, nullptr, nullptr, stream);
+        if (st != SC_OK) return st;
+        ++count;
+    }
+    if (n_compressed) *n_compressed = count;
+    return count ? SC_OK : SC_ERR_STATE;
+}
+
 void sc_layers_destroy(sc_layers* ls) {
     if (!ls) return;
     for (sc_cache* h : ls->layer) sc_cache_destroy(h);

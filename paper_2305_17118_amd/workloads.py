@@ -86,6 +86,8 @@ def unit_streams(wl: Workload, unit: int, steps: int | None = None):
     ``steps`` truncates the returned stream (the draws themselves always cover the full
     length, so a prefix equals the prefix of the full stream)."""
     T, d = wl.total, wl.head_dim
+    if steps is not None and steps > T:
+        raise ValueError("workload %s has %d positions, %d asked for" % (wl.name, T, steps))
     rng = np.random.Generator(np.random.Philox(key=[wl.seed, unit]))
     direction = rng.standard_normal(d)
     direction /= np.linalg.norm(direction)

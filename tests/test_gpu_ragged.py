@@ -12,8 +12,8 @@ pytestmark = pytest.mark.gpu
 
 
 def _wl(name, batch, heads, d, kv, budget, r, w, m, heavy=0.0, seed=1300):
-    # prompt/decode of the workload are unused here (the lengths are per sequence)
-    return Workload(name, seed, batch, heads, d, kv, 0, 1, budget, r, w, m, heavy)
+    # the lengths are per sequence; the workload only has to offer enough stream positions
+    return Workload(name, seed, batch, heads, d, kv, 0, 1024, budget, r, w, m, heavy)
 
 
 CASES = [
@@ -396,3 +396,91 @@ def test_decode_step_replayed_from_a_graph_with_the_device_clock(kv):
         u, nb = slice(b * wl.heads, (b + 1) * wl.heads), eager.len_seq(b)[0]
         assert torch.equal(eager.pos()[u, :nb], graphed.pos()[u, :nb])
         assert torch.equal(Ka[u, :nb], Kb[u, :nb]) and torch.equal(Va[u, :nb], Vb[u, :nb])
+
+
+def test_layer_set_step_in_one_call_and_replayed_from_one_graph():
+    """sc_layers_decode_step = one sc_decode_step_ragged per layer: the layers of a set (own budgets
+    and drop sizes, so compressions fall on different steps) are stepped (a) by one call per step
+    and (b) by replaying ONE captured call, and must equal, bit for bit, standalone caches stepped
+    layer by layer; compressions are eager in all three."""
+    kv, L = KV_F16, 4
+    wl = _wl("layers-graph", 2, 3, 128, kv, 40, 4, 24, 12, 0.05)
+    T, U, d = 200, wl.units, wl.head_dim
+    cfg = B.make_config(wl.batch, wl.heads, d, kv, wl.budget, wl.recent, wl.history, wl.drop)
+    budgets, drops = [40, 46, 52, 64], [12, 12, 24, 8]
+    q, k, v = (torch.from_numpy(a).cuda() for a in streams(wl.scaled(heads=wl.heads * L), steps=T))
+    # [U*L, T, d] -> per layer [L, U, T, d]
+    q, k, v = (x.view(wl.batch, L, wl.heads, T, d).permute(1, 0, 2, 3, 4).reshape(L, U, T, d).contiguous()
+               for x in (q, k, v))
+    import copy
+    alone = []
+    for l in range(L):
+        c = copy.copy(cfg)
+        c.budget, c.drop = budgets[l], drops[l]
+        alone.append(B.BudgetCache(c))
+    called, graphed = B.LayerSet(cfg, budgets, drops), B.LayerSet(cfg, budgets, drops)
+    P = 20
+    for l in range(L):
+        for c in (alone[l], called[l], graphed[l]):
+            c.prefill_ragged(q[l], k[l], v[l], [P] * wl.batch, T * d, None)
+    graphed.device_clock(True)
+    qs, ks, vs = (torch.empty(L, U, d, dtype=torch.float16, device="cuda") for _ in range(3))
+    out_a, out_c, out_g = (torch.empty(L, U, d, dtype=torch.float16, device="cuda") for _ in range(3))
+
+    def load(s):
+        qs.copy_(q[:, :, s]); ks.copy_(k[:, :, s]); vs.copy_(v[:, :, s])
+
+    def step_alone():
+        return sum(alone[l].decode_step_ragged(qs[l], ks[l], vs[l], out_a[l]) for l in range(L))
+
+    load(P)
+    due = step_alone()
+    assert called.decode_step(qs, ks, vs, out_c) == due == graphed.decode_step(qs, ks, vs, out_g)
+    assert torch.equal(out_a, out_c) and torch.equal(out_a, out_g)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        due_g = graphed.decode_step(qs, ks, vs, out_g)
+    first, comps = True, 0
+    for s in range(P + 1, T):
+        load(s)
+        due = step_alone()
+        assert called.decode_step(qs, ks, vs, out_c) == due
+        if first:
+            first = False
+        else:
+            assert graphed.steps_until_due() >= 1
+            due_g = graphed.note_replays(1)
+        g.replay()
+        torch.cuda.synchronize()
+        assert due_g == due, "step %d" % s
+        assert torch.equal(out_a, out_c) and torch.equal(out_a, out_g), "step %d" % s
+        if due:
+            with pytest.raises(B.ScError) as e:
+                graphed.note_replays(1)
+            assert e.value.status == B.SC_ERR_FULL
+            with pytest.raises(B.ScError) as e:
+                called.decode_step(qs, ks, vs, out_c)
+            assert e.value.status == B.SC_ERR_FULL
+            n_alone = 0
+            for c in alone:
+                if any(c.len_seq(b)[0] == c.n_trig for b in range(wl.batch)):
+                    c.compress_ragged()
+                    n_alone += 1
+            assert called.compress() == n_alone == graphed.compress()
+            comps += n_alone
+    assert comps >= 20
+    with pytest.raises(B.ScError) as e:
+        called.compress()
+    assert e.value.status == B.SC_ERR_STATE
+    for l in range(L):
+        for other in (called[l], graphed[l]):
+            assert torch.equal(alone[l].cnt(), other.cnt())
+            Ka, Va = alone[l].kv_rows()
+            Kb, Vb = other.kv_rows()
+            for b in range(wl.batch):
+                assert alone[l].len_seq(b) == other.len_seq(b)
+                u, nb = slice(b * wl.heads, (b + 1) * wl.heads), alone[l].len_seq(b)[0]
+                assert torch.equal(alone[l].pos()[u, :nb], other.pos()[u, :nb])
+                assert torch.equal(Ka[u, :nb], Kb[u, :nb]) and torch.equal(Va[u, :nb], Vb[u, :nb])
