@@ -239,6 +239,80 @@ def copy_probe(args, dev) -> int:
     return 0
 
 
+def bench_layers(args, wl, dev) -> int:
+    """A model step = one decode step of each of --layers caches of the workload's shape (the
+    layers of a model, stepped one after another on one stream), enqueued three ways:
+      calls  : one sc_decode_step_ragged call per layer,
+      one    : one sc_layers_decode_step call for all layers,
+      graph  : one captured sc_layers_decode_step call replayed from a HIP graph (step count kept
+               on the device); compressions run eagerly between replays in all three.
+    Reports microseconds per layer step (wall time of the model steps / layers)."""
+    import torch
+
+    from paper_2305_17118_amd import binding as B
+    from paper_2305_17118_amd.workloads import streams
+
+    L, U, d, T = args.layers, wl.units, wl.head_dim, wl.total
+    cfg = B.make_config(wl.batch, wl.heads, d, wl.kv_dtype, wl.budget, wl.recent, wl.history, wl.drop)
+    q, k, v = (torch.from_numpy(a).to(dev) for a in streams(wl, threads=16))
+    K = min(args.steps, wl.decode - 2)
+    res = {}
+    for mode in ("calls", "one", "graph"):
+        ls = B.LayerSet(cfg, [wl.budget] * L, None, dev)
+        for c in ls.layers:
+            c.prefill_ragged(q, k, v, [wl.prompt] * wl.batch, T * d, None)
+        if mode == "graph":
+            ls.device_clock(True)
+        qs, ks, vs = (torch.empty(L, U, d, dtype=q.dtype, device=dev) for _ in range(3))
+        out = torch.empty(L, U, d, dtype=q.dtype, device=dev)
+
+        def load(s):
+            qs.copy_(q[:, s].unsqueeze(0).expand(L, U, d))
+            ks.copy_(k[:, s].unsqueeze(0).expand(L, U, d))
+            vs.copy_(v[:, s].unsqueeze(0).expand(L, U, d))
+
+        def eager_step():
+            if mode == "calls":
+                return sum(c.decode_step_ragged(qs[l], ks[l], vs[l], out[l]) for l, c in enumerate(ls.layers))
+            return ls.decode_step(qs, ks, vs, out)
+
+        s = wl.prompt
+        load(s)
+        if eager_step():   # (brings the device tables up to date)
+            ls.compress()
+        s += 1
+        g, first = None, True
+        if mode == "graph":
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                ls.decode_step(qs, ks, vs, out)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            load(s)
+            s += 1
+            if g is None:
+                due = eager_step()
+            else:
+                due = 0 if first else ls.note_replays(1)
+                first = False
+                g.replay()
+            if due:
+                ls.compress()
+        torch.cuda.synchronize()
+        res[mode] = (time.perf_counter() - t0) / K / L * 1e6
+        ls.close()
+        del ls
+        torch.cuda.empty_cache()
+    print(json.dumps({"probe": "layer set", "workload": wl.name, "layers": L, "model_steps": K,
+                      "us_per_layer_step": {"one_call_per_layer": res["calls"],
+                                            "one_call_for_all_layers": res["one"],
+                                            "one_graph_replay": res["graph"]}}))
+    return 0
+
+
 def pick_instances(ws_bytes: int, rotate: int) -> int:
     """Cache instances stepped round-robin: at least four (phases of the compression cycle), and
     enough that their total footprint is three times the 256 MB last-level cache."""
@@ -467,9 +541,11 @@ def main() -> int:
                     "(few-unit batches; the line is then not the workload's own)")
     ap.add_argument("--rotate", type=int, default=0, help="cache instances stepped round-robin "
                     "(0 = at least 4 and enough to cover three times the 256 MB last-level cache)")
-    ap.add_argument("--phase", choices=("decode", "prefill", "copy"), default="decode",
+    ap.add_argument("--phase", choices=("decode", "prefill", "copy", "layers"), default="decode",
                     help="decode = the headline metric; prefill = the prompt phase; copy = plain "
-                         "device copies of --copy-mib MiB (calibration of HBM traffic counters)")
+                         "device copies of --copy-mib MiB (calibration of HBM traffic counters); "
+                         "layers = --layers caches stepped per model step, eager against one HIP graph")
+    ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--copy-mib", type=int, default=1024)
     ap.add_argument("--window", choices=("auto", "ring"), default="auto",
                     help="importance record: bucket counters (auto, when w is a multiple of m) or "
@@ -512,6 +588,8 @@ def main() -> int:
         return bench_prefill(args, wl, dev)
     if args.phase == "copy":
         return copy_probe(args, dev)
+    if args.phase == "layers":
+        return bench_layers(args, wl, dev)
 
     head = run_decode(wl, args, args.steps, args.warmup, dev)
     K, W = head["K"], head["W"]

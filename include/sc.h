@@ -22,8 +22,15 @@
  *              the handle.  The handle owns host metadata only.
  *   Streams.   `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *              Calls only enqueue kernels on it and never synchronise.
- *   Errors.    Functions return sc_status; nothing throws, aborts or prints.  On any error
- *              the cache (t, n, device contents) is unchanged and out-params untouched.
+ *   Errors.    Functions return sc_status; nothing throws, aborts or prints.  Every argument
+ *              and state check is made before anything is enqueued or changed: on
+ *              SC_ERR_INVALID_ARG, _WORKSPACE, _FULL, _STATE, _UNSUPPORTED, _SCRATCH and
+ *              _HOST_MEMORY the cache (t, n, device contents) is unchanged and out-params are
+ *              untouched.  SC_ERR_DEVICE (a launch was refused by the runtime) can arrive in
+ *              the middle of a call that enqueues several launches (sc_prefill and its ragged
+ *              form, sc_compress with the record rebuilt first, the ragged step after its
+ *              table upload): the cache is then in no defined state and must be put back to
+ *              empty with sc_cache_reset before it is used again.
  *   Threads.   A handle is not thread-safe; distinct handles are independent.
  *   Element types.  SC_KV_F32: q/k/v/out are float.  SC_KV_F16 and SC_KV_I4G64: q/k/v/out
  *              are IEEE binary16.  All dot products, the softmax and the weighted value sum
@@ -49,8 +56,9 @@ typedef enum {
     SC_ERR_STATE = 4,       /* sc_compress when none is due; lock-step call on a ragged handle */
     SC_ERR_UNSUPPORTED = 5, /* head_dim / kv_dtype / sizes this build does not cover          */
     SC_ERR_DEVICE = 6,      /* a kernel launch failed (hipGetLastError)                       */
-    SC_ERR_SCRATCH = 7      /* sc_compress_static: the cache needs more scratch than the
+    SC_ERR_SCRATCH = 7,     /* sc_compress_static: the cache needs more scratch than the
                                library's static array holds (SC_STATIC_SCRATCH_BYTES)          */
+    SC_ERR_HOST_MEMORY = 8  /* host memory for the handle's own bookkeeping could not be had  */
 } sc_status;
 
 /* Storage format of the cached K/V rows. */
@@ -154,9 +162,11 @@ void sc_cache_destroy(sc_cache *c);
  *   q, k_new, v_new : device, U rows of head_dim elements; consecutive units are `in_stride`
  *                     elements apart (0 = densely packed [batch, heads, head_dim])
  *   out             : device, dense [batch, heads, head_dim]
- *   probs_out       : device fp32 [U][capacity] or NULL; receives, for slots < n, exactly the
- *                     probabilities the threshold test was applied to (slot n is written
- *                     as 0 when n is odd, other slots >= n are untouched)
+ *   probs_out       : device fp32 [U][capacity] or NULL, 8-byte aligned (probabilities are
+ *                     stored in pairs); receives, for slots < n, exactly the probabilities the
+ *                     threshold test was applied to (slot n is written as 0 when n is odd,
+ *                     other slots >= n are untouched)
+ * q, k_new, v_new and out must be 16-byte aligned, in_stride a multiple of 16 bytes.
  *   compress_due    : host int or NULL; set to 1 when n has reached n_trig, i.e. the caller
  *                     must call sc_compress before the next step, else 0
  * SC_ERR_FULL if a compression is due. */

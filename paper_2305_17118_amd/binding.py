@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libsc.so")
 
 SC_OK, SC_ERR_INVALID_ARG, SC_ERR_WORKSPACE, SC_ERR_FULL, SC_ERR_STATE, SC_ERR_UNSUPPORTED, \
-    SC_ERR_DEVICE, SC_ERR_SCRATCH = range(8)
+    SC_ERR_DEVICE, SC_ERR_SCRATCH, SC_ERR_HOST_MEMORY = range(9)
 SC_STATIC_SCRATCH_BYTES = 32 << 20
 SC_KV_F32, SC_KV_F16, SC_KV_I4G64 = 0, 1, 2
 SC_TRIGGER_HARD_CAP, SC_TRIGGER_HIGH_WATER = 0, 1

@@ -263,7 +263,13 @@ __global__ void __launch_bounds__(256) write_seq_table_kernel(int32_t* __restric
     if ((int)threadIdx.x < count) dst[threadIdx.x] = c.v[threadIdx.x];
 }
 
-__global__ void tick_kernel(int32_t* counter) { *counter += 1; }
+// Up to 64 step counts (one per cache of a layer set) advanced by one launch.
+struct TickList {
+    int32_t* counter[64];
+};
+__global__ void __launch_bounds__(64) tick_kernel(TickList t, int count) {
+    if ((int)threadIdx.x < count) *t.counter[threadIdx.x] += 1;
+}
 
 }  // namespace
 
@@ -296,9 +302,16 @@ hipError_t launch_write_seq_table(int32_t* dst, const int32_t* host_values, int 
     return hipSuccess;
 }
 
-hipError_t launch_tick(int32_t* counter, hipStream_t stream) {
-    tick_kernel<<<1, 1, 0, stream>>>(counter);
-    return hipGetLastError();
+hipError_t launch_tick(int32_t* const* counters, int count, hipStream_t stream) {
+    for (int base = 0; base < count; base += 64) {
+        TickList t;
+        const int k = count - base < 64 ? count - base : 64;
+        for (int i = 0; i < 64; ++i) t.counter[i] = i < k ? counters[base + i] : nullptr;
+        tick_kernel<<<1, 64, 0, stream>>>(t, k);
+        const hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_compress(const Layout& L, const CompressArgs& c, hipStream_t stream) {

@@ -8,12 +8,15 @@
 // schedule, every position counts into the same bucket, so the whole run is
 //   S = Q K^T (causal), P = softmax(S), out = P V, cnt[j] += #{i : P[i][j] < 1/t_i}.
 //
-// fp16 storage only.  Two kernels per run: the rows are copied into their slots first, then
-// one workgroup per (unit, 64 queries) makes two passes over the visible rows in tiles of 64:
-// pass 1 is the usual running-softmax attention (scores and P.V on v_mfma_f32_16x16x32_f16),
-// pass 2 recomputes the scores against the final maximum and sum to form the very
+// Every storage type (fp16, fp32 and 4-bit rows; bucket counters or the one-bit-per-step ring).
+// One launch per run, one workgroup per (unit, block of queries), which makes two passes over
+// the visible rows in tiles of 64 staged in LDS: pass 1 is the usual running-softmax attention
+// (scores and P.V on the matrix cores: v_mfma_f32_16x16x32_f16, or v_mfma_f32_16x16x4_f32 for
+// fp32 rows), pass 2 recomputes the scores against the final maximum and sum to form the very
 // probabilities the threshold is applied to, counts the low ones per cache row and adds the
-// counts to the 16-bit counters (two per 32-bit atomic).
+// counts to the 16-bit counters (two per 32-bit atomic).  The run's own fp16/fp32 rows reach
+// their slots through the registers of the workgroup that holds the last query block; 4-bit
+// rows are quantised into their slots by a small launch of their own first.
 #include "quant.hpp"
 #include "sc_kernels.hpp"
 

@@ -37,6 +37,7 @@ struct sc_cache {
 
 struct sc_layers {
     std::vector<sc_cache*> layer;
+    std::vector<int32_t*> clocks;  // scratch of sc_layers_decode_step: device step counts to advance
 };
 
 namespace {
@@ -235,14 +236,18 @@ sc_status enter_ragged(sc_cache* c) {
     if (c->ragged) return SC_OK;
     if (c->n >= c->n_trig) return SC_ERR_FULL;  // the pending lock-step compression comes first
     const size_t B = (size_t)c->cfg.batch;
-    c->ts.assign(B, c->t);
-    c->ns.assign(B, c->n);
-    c->table.assign(B, sc::kSeqIdle);
-    c->wanted.assign(B, sc::kSeqIdle);
+    try {  // nothing may be thrown across the C ABI
+        c->ts.assign(B, c->t);
+        c->ns.assign(B, c->n);
+        c->table.assign(B, sc::kSeqIdle);
+        c->wanted.assign(B, sc::kSeqIdle);
+        c->last_active.assign(B, 0);
+    } catch (const std::bad_alloc&) {
+        return SC_ERR_HOST_MEMORY;
+    }
     c->table_known = false;
     c->step = 0;
     c->step_dev_known = false;
-    c->last_active.assign(B, 0);
     c->ragged = true;
     return SC_OK;
 }
@@ -390,7 +395,7 @@ sc_status sc_cache_create(const sc_config* cfg, void* dev_workspace, size_t byte
     if (bytes < s.total || (reinterpret_cast<uintptr_t>(dev_workspace) % kAlign) != 0)
         return SC_ERR_WORKSPACE;
     sc_cache* c = new (std::nothrow) sc_cache;
-    if (!c) return SC_ERR_INVALID_ARG;
+    if (!c) return SC_ERR_HOST_MEMORY;
     c->cfg = *cfg;
     char* base = static_cast<char*>(dev_workspace);
     sc::Layout& L = c->L;
@@ -456,6 +461,7 @@ sc_status sc_decode_step(sc_cache* c, const void* q, const void* k_new, const vo
     if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_new) |
          reinterpret_cast<uintptr_t>(v_new) | reinterpret_cast<uintptr_t>(out)) % 16 != 0)
         return SC_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(probs_out) % 8 != 0) return SC_ERR_INVALID_ARG;  // stored in pairs
     if (c->ragged) return SC_ERR_STATE;
     if (c->n >= c->n_trig) return SC_ERR_FULL;
     const int64_t stride = in_stride ? in_stride : c->cfg.head_dim;
@@ -621,9 +627,11 @@ sc_status sc_prefill_ragged(sc_cache* c, const void* q, const void* k, const voi
     return st;
 }
 
-sc_status sc_decode_step_ragged(sc_cache* c, const void* q, const void* k_new, const void* v_new,
-                                int64_t in_stride, void* out, float* probs_out, const uint8_t* active,
-                                int32_t* n_due, void* stream) {
+// `tick`: advance the device-side step count right after the launch (a layer set advances the
+// counts of all its caches with one launch instead).
+static sc_status decode_step_ragged_impl(sc_cache* c, const void* q, const void* k_new, const void* v_new,
+                                         int64_t in_stride, void* out, float* probs_out, const uint8_t* active,
+                                         int32_t* n_due, void* stream, bool tick) {
     if (!c || !q || !k_new || !v_new || !out) return SC_ERR_INVALID_ARG;
     if (in_stride < 0 || (in_stride != 0 && in_stride < c->cfg.head_dim)) return SC_ERR_INVALID_ARG;
     const size_t eb = elem_bytes(c->cfg);
@@ -631,6 +639,7 @@ sc_status sc_decode_step_ragged(sc_cache* c, const void* q, const void* k_new, c
     if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_new) |
          reinterpret_cast<uintptr_t>(v_new) | reinterpret_cast<uintptr_t>(out)) % 16 != 0)
         return SC_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(probs_out) % 8 != 0) return SC_ERR_INVALID_ARG;  // stored in pairs
     const int B = c->cfg.batch;
     bool any = false;
     for (int b = 0; b < B; ++b) any = any || !active || active[b];
@@ -674,7 +683,10 @@ sc_status sc_decode_step_ragged(sc_cache* c, const void* q, const void* k_new, c
     }
     a.trace = c->trace;
     if (sc::launch_decode_step(c->L, a, s) != hipSuccess) return SC_ERR_DEVICE;
-    if (c->device_clock && sc::launch_tick(c->seq_off + B, s) != hipSuccess) return SC_ERR_DEVICE;
+    if (c->device_clock && tick) {
+        int32_t* const counter = c->seq_off + B;
+        if (sc::launch_tick(&counter, 1, s) != hipSuccess) return SC_ERR_DEVICE;
+    }
     c->step += 1;
     int32_t due = 0;
     for (int b = 0; b < B; ++b) {
@@ -686,6 +698,12 @@ sc_status sc_decode_step_ragged(sc_cache* c, const void* q, const void* k_new, c
     }
     if (n_due) *n_due = due;
     return SC_OK;
+}
+
+sc_status sc_decode_step_ragged(sc_cache* c, const void* q, const void* k_new, const void* v_new,
+                                int64_t in_stride, void* out, float* probs_out, const uint8_t* active,
+                                int32_t* n_due, void* stream) {
+    return decode_step_ragged_impl(c, q, k_new, v_new, in_stride, out, probs_out, active, n_due, stream, true);
 }
 
 sc_status sc_cache_device_clock(sc_cache* c, int32_t enable) {
@@ -847,7 +865,7 @@ sc_status sc_layers_create(const sc_config* cfg, int32_t layers, const int32_t* 
     if (!cfg || layers < 1 || !budgets || !out) return SC_ERR_INVALID_ARG;
     if (!dev_workspace) return SC_ERR_INVALID_ARG;
     sc_layers* ls = new (std::nothrow) sc_layers;
-    if (!ls) return SC_ERR_INVALID_ARG;
+    if (!ls) return SC_ERR_HOST_MEMORY;
     size_t off = 0;
     for (int32_t l = 0; l < layers; ++l) {
         sc_config c = *cfg;
@@ -862,8 +880,20 @@ sc_status sc_layers_create(const sc_config* cfg, int32_t layers, const int32_t* 
             sc_layers_destroy(ls);
             return st;
         }
-        ls->layer.push_back(h);
+        try {  // nothing may be thrown across the C ABI
+            ls->layer.push_back(h);
+        } catch (const std::bad_alloc&) {
+            sc_cache_destroy(h);
+            sc_layers_destroy(ls);
+            return SC_ERR_HOST_MEMORY;
+        }
         off += z.total;
+    }
+    try {
+        ls->clocks.reserve(ls->layer.size());
+    } catch (const std::bad_alloc&) {
+        sc_layers_destroy(ls);
+        return SC_ERR_HOST_MEMORY;
     }
     *out = ls;
     return SC_OK;
@@ -901,16 +931,24 @@ sc_status sc_layers_decode_step(sc_layers* ls, const void* q, const void* k_new,
         for (int b = 0; b < h->cfg.batch; ++b)
             if ((!active || active[b]) && (h->ragged ? h->ns[b] : h->n) >= h->n_trig) return SC_ERR_FULL;
     int32_t total = 0;
-    for (size_t l = 0; l < ls->layer.size(); ++l) {
+    ls->clocks.clear();  // (capacity reserved at creation: nothing is allocated here)
+    sc_status st = SC_OK;
+    for (size_t l = 0; l < ls->layer.size() && st == SC_OK; ++l) {
         const size_t in_off = l * (size_t)layer_stride * eb, out_off = l * (size_t)out_layer_stride * eb;
         int32_t due = 0;
-        const sc_status st = sc_decode_step_ragged(
-            ls->layer[l], static_cast<const char*>(q) + in_off, static_cast<const char*>(k_new) + in_off,
-            static_cast<const char*>(v_new) + in_off, in_stride, static_cast<char*>(out) + out_off, nullptr,
-            active, &due, stream);
-        if (st != SC_OK) return st;
+        sc_cache* h = ls->layer[l];
+        st = decode_step_ragged_impl(h, static_cast<const char*>(q) + in_off,
+                                     static_cast<const char*>(k_new) + in_off,
+                                     static_cast<const char*>(v_new) + in_off, in_stride,
+                                     static_cast<char*>(out) + out_off, nullptr, active, &due, stream, false);
+        if (st == SC_OK && h->device_clock) ls->clocks.push_back(h->seq_off + h->cfg.batch);
         total += due;
     }
+    // the device-side step counts of the layers that took the step advance with one launch
+    if (!ls->clocks.empty() &&
+        sc::launch_tick(ls->clocks.data(), (int)ls->clocks.size(), static_cast<hipStream_t>(stream)) != hipSuccess)
+        return SC_ERR_DEVICE;
+    if (st != SC_OK) return st;
     if (n_due) *n_due = total;
     return SC_OK;
 }
@@ -982,6 +1020,7 @@ const char* sc_status_str(sc_status s) {
         case SC_ERR_UNSUPPORTED: return "configuration not supported by this build";
         case SC_ERR_DEVICE: return "kernel launch failed";
         case SC_ERR_SCRATCH: return "cache needs more scratch than the library's static array holds";
+        case SC_ERR_HOST_MEMORY: return "out of host memory";
     }
     return "unknown status";
 }

@@ -106,8 +106,9 @@ __host__ __device__ inline SeqStep sched_step(const SeqSched& s, long t1) {
 // Write `count` table entries (host values) to device memory on `stream`.
 hipError_t launch_write_seq_table(int32_t* dst, const int32_t* host_values, int count, hipStream_t stream);
 
-// *counter += 1 on `stream` (the device-side step count of ragged batches).
-hipError_t launch_tick(int32_t* counter, hipStream_t stream);
+// *counters[i] += 1 for i < count on `stream` (the device-side step counts of ragged batches; one
+// launch serves up to 64 caches).
+hipError_t launch_tick(int32_t* const* counters, int count, hipStream_t stream);
 
 struct StepArgs {
     const void* q;
@@ -173,9 +174,10 @@ struct ChunkArgs {
     float qk_log2;
 };
 
-// Whether launch_prefill_chunk handles such a cache: fp16 rows (either head size; bucket
-// counters or the one-bit-per-step ring) or 4-bit rows of 128 channels (bucket counters), and a
-// per-slot LDS array that fits beside the tiles.
+// Whether launch_prefill_chunk handles such a cache: every storage type and head size it does
+// (fp32, fp16, 4-bit; 64 or 128 channels; bucket counters, the one-bit-per-step ring, or the
+// record rebuilt at compression time); what limits it is the per-slot LDS array that has to fit
+// beside the tiles.
 inline bool prefill_chunk_supported(int kv_dtype, int d, int E, int W32, int C) {
     if (C > 6144) return false;
     (void)kv_dtype;

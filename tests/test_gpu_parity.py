@@ -439,6 +439,15 @@ def test_error_codes_leave_state_untouched():
     with pytest.raises(B.ScError) as e:
         B.sc_decode_step(c.handle, None, x.data_ptr(), x.data_ptr(), 0, out.data_ptr())
     assert e.value.status == B.SC_ERR_INVALID_ARG and (c.n, c.t) == (5, 9)
+    probs = torch.zeros(2, c.capacity + 2, device="cuda")
+    with pytest.raises(B.ScError) as e:  # probabilities are stored in pairs: 8-byte alignment
+        B.sc_decode_step(c.handle, x.data_ptr(), x.data_ptr(), x.data_ptr(), 0, out.data_ptr(),
+                         probs.data_ptr() + 4)
+    assert e.value.status == B.SC_ERR_INVALID_ARG and (c.n, c.t) == (5, 9)
+    with pytest.raises(B.ScError) as e:
+        B.sc_decode_step_ragged(c.handle, x.data_ptr(), x.data_ptr(), x.data_ptr(), 0, out.data_ptr(),
+                                probs.data_ptr() + 4)
+    assert e.value.status == B.SC_ERR_INVALID_ARG and (c.n, c.t) == (5, 9)  # still a lock-step handle
     fresh = B.BudgetCache(cfg)
     with pytest.raises(B.ScError) as e:
         fresh.prefill(x, x, x, 0)

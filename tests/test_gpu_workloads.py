@@ -47,8 +47,8 @@ def test_headline_workload_high_water_policy():
     assert st["compressions"] == 2 and run.cache.n == wl.budget + (wl.total - wl.budget - wl.drop) % wl.drop
 
 
-@pytest.mark.parametrize("idx,extra,decode", [(0, 0, 128), (1, 8, 160), (2, 8, 140), (4, 8, 280)],
-                         ids=["cfg1", "cfg2", "cfg3", "cfg5"])
+@pytest.mark.parametrize("idx,extra,decode", [(0, 0, 128), (1, 8, 160), (2, 8, 140), (3, 8, 128), (4, 8, 280)],
+                         ids=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
 def test_dense_prefill_at_full_size(idx, extra, decode):
     """The prompt of a full-size workload (fp32, fp16, 4-bit) through one sc_prefill call (dense causal blocks
     on the matrix cores), every position compared on the sampled units; the decode steps that

@@ -30,8 +30,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_status_strings():
-    seen = {B.sc_status_str(s) for s in range(8)}
-    assert len(seen) == 8 and "ok" in seen
+    seen = {B.sc_status_str(s) for s in range(9)}
+    assert len(seen) == 9 and "ok" in seen
     assert B.sc_status_str(99) == "unknown status"
 
 
