@@ -759,34 +759,30 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_mfma_kernel(AttnArgs a) {
     uint32_t cpre[cnt_pf(NW * 64)];
     prefetch_counters<NW * 64>(a, u, cpre);
 
-    // Ring of UNR tiles per wave, refilled as soon as consumed (see attn_i4_kernel).
-    const int nfull = nc / RPW;
+    // Ring of UNR tiles per wave, refilled as soon as consumed.  Wave w owns tiles w, w+NW, ...;
+    // every request is unconditional and has the same form (rows beyond the last resident one
+    // repeat that row: in bounds, finite, never used), so that the number of loads issued after
+    // the ones a tile waits for is a compile-time constant everywhere and a wait covers that
+    // tile only: behind a condition the compiler has to wait for everything outstanding.
     const int ntiles = (nc + RPW - 1) / RPW;
+    const int nloc = ntiles > wv ? (ntiles - wv + NW - 1) / NW : 0;  // tiles of this wave
     uint4 kr[UNR], vr[UNR];
     uint2 km[UNR];
     uint32_t vm[UNR];
-    uint32_t code_off = ((uint32_t)(wv * RPW + r)) * ROWB + (uint32_t)kb * 16u;
-    uint32_t meta_off = ((uint32_t)(wv * RPW + r)) * GPR;
-    auto issue = [&](int x, int tile) {
-        if (tile < nfull) {
-            kr[x] = load_stream16(Kb, code_off);
-            vr[x] = load_stream16(Vb, code_off);
-            km[x] = *reinterpret_cast<const uint2*>(Kmb + meta_off);
-            vm[x] = Vmb[meta_off + gi];
-        } else {
-            const int j = tile * RPW + r;
-            const uint32_t jj = j < nc ? (uint32_t)j : 0u;
-            kr[x] = load_stream16(Kb, jj * ROWB + (uint32_t)kb * 16u);
-            vr[x] = load_stream16(Vb, jj * ROWB + (uint32_t)kb * 16u);
-            km[x] = *reinterpret_cast<const uint2*>(Kmb + jj * GPR);
-            vm[x] = Vmb[jj * GPR + gi];
-        }
-        code_off += NW * RPW * ROWB;
-        meta_off += NW * RPW * GPR;
+    int next_row = wv * RPW + r;  // row this lane holds in the tile requested next
+    auto request = [&](int x) {
+        const uint32_t jj = (uint32_t)(next_row < nc ? next_row : nc - 1);
+        const uint32_t off = jj * ROWB + (uint32_t)kb * 16u;
+        kr[x] = load_stream16(Kb, off);
+        vr[x] = load_stream16(Vb, off);
+        km[x] = *reinterpret_cast<const uint2*>(Kmb + jj * GPR);
+        vm[x] = Vmb[jj * GPR + gi];
+        next_row += NW * RPW;
     };
+    if (nloc > 0) {
 #pragma unroll
-    for (int x = 0; x < UNR; ++x)
-        if (wv + x * NW < ntiles) issue(x, wv + x * NW);
+        for (int x = 0; x < UNR; ++x) request(x);
+    }
 
     // Alg. 1 model update: wave 0 quantises the key row, wave 1 (wave 0 again when the
     // workgroup is a single wave) the value row.
@@ -898,40 +894,31 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_mfma_kernel(AttnArgs a) {
     using Full = std::integral_constant<bool, false>;
     using Ragged = std::integral_constant<bool, true>;
 
-    // Steady state: rounds of UNR full tiles whose refills are full tiles too, with no
-    // condition anywhere in the round, so that the number of loads issued after the ones a
-    // tile waits for is a compile-time constant (the wait then covers that tile only and the
-    // other UNR-1 tiles stay in flight; behind a condition the compiler has to wait for
-    // everything outstanding).  The last rounds, whose refills may be ragged or absent, take
-    // the general path below.
+    // All rounds but the last: UNR tiles taken and replaced, no condition anywhere.  The last
+    // round (the only one that can hold the cache's ragged last tile, or fewer than UNR tiles)
+    // takes what is left with masks and requests nothing.
     const int slot = (int)(__builtin_amdgcn_s_getreg(GETREG_IMMED(3, 0, HW_ID)) % 3u);  // slot on the SIMD
+    const int rounds = (nloc + UNR - 1) / UNR;
+    int li = 0;  // local index of the round's first tile
     int turn = slot;
-    int t = wv;
-    for (; t + (2 * UNR - 1) * NW < nfull; t += UNR * NW) {
+    for (int rr = 0; rr + 1 < rounds; ++rr, li += UNR) {
 #pragma unroll
         for (int x = 0; x < UNR; ++x) {
-            rotate_priority(x == UNR - 1 ? slot : slot + x);
-            take_tile(Full{}, kr[x], vr[x], km[x], vm[x], (t + x * NW) * RPW + r, true);
-            kr[x] = load_stream16(Kb, code_off);
-            vr[x] = load_stream16(Vb, code_off);
-            km[x] = *reinterpret_cast<const uint2*>(Kmb + meta_off);
-            vm[x] = Vmb[meta_off + gi];
-            code_off += NW * RPW * ROWB;
-            meta_off += NW * RPW * GPR;
+            // every other tile at the level of the wave's slot (the hardware's own order among
+            // equal levels favours the low slots; this leans the other way), the tiles in
+            // between walking through the three levels
+            if (x & 1) rotate_priority(slot); else rotate_priority(turn++);
+            take_tile(Full{}, kr[x], vr[x], km[x], vm[x], (wv + (li + x) * NW) * RPW + r, true);
+            request(x);
         }
     }
-    for (; t < ntiles; t += UNR * NW) {
-        rotate_priority(turn++);
+    if (nloc > 0) {
+        rotate_priority(slot);
 #pragma unroll
         for (int x = 0; x < UNR; ++x) {
-            const int tc = t + x * NW;
-            if (tc < ntiles) {
-                const int j = tc * RPW + r;
-                if (tc < nfull)
-                    take_tile(Full{}, kr[x], vr[x], km[x], vm[x], j, true);
-                else
-                    take_tile(Ragged{}, kr[x], vr[x], km[x], vm[x], j, j < nc);
-                if (tc + UNR * NW < ntiles) issue(x, tc + UNR * NW);
+            if (li + x < nloc) {
+                const int j = (wv + (li + x) * NW) * RPW + r;
+                take_tile(Ragged{}, kr[x], vr[x], km[x], vm[x], j, j < nc);
             }
         }
     }
