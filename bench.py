@@ -41,6 +41,11 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 # current run timed the same launches, else `traffic` is null.  Sources: profiles/*hbm_traffic*.
 MEASURED_TRAFFIC = {
     # workload: (steps, warmup, resident_rows_avg, bytes per launch)
+    "cfg1-small-fp32": (200, 5, 225.94, 1504710),
+    "cfg2-opt6.7b-fp16": (200, 5, 959.23, 254330269),
+    "cfg3-opt13b-fp16": (200, 5, 346.75, 462222460),
+    "cfg4-opt66b-fp16": (20, 5, 561.25, 2684627209),
+    "cfg5-opt175b-int4": (200, 5, 574.29, 265940475),
 }
 
 
@@ -517,9 +522,18 @@ def workgroup_lifetimes(B, handle, U, dev, step, dump=None) -> dict:
     }
 
 
+def measured_traffic(m):
+    """HBM bytes per launch from the counter runs, if they were taken on exactly these launches."""
+    known = MEASURED_TRAFFIC.get(m["workload"])
+    if known and (m["K"], m["W"]) == known[:2] and abs(m["rows_avg"] - known[2]) < 0.05:
+        return known[3]
+    return None
+
+
 def config_summary(m) -> dict:
     """One entry of `per_config`."""
     return {
+        "traffic": measured_traffic(m),
         "workload": m["workload"], "steps": m["K"], "cache_instances_round_robin": m["R"],
         "kernel": m["kernel"], "kernel_ms_avg": m["kernel_ms_avg"],
         "algorithmic_bytes_per_launch": m["alg"], "achieved_gbs": m["achieved"], "frac": m["frac"],
@@ -605,10 +619,7 @@ def main() -> int:
             per_config.append(config_summary(m))
             del m
             torch.cuda.empty_cache()
-    traffic = None
-    known = MEASURED_TRAFFIC.get(wl.name)
-    if known and not variant and (K, W) == known[:2] and abs(head["rows_avg"] - known[2]) < 0.05:
-        traffic = known[3]
+    traffic = None if variant else measured_traffic(head)
     res = {
         "metric": "decode tokens/s with budgeted KV cache",
         "value": head["tokens_per_s"],
