@@ -569,47 +569,44 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_kernel(AttnArgs a) {
 
     // A ring of UNR tiles (RPW cache rows each) per wave: as soon as a tile has been consumed
     // its registers are refilled with the tile UNR positions ahead, so UNR-1 tiles of loads
-    // stay in flight behind the arithmetic.  Wave w owns tiles w, w+NW, w+2NW, ...; tiles are
-    // requested in increasing order, so one running byte offset (codes) and one running word
-    // offset (meta) serve every refill.  Tiles below `nfull` are complete; at most one ragged
-    // tile follows them.
-    const int nfull = nc / RPW;
+    // stay in flight behind the arithmetic.  Wave w owns tiles w, w+NW, w+2NW, ...  Every
+    // request is unconditional and has the same form (rows beyond the last resident one repeat
+    // that row: in bounds, finite, never used), so that the number of loads issued after the
+    // ones a tile waits for is a compile-time constant and a wait covers that tile only.
     const int ntiles = (nc + RPW - 1) / RPW;
+    const int nloc = ntiles > wv ? (ntiles - wv + NW - 1) / NW : 0;  // tiles of this wave
     uint4 kr[UNR], vr[UNR];
     uint32_t km[UNR], vm[UNR];
-    uint32_t code_off = ((uint32_t)(wv * RPW + g)) * ROWB + (uint32_t)c * 16u;
-    uint32_t meta_off = ((uint32_t)(wv * RPW + g)) * GPR + (uint32_t)gi;
-    auto issue = [&](int x, int tile) {
-        if (tile < nfull) {
-            kr[x] = load_stream16(Kb, code_off);
-            vr[x] = load_stream16(Vb, code_off);
-            km[x] = __builtin_nontemporal_load(Kmb + meta_off);
-            vm[x] = __builtin_nontemporal_load(Vmb + meta_off);
-        } else {
-            const int j = tile * RPW + g;
-            const uint32_t jj = j < nc ? (uint32_t)j : 0u;
-            kr[x] = load_stream16(Kb, jj * ROWB + (uint32_t)c * 16u);
-            vr[x] = load_stream16(Vb, jj * ROWB + (uint32_t)c * 16u);
-            km[x] = Kmb[jj * GPR + gi];
-            vm[x] = Vmb[jj * GPR + gi];
-        }
-        code_off += NW * RPW * ROWB;
-        meta_off += NW * RPW * GPR;
+    int next_row = wv * RPW + g;  // row this lane group holds in the tile requested next
+    auto request = [&](int x) {
+        const uint32_t jj = (uint32_t)(next_row < nc ? next_row : nc - 1);
+        kr[x] = load_stream16(Kb, jj * ROWB + (uint32_t)c * 16u);
+        vr[x] = load_stream16(Vb, jj * ROWB + (uint32_t)c * 16u);
+        km[x] = Kmb[jj * GPR + gi];
+        vm[x] = Vmb[jj * GPR + gi];
+        next_row += NW * RPW;
     };
+    if (nloc > 0) {
 #pragma unroll
-    for (int x = 0; x < UNR; ++x)
-        if (wv + x * NW < ntiles) issue(x, wv + x * NW);
-    for (int t = wv; t < ntiles; t += UNR * NW) {
+        for (int x = 0; x < UNR; ++x) request(x);
+    }
+    // All rounds but the last hold complete tiles only (a later tile of this wave exists, so
+    // every row of these is resident) and refill each slot; the last round checks both.
+    const int rounds = (nloc + UNR - 1) / UNR;
+    int li = 0;
+    for (int rr = 0; rr + 1 < rounds; ++rr, li += UNR) {
 #pragma unroll
         for (int x = 0; x < UNR; ++x) {
-            const int tc = t + x * NW;
-            if (tc < ntiles) {
-                const int j = tc * RPW + g;
-                if (tc < nfull)
-                    take_row(Full{}, kr[x], vr[x], km[x], vm[x], j, true);
-                else
-                    take_row(Ragged{}, kr[x], vr[x], km[x], vm[x], j, j < nc);
-                if (tc + UNR * NW < ntiles) issue(x, tc + UNR * NW);
+            take_row(Full{}, kr[x], vr[x], km[x], vm[x], (wv + (li + x) * NW) * RPW + g, true);
+            request(x);
+        }
+    }
+    if (nloc > 0) {
+#pragma unroll
+        for (int x = 0; x < UNR; ++x) {
+            if (li + x < nloc) {
+                const int j = (wv + (li + x) * NW) * RPW + g;
+                take_row(Ragged{}, kr[x], vr[x], km[x], vm[x], j, j < nc);
             }
         }
     }
@@ -912,6 +909,14 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_mfma_kernel(AttnArgs a) {
             request(x);
         }
     }
+    // The new row (quantised into LDS at the start) is attended to here, while the last round's
+    // loads are still on their way, rather than after them at the very end of the wave.
+    if constexpr (NW > 1) __syncthreads();  // (a single wave reads what it wrote itself)
+    if (wv == 0) {
+        const uint4 nk = *reinterpret_cast<const uint4*>(&new_codes[0][kb * 16]);
+        const uint4 nv = *reinterpret_cast<const uint4*>(&new_codes[1][kb * 16]);
+        take_tile(Ragged{}, nk, nv, make_uint2(new_meta[0][0], new_meta[0][1]), new_meta[1][gi], nc, r == 0);
+    }
     if (nloc > 0) {
         rotate_priority(slot);
 #pragma unroll
@@ -924,12 +929,6 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_mfma_kernel(AttnArgs a) {
     }
     __builtin_amdgcn_s_setprio(0);
     clk.streamed(a);
-    __syncthreads();  // the quantised new row is in LDS
-    if (wv == 0) {
-        const uint4 nk = *reinterpret_cast<const uint4*>(&new_codes[0][kb * 16]);
-        const uint4 nv = *reinterpret_cast<const uint4*>(&new_codes[1][kb * 16]);
-        take_tile(Ragged{}, nk, nv, make_uint2(new_meta[0][0], new_meta[0][1]), new_meta[1][gi], nc, r == 0);
-    }
     // Add up the 16 cache rows of every DPP row, then remove the pair offsets (1024*weight,
     // resp. 1024*weight/16) and add the zero points.
     {
