@@ -41,11 +41,11 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 # current run timed the same launches, else `traffic` is null.  Sources: profiles/*hbm_traffic*.
 MEASURED_TRAFFIC = {
     # workload: (steps, warmup, resident_rows_avg, bytes per launch)
-    "cfg1-small-fp32": (200, 5, 225.94, 1504710),
-    "cfg2-opt6.7b-fp16": (200, 5, 959.23, 254330269),
-    "cfg3-opt13b-fp16": (200, 5, 346.75, 462222460),
-    "cfg4-opt66b-fp16": (20, 5, 561.25, 2684627209),
-    "cfg5-opt175b-int4": (200, 5, 574.29, 265940475),
+    "cfg1-small-fp32": (200, 5, 225.94, 1525191),
+    "cfg2-opt6.7b-fp16": (200, 5, 959.23, 254320975),
+    "cfg3-opt13b-fp16": (200, 5, 346.75, 462212911),
+    "cfg4-opt66b-fp16": (20, 5, 561.25, 2684529040),
+    "cfg5-opt175b-int4": (200, 5, 574.29, 265962967),
 }
 
 
@@ -662,7 +662,7 @@ def main() -> int:
     if args.ragged:
         res["config"]["ragged_prompt_lengths"] = head["plens"]
     if not args.no_cpu_baseline and not args.ragged:
-        units = args.cpu_units or {1: 12, 2: 512, 3: 256, 4: 256, 5: 256}[wl.config_id]
+        units = args.cpu_units or {1: 12, 2: 512, 3: 512, 4: 1024, 5: 512}[wl.config_id]
         res["cpu_baseline"] = cpu_baseline(wl, units, args.cpu_steps)
     print(json.dumps(res))
     return 0
