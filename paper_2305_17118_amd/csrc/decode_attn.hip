@@ -191,16 +191,78 @@ __device__ __forceinline__ void store_through(_Float16* p, _Float16 v) {
     __hip_atomic_store(reinterpret_cast<unsigned short*>(p), c.u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Shared tail of the attention kernels: combine the partials, write `out`, then the
-// probability epilogue with the update of the importance record (Alg. 2, kept online).
-// NT = threads of the workgroup, NP = number of partial (m, l, acc[D]) triples published in LDS.
+// The probability epilogue with the update of the importance record (Alg. 2, kept online):
+// p_j = exp2(s_j - M) / L for every resident slot, tested against the threshold.
 // Bucket mode: two 16-bit counters per word, +1 where the probability is below the threshold.
 // Ring mode: one 32-bit ring word per slot; this step's bit is set or cleared.
+// The scores of all the prefetched words of a thread are read from LDS before any of them is
+// used, whether or not the word lies below n (LDS holds C >= n scores and the partials behind
+// them, so the read is in bounds; the value is then unused): behind a condition every read
+// would be waited for on its own, one LDS round trip after the other.
+template <int NT>
+__device__ __forceinline__ void finish_counters(const AttnArgs& a, int u, const float* s_lds, float M, float invL,
+                                                const uint32_t (&pre)[cnt_pf(NT)]) {
+    constexpr int CNT_PF = cnt_pf(NT);
+    const int tid = threadIdx.x;
+    uint32_t* cw = reinterpret_cast<uint32_t*>(a.cnt + (size_t)u * a.cnt_unit_stride);
+    const int n = a.n;
+    if (a.ring_bit) {
+        float* probs = a.probs ? a.probs + (size_t)u * a.probs_stride : nullptr;
+        auto do_slot = [&](int j, uint32_t word, float score) {
+            const float p = fast_exp2(score - M) * invL;
+            if (probs) probs[j] = p;
+            const uint32_t upd = (p < a.tau) ? (word | a.ring_bit) : (word & ~a.ring_bit);
+            if (upd != word) {
+                if (a.through) store_through(cw + j, upd); else cw[j] = upd;
+            }
+        };
+        float sc[CNT_PF];
+#pragma unroll
+        for (int k = 0; k < CNT_PF; ++k) {
+            const int j = tid + k * NT;
+            sc[k] = s_lds[j < n ? j : 0];
+        }
+#pragma unroll
+        for (int k = 0; k < CNT_PF; ++k) {
+            const int j = tid + k * NT;
+            if (j < n) do_slot(j, pre[k], sc[k]);
+        }
+        for (int j = tid + CNT_PF * NT; j < n; j += NT) do_slot(j, cw[j], s_lds[j]);
+        return;
+    }
+    float2* probs = a.probs ? reinterpret_cast<float2*>(a.probs + (size_t)u * a.probs_stride) : nullptr;
+    auto do_word = [&](int i, uint32_t word, float2 score) {
+        const int j = 2 * i;  // j < n here; slot j+1 may be the first free one
+        const float p0 = fast_exp2(score.x - M) * invL;
+        const float p1 = (j + 1 < n) ? fast_exp2(score.y - M) * invL : 0.f;
+        if (probs) probs[i] = make_float2(p0, p1);
+        const uint32_t inc = (p0 < a.tau ? 1u : 0u) | ((j + 1 < n && p1 < a.tau) ? 0x10000u : 0u);
+        if (a.counted && inc) {
+            if (a.through) store_through(cw + i, word + inc); else cw[i] = word + inc;
+        }
+    };
+    const float2* s2 = reinterpret_cast<const float2*>(s_lds);  // slots 2i, 2i+1
+    float2 sc[CNT_PF];
+#pragma unroll
+    for (int k = 0; k < CNT_PF; ++k) {
+        const int i = tid + k * NT;
+        sc[k] = s2[2 * i < n ? i : 0];
+    }
+#pragma unroll
+    for (int k = 0; k < CNT_PF; ++k) {
+        const int i = tid + k * NT;
+        if (2 * i < n) do_word(i, pre[k], sc[k]);
+    }
+    for (int i = tid + CNT_PF * NT; 2 * i < n; i += NT) do_word(i, a.counted ? cw[i] : 0u, s2[i]);
+}
+
+// Shared tail of the attention kernels: combine the partials, write `out`, then the
+// probability epilogue.  NT = threads of the workgroup, NP = number of partial (m, l, acc[D])
+// triples published in LDS.
 template <typename TOut, int D, int NT, int NP>
 __device__ __forceinline__ void finish_unit(const AttnArgs& a, int u, const float* s_lds,
                                             const float* part_m, const float* part_l,
                                             const float* part_acc, const uint32_t (&pre)[cnt_pf(NT)]) {
-    constexpr int CNT_PF = cnt_pf(NT);
     const int tid = threadIdx.x;
     float M = part_m[0];
 #pragma unroll
@@ -218,43 +280,7 @@ __device__ __forceinline__ void finish_unit(const AttnArgs& a, int u, const floa
             if (a.through) store_through(dst, (TOut)(o * invL)); else *dst = (TOut)(o * invL);
         }
     }
-    uint32_t* cw = reinterpret_cast<uint32_t*>(a.cnt + (size_t)u * a.cnt_unit_stride);
-    const int n = a.n;
-    if (a.ring_bit) {
-        float* probs = a.probs ? a.probs + (size_t)u * a.probs_stride : nullptr;
-        auto do_slot = [&](int j, uint32_t word) {
-            const float p = fast_exp2(s_lds[j] - M) * invL;
-            if (probs) probs[j] = p;
-            const uint32_t upd = (p < a.tau) ? (word | a.ring_bit) : (word & ~a.ring_bit);
-            if (upd != word) {
-                if (a.through) store_through(cw + j, upd); else cw[j] = upd;
-            }
-        };
-#pragma unroll
-        for (int k = 0; k < CNT_PF; ++k) {
-            const int j = tid + k * NT;
-            if (j < n) do_slot(j, pre[k]);
-        }
-        for (int j = tid + CNT_PF * NT; j < n; j += NT) do_slot(j, cw[j]);
-        return;
-    }
-    float2* probs = a.probs ? reinterpret_cast<float2*>(a.probs + (size_t)u * a.probs_stride) : nullptr;
-    auto do_word = [&](int i, uint32_t word) {
-        const int j = 2 * i;  // j < n here; slot j+1 may be the first free one
-        const float p0 = fast_exp2(s_lds[j] - M) * invL;
-        const float p1 = (j + 1 < n) ? fast_exp2(s_lds[j + 1] - M) * invL : 0.f;
-        if (probs) probs[i] = make_float2(p0, p1);
-        const uint32_t inc = (p0 < a.tau ? 1u : 0u) | ((j + 1 < n && p1 < a.tau) ? 0x10000u : 0u);
-        if (a.counted && inc) {
-            if (a.through) store_through(cw + i, word + inc); else cw[i] = word + inc;
-        }
-    };
-#pragma unroll
-    for (int k = 0; k < CNT_PF; ++k) {
-        const int i = tid + k * NT;
-        if (2 * i < n) do_word(i, pre[k]);
-    }
-    for (int i = tid + CNT_PF * NT; 2 * i < n; i += NT) do_word(i, a.counted ? cw[i] : 0u);
+    finish_counters<NT>(a, u, s_lds, M, invL, pre);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -982,16 +1008,34 @@ __global__ void __launch_bounds__(NW * 64) attn_i4_mfma_kernel(AttnArgs a) {
                 acc[w * 8 + k + 4] = row16_sum(acc[w * 8 + k + 4]) + o;
             }
     }
-    if (r == 0) {
+    if constexpr (NW == 1) {
+        // A single wave already holds everything: m is the wave's maximum, l the sum over all
+        // rows, and lane (r = 0, kb) the 32 output channels 32*kb ..; no trip through LDS.
+        const float invL = 1.0f / l;
+        if (a.out && r == 0) {
+            _Float16* dst = (_Float16*)a.out + (size_t)u * a.out_stride + kb * 32;
 #pragma unroll
-        for (int i = 0; i < 32; ++i) part_acc[wv * D + kb * 32 + i] = acc[i];
-        if (kb == 0) {
-            part_m[wv] = m;
-            part_l[wv] = l;
+            for (int w = 0; w < 4; ++w) {
+                Frag<_Float16, 8> o;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o.e[e] = (_Float16)(acc[w * 8 + e] * invL);
+                if (a.through) store_through16(dst + w * 8, o.raw); else *reinterpret_cast<uint4*>(dst + w * 8) = o.raw;
+            }
         }
+        __syncthreads();  // the scores in LDS are complete
+        finish_counters<64>(a, u, s_lds, m, invL, cpre);
+    } else {
+        if (r == 0) {
+#pragma unroll
+            for (int i = 0; i < 32; ++i) part_acc[wv * D + kb * 32 + i] = acc[i];
+            if (kb == 0) {
+                part_m[wv] = m;
+                part_l[wv] = l;
+            }
+        }
+        __syncthreads();
+        finish_unit<_Float16, D, NW * 64, NW>(a, u, s_lds, part_m, part_l, part_acc, cpre);
     }
-    __syncthreads();
-    finish_unit<_Float16, D, NW * 64, NW>(a, u, s_lds, part_m, part_l, part_acc, cpre);
     clk.finish(a, u);
 }
 
