@@ -67,6 +67,12 @@ struct AttnArgs {
     long q_keep_slot_bytes;  // ragged + kept queries: q_keep = slot 0 of unit 0, slots this far apart
     unsigned long long* trace;  // diagnostics, normally null: [U][4] clock readings per workgroup
     int through;  // counters and outputs are written through the L2 (see store_through)
+    // Units handed out by ticket (fp32/fp16 kernel, lock step, many units; null otherwise):
+    // workgroups below n_static own the unit of their index, the n_ticket_wgs workgroups from
+    // there on draw a number from *ticket and take unit n_static + number while it is below
+    // n_tail (the rest return at once); the last to draw sets the counter back to zero.
+    int32_t* ticket;
+    int n_static, n_tail, n_ticket_wgs;
 };
 
 // Diagnostics (a.trace set): every workgroup reports when it started, when its K/V stream ended
@@ -319,7 +325,26 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
     float* part_l = part_m + NW;
     float* part_acc = part_l + NW;
 
-    const int u = blockIdx.x;
+    // Workgroup i runs on XCD i mod 8 whatever the XCDs' progress, and the XCDs are not equally
+    // fast (measured: the odd ones about 4% behind on 9216 units), so with one unit per workgroup
+    // index the launch lasts as long as the slowest XCD.  The last units are therefore not tied
+    // to a workgroup index: twice as many workgroups as there are such units draw tickets, an XCD
+    // that gets to its ticket workgroups early takes more of the units, and workgroups that draw
+    // when none is left return.
+    int u = blockIdx.x;
+    if (a.ticket && u >= a.n_static) {
+        __shared__ int drawn;
+        if (threadIdx.x == 0) {
+            const int k = __hip_atomic_fetch_add(a.ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (k == a.n_ticket_wgs - 1)  // every workgroup has drawn: ready for the next launch
+                __hip_atomic_store(a.ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            drawn = k;
+        }
+        __syncthreads();
+        const int k = __builtin_amdgcn_readfirstlane(drawn);
+        if (k >= a.n_tail) return;
+        u = a.n_static + k;
+    }
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int g = lane / LPR, c = lane % LPR;
     const int nc = a.n - 1;  // rows resident before this step; the new row goes to slot nc
@@ -1046,12 +1071,12 @@ __global__ void clear_u32_kernel(uint32_t* p, size_t n) {
 }
 
 template <typename T, int D, int UNR>
-hipError_t launch_rows(const AttnArgs& a, int U, int nw, hipStream_t stream) {
+hipError_t launch_rows(const AttnArgs& a, int grid, int nw, hipStream_t stream) {
     const size_t lds = ((size_t)a.C + 2 * nw + (size_t)nw * D) * sizeof(float);
     switch (nw) {
-        case 4: attn_rows_kernel<T, D, 4, UNR><<<U, 256, lds, stream>>>(a); break;
-        case 8: attn_rows_kernel<T, D, 8, UNR><<<U, 512, lds, stream>>>(a); break;
-        default: attn_rows_kernel<T, D, 16, UNR><<<U, 1024, lds, stream>>>(a); break;
+        case 4: attn_rows_kernel<T, D, 4, UNR><<<grid, 256, lds, stream>>>(a); break;
+        case 8: attn_rows_kernel<T, D, 8, UNR><<<grid, 512, lds, stream>>>(a); break;
+        default: attn_rows_kernel<T, D, 16, UNR><<<grid, 1024, lds, stream>>>(a); break;
     }
     return hipGetLastError();
 }
@@ -1141,12 +1166,24 @@ hipError_t launch_decode_step(const Layout& L, const StepArgs& s, hipStream_t st
         a.through = (size_t)L.U * per_unit >= ((size_t)8 << 20);
     }
     const int nw = pick_waves(L.U);
+    // Tickets for the last sixteenth of the units once a launch has several generations of
+    // workgroups per XCD (512 workgroups are resident at a time).
+    a.ticket = nullptr;
+    a.n_static = L.U;
+    a.n_tail = a.n_ticket_wgs = 0;
+    if (L.ticket && !s.seq.off && L.kv_dtype != KV_I4G64 && L.U >= 2048) {
+        a.ticket = L.ticket;
+        a.n_tail = L.U / 16;
+        a.n_static = L.U - a.n_tail;
+        a.n_ticket_wgs = 2 * a.n_tail;
+    }
+    const int grid = a.n_static + a.n_ticket_wgs;
     if (L.kv_dtype == KV_F32)
-        return L.d == 64 ? launch_rows<float, 64, 2>(a, L.U, nw, stream)
-                         : launch_rows<float, 128, 2>(a, L.U, nw, stream);
+        return L.d == 64 ? launch_rows<float, 64, 2>(a, grid, nw, stream)
+                         : launch_rows<float, 128, 2>(a, grid, nw, stream);
     if (L.kv_dtype == KV_F16)
-        return L.d == 64 ? launch_rows<_Float16, 64, 2>(a, L.U, nw, stream)
-                         : launch_rows<_Float16, 128, 2>(a, L.U, nw, stream);
+        return L.d == 64 ? launch_rows<_Float16, 64, 2>(a, grid, nw, stream)
+                         : launch_rows<_Float16, 128, 2>(a, grid, nw, stream);
     const int nw4 = pick_waves_i4(L.U);
     return L.d == 64 ? launch_i4<64, 4>(a, L.U, nw4, stream) : launch_i4_mfma<4>(a, L.U, nw4, stream);
 }
@@ -1154,6 +1191,7 @@ hipError_t launch_decode_step(const Layout& L, const StepArgs& s, hipStream_t st
 hipError_t launch_clear_counters(const Layout& L, hipStream_t stream) {
     const size_t words = L.W32 ? (size_t)L.U * L.W32 * L.C : (size_t)L.U * L.E * L.C / 2;  // C is even
     clear_u32_kernel<<<1024, 256, 0, stream>>>(reinterpret_cast<uint32_t*>(L.cnt), words);
+    if (L.ticket) clear_u32_kernel<<<1, 64, 0, stream>>>(reinterpret_cast<uint32_t*>(L.ticket), 1);
     return hipGetLastError();
 }
 

@@ -27,7 +27,7 @@ struct sc_cache {
     std::vector<int32_t> wanted;   // scratch for building the next table
     bool table_known;              // false until the first upload
     int32_t step;                  // ragged decode calls made so far
-    int32_t* seq_off;              // device [batch], followed by the device-side step count
+    int32_t* seq_off;              // device [batch], followed by the device-side step count and the ticket counter
     bool device_clock;             // ragged decode launches read the step count from the device
     bool step_dev_known;           // the device-side count equals `step`
     std::vector<uint8_t> last_active;  // sequences of the most recent ragged decode step
@@ -103,7 +103,7 @@ sc_status derive(const sc_config* cfg, Sizes* s) {
                                  (cfg->kv_dtype == SC_KV_F32 ? 4 : 2));
     s->off_map = off;   off = align_up(off + rows * 4);
     s->off_first = off; off = align_up(off + (size_t)cfg->batch * cfg->heads * 4);
-    s->off_seq = off;   off = align_up(off + ((size_t)cfg->batch + 1) * 4);
+    s->off_seq = off;   off = align_up(off + ((size_t)cfg->batch + 2) * 4);  // table, step count, ticket counter
     s->total = off;
     return SC_OK;
 }
@@ -415,6 +415,7 @@ sc_status sc_cache_create(const sc_config* cfg, void* dev_workspace, size_t byte
     L.w = cfg->history;
     L.srcmap = reinterpret_cast<int32_t*>(base + s.off_map);
     L.first = reinterpret_cast<int32_t*>(base + s.off_first);
+    L.ticket = reinterpret_cast<int32_t*>(base + s.off_seq) + cfg->batch + 1;
     c->ragged = false;
     c->table_known = false;
     c->step = 0;

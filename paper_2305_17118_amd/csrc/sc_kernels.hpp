@@ -26,6 +26,7 @@ struct Layout {
     int w;          // history window in steps
     int32_t* srcmap;  // [U][C] scratch written by select, read by compact
     int32_t* first;   // [U] scratch: first slot whose row moves
+    int32_t* ticket;  // one counter, zero between launches: units of a decode launch handed out by ticket
 };
 
 // ---- Ragged batches: every sequence runs Alg. 1 on its own clock ----------------------------

@@ -8,7 +8,7 @@ must agree bit for bit at every compression.
 import pytest
 
 from paper_2305_17118_amd import binding as B
-from paper_2305_17118_amd.workloads import CONFIGS, sample_units
+from paper_2305_17118_amd.workloads import CONFIGS, KV_F16, KV_F32, Workload, sample_units
 
 from .parity_util import ParityRun
 
@@ -19,7 +19,9 @@ def _sample(wl, extra):
     if wl.units <= 64:
         return list(range(wl.units))
     first_seq = list(range(wl.heads))
-    return sorted(set(first_seq) | set(sample_units(wl, extra)))
+    # the last units of a large batch are handed out by ticket rather than by workgroup index
+    last = [wl.units - 1, wl.units - 2, wl.units - wl.units // 32]
+    return sorted(set(first_seq) | set(sample_units(wl, extra)) | set(last))
 
 
 @pytest.mark.parametrize("idx,extra", [(0, 0), (1, 16), (2, 24), (3, 24), (4, 24)],
@@ -36,6 +38,19 @@ def test_workload_matches_oracle(idx, extra):
                    if t >= wl.budget + 1 and (t - wl.budget - 1) % wl.drop == 0)
     assert st["compressions"] == expected
     assert run.cache.n <= wl.budget + 1
+
+
+@pytest.mark.parametrize("kv,d", [(KV_F32, 64), (KV_F16, 128)], ids=["f32", "f16"])
+def test_many_small_units_drawn_by_ticket(kv, d):
+    """2048 units and more: the last sixteenth of the units is not tied to a workgroup index
+    (workgroups draw tickets for them, surplus workgroups return).  Small caches, every step
+    compared on the first sequence, on scattered units and on units of the ticketed tail."""
+    wl = Workload("tickets", 90, 96, 32, d, kv, 40, 50, 32, 4, 16, 8)
+    assert wl.units >= 2048
+    tail = list(range(wl.units - wl.units // 16, wl.units, 37)) + [wl.units - 1]
+    run = ParityRun(wl, sel=sorted(set(_sample(wl, 16)) | set(tail)))
+    st = run.run(check_rows_every=1)
+    assert st["steps"] == wl.total and st["compressions"] >= 6
 
 
 def test_headline_workload_high_water_policy():
