@@ -1,5 +1,7 @@
 """Ragged batches through the C ABI (sc_prefill_ragged / sc_decode_step_ragged / sc_compress_ragged)
 against one single-sequence oracle per batch entry."""
+import ctypes as C
+
 import numpy as np
 import pytest
 import torch
@@ -484,3 +486,48 @@ def test_layer_set_step_in_one_call_and_replayed_from_one_graph():
                 u, nb = slice(b * wl.heads, (b + 1) * wl.heads), alone[l].len_seq(b)[0]
                 assert torch.equal(alone[l].pos()[u, :nb], other.pos()[u, :nb])
                 assert torch.equal(Ka[u, :nb], Kb[u, :nb]) and torch.equal(Va[u, :nb], Vb[u, :nb])
+
+
+def test_layer_set_calls_reject_bad_arguments_and_change_nothing():
+    """Argument and state errors of the layer-set calls are found before anything is enqueued:
+    strides that are too small or not 16-byte multiples, null pointers, a step or a replay
+    without the device clock, a compression when none is due; the caches stay where they were."""
+    kv, L = KV_F16, 3
+    wl = _wl("layers-errors", 2, 2, 128, kv, 30, 4, 16, 8)
+    U, d = wl.units, wl.head_dim
+    cfg = B.make_config(wl.batch, wl.heads, d, kv, wl.budget, wl.recent, wl.history, wl.drop)
+    ls = B.LayerSet(cfg, [30, 34, 38], [8, 8, 8])
+    q, k, v = (torch.from_numpy(a).cuda() for a in streams(wl, steps=12))
+    for l in range(L):
+        ls[l].prefill_ragged(q, k, v, [10] * wl.batch, 12 * d, None)
+    x = torch.zeros(L, U, d, dtype=torch.float16, device="cuda")
+    out = torch.empty(L, U, d, dtype=torch.float16, device="cuda")
+    lib, h, s = B.lib(), ls.handle, ls._stream()
+    due = C.c_int32(-7)
+    p, o = x.data_ptr(), out.data_ptr()
+    before = [[ls[l].len_seq(b) for b in range(wl.batch)] for l in range(L)]
+
+    def call(q_=p, k_=p, v_=p, ls_stride=U * d, in_stride=0, o_=o, out_stride=U * d):
+        return lib.sc_layers_decode_step(h, q_, k_, v_, ls_stride, in_stride, o_, out_stride, None, C.byref(due), s)
+
+    assert call(q_=None) == B.SC_ERR_INVALID_ARG and call(k_=None) == B.SC_ERR_INVALID_ARG
+    assert call(v_=None) == B.SC_ERR_INVALID_ARG and call(o_=None) == B.SC_ERR_INVALID_ARG
+    assert call(ls_stride=U * d - 8) == B.SC_ERR_INVALID_ARG       # layers would overlap
+    assert call(ls_stride=U * d + 4) == B.SC_ERR_INVALID_ARG       # not a multiple of 16 bytes
+    assert call(out_stride=U * d - 8) == B.SC_ERR_INVALID_ARG
+    assert call(out_stride=U * d + 4) == B.SC_ERR_INVALID_ARG
+    assert call(in_stride=2 * d) == B.SC_ERR_INVALID_ARG            # units 2d apart do not fit in U*d per layer
+    assert lib.sc_layers_decode_step(None, p, p, p, U * d, 0, o, U * d, None, C.byref(due), s) == B.SC_ERR_INVALID_ARG
+    assert due.value == -7
+    with pytest.raises(B.ScError) as e:   # nothing captured to replay: the clock is off and no step was taken
+        ls.note_replays(1)
+    assert e.value.status == B.SC_ERR_STATE
+    with pytest.raises(B.ScError) as e:
+        ls.compress()
+    assert e.value.status == B.SC_ERR_STATE
+    torch.cuda.synchronize()
+    assert before == [[ls[l].len_seq(b) for b in range(wl.batch)] for l in range(L)]
+    assert call() == B.SC_OK and due.value == 0
+    torch.cuda.synchronize()
+    assert [[ls[l].len_seq(b) for b in range(wl.batch)] for l in range(L)] == \
+        [[(n + 1, t + 1) for n, t in row] for row in before]
