@@ -627,6 +627,8 @@ def test_prefill_can_be_captured_in_a_graph_and_replayed(kv):
     (3, 24, KV_F32, 64, 300),
     (2, 80, KV_F16, 64, 290),
     (1, 5, KV_F32, 128, 255),
+    (2, 40, KV_F32, 64, 600),
+    (1, 3, KV_F16, 64, 513),      # head size 64, capacity just above 512 slots
 ])
 def test_few_units_with_many_rows(batch, heads, kv, d, budget):
     """Small batches with long caches (the shape of low-latency serving): a streamed prompt, then

@@ -33,6 +33,8 @@ LONG_CASES = [
     # few units with long caches
     (_wl("rag-long-f16", 3, 4, 128, KV_F16, 330, 8, 64, 32, 0.05), [300, 40, 0], [0, 0, 10], [120, 150, 100]),
     (_wl("rag-long-f32", 2, 3, 64, KV_F32, 280, 6, 40, 20), [270, 5], [0, 0], [90, 110]),
+    # capacity above 512 slots, one sequence nearly full and one nearly empty
+    (_wl("rag-split-f16", 2, 3, 128, KV_F16, 520, 8, 64, 32, 0.05), [505, 60], [0, 0], [90, 120]),
 ]
 
 
