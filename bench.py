@@ -549,8 +549,8 @@ def config_summary(m) -> dict:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=96)
-    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, help="headline workload 1..5 (4 = the largest)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size "
                     "(few-unit batches; the line is then not the workload's own)")
