@@ -245,6 +245,35 @@ def copy_probe(args, dev) -> int:
     return 0
 
 
+def read_probe(args, dev) -> int:
+    """What a launch that only reads reaches on this chip (sc_diag_read_bandwidth: --copy-mib MiB,
+    rounded down to a multiple of 32, per launch; three buffers in turn so that every launch
+    finds its buffer cold): the reference point for the decode kernels' fractions of peak."""
+    import torch
+
+    from paper_2305_17118_amd import binding as B
+
+    n = max(32, args.copy_mib // 32 * 32) * 2 ** 20
+    bufs = [torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(3)]
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    stream = int(torch.cuda.current_stream(dev).cuda_stream)
+    reps = max(10, args.steps)
+    out = {"probe": "pure read", "mib": n // 2 ** 20, "launches": reps}
+    for name, nt in (("nontemporal", True), ("plain", False)):
+        for i in range(5):
+            B.sc_diag_read_bandwidth(bufs[i % 3].data_ptr(), n, nt, sink.data_ptr(), stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            B.sc_diag_read_bandwidth(bufs[i % 3].data_ptr(), n, nt, sink.data_ptr(), stream)
+        e1.record()
+        e1.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        out[name] = {"us_per_launch": us, "gbs": n / us / 1e3, "frac_of_8tbs": n / us / 1e3 / HBM_PEAK_GBS}
+    print(json.dumps(out))
+    return 0
+
+
 def bench_layers(args, wl, dev) -> int:
     """A model step = one decode step of each of --layers caches of the workload's shape (the
     layers of a model, stepped one after another on one stream), enqueued three ways:
@@ -556,9 +585,10 @@ def main() -> int:
                     "(few-unit batches; the line is then not the workload's own)")
     ap.add_argument("--rotate", type=int, default=0, help="cache instances stepped round-robin "
                     "(0 = at least 4 and enough to cover three times the 256 MB last-level cache)")
-    ap.add_argument("--phase", choices=("decode", "prefill", "copy", "layers"), default="decode",
+    ap.add_argument("--phase", choices=("decode", "prefill", "copy", "read", "layers"), default="decode",
                     help="decode = the headline metric; prefill = the prompt phase; copy = plain "
-                         "device copies of --copy-mib MiB (calibration of HBM traffic counters); "
+                         "device copies of --copy-mib MiB (calibration of HBM traffic counters); read = a launch that "
+                         "only reads --copy-mib MiB (what reading reaches on this chip); "
                          "layers = --layers caches stepped per model step, eager against one HIP graph")
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--copy-mib", type=int, default=1024)
@@ -603,6 +633,8 @@ def main() -> int:
         return bench_prefill(args, wl, dev)
     if args.phase == "copy":
         return copy_probe(args, dev)
+    if args.phase == "read":
+        return read_probe(args, dev)
     if args.phase == "layers":
         return bench_layers(args, wl, dev)
 

@@ -449,6 +449,19 @@ sc_status sc_diag_persistence(const float *probs, int32_t units, int32_t length,
 sc_status sc_diag_kept_mass(const sc_cache *c, const float *probs_full, int64_t unit_stride,
                             float *mass_out, void *stream);
 
+/* Reference point for the roofline fractions: one launch that reads `bytes` of device memory and
+ * does nothing else (16-byte loads, eight in flight per thread, 1024 workgroups of 256 threads,
+ * each on its own contiguous share).  Timing it (HIP events, rocprofv3) gives the read bandwidth
+ * this chip reaches in practice, which the decode kernels, bound by the same reads (Sec. 4.1's
+ * estimator touches every resident row once per step), cannot exceed.
+ *   buf         : device, 16-byte aligned, at least `bytes` long; bytes a multiple of 32 MiB
+ *   nontemporal : non-zero = streaming loads (as the decode kernels use), 0 = plain loads
+ *   sink        : device uint32, written only if the folded data equals a fixed constant (it
+ *                 keeps the loads alive; in practice it stays untouched)
+ * SC_ERR_INVALID_ARG for null or misaligned pointers or a size that is no multiple of 32 MiB. */
+sc_status sc_diag_read_bandwidth(const void *buf, size_t bytes, int32_t nontemporal, uint32_t *sink,
+                                 void *stream);
+
 /* Diagnostic of the decode-attention launch itself (where the time of a step goes): while a
  * buffer is set, every workgroup of the launches made by sc_decode_step / sc_decode_step_ragged
  * (one workgroup per unit; units of idle sequences write nothing) records

@@ -26,7 +26,7 @@ EXPORTS = (
     "sc_config_sizes", "sc_workspace_bytes", "sc_schedule", "sc_cache_create", "sc_cache_reset",
     "sc_cache_destroy",
     "sc_decode_step", "sc_compress", "sc_compress_static", "sc_prefill", "sc_prefill_plan", "sc_cache_len", "sc_cache_view", "sc_status_str",
-    "sc_diag_persistence", "sc_diag_kept_mass", "sc_diag_trace",
+    "sc_diag_persistence", "sc_diag_kept_mass", "sc_diag_trace", "sc_diag_read_bandwidth",
     "sc_prefill_ragged", "sc_decode_step_ragged", "sc_compress_ragged", "sc_cache_len_seq",
     "sc_schedule_rows", "sc_cache_reset_seq", "sc_cache_device_clock", "sc_steps_until_due",
     "sc_cache_note_replays",
@@ -81,6 +81,7 @@ def lib():
     l.sc_diag_persistence.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int32, vp, vp]
     l.sc_diag_kept_mass.argtypes = [vp, vp, C.c_int64, vp, vp]
     l.sc_diag_trace.argtypes = [vp, vp]
+    l.sc_diag_read_bandwidth.argtypes = [vp, C.c_size_t, C.c_int32, vp, vp]
     l.sc_prefill_ragged.argtypes = [vp, vp, vp, vp, i32p, C.c_int64, vp, vp, C.c_int32, vp]
     l.sc_decode_step_ragged.argtypes = [vp, vp, vp, vp, C.c_int64, vp, vp, C.POINTER(C.c_uint8), i32p, vp]
     l.sc_compress_ragged.argtypes = [vp, vp, vp, vp]
@@ -267,6 +268,11 @@ def sc_diag_persistence(probs_ptr, units, length, row_stride, unit_stride, split
 def sc_diag_kept_mass(handle, probs_full_ptr, unit_stride, mass_ptr, stream=0) -> None:
     _check(lib().sc_diag_kept_mass(handle, probs_full_ptr, int(unit_stride), mass_ptr, stream),
            "sc_diag_kept_mass")
+
+
+def sc_diag_read_bandwidth(buf_ptr, nbytes: int, nontemporal: bool, sink_ptr, stream=0) -> None:
+    _check(lib().sc_diag_read_bandwidth(buf_ptr, int(nbytes), 1 if nontemporal else 0, sink_ptr, stream),
+           "sc_diag_read_bandwidth")
 
 
 def sc_diag_trace(handle, trace_ptr=None) -> None:

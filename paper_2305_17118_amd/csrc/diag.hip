@@ -56,7 +56,38 @@ kept_mass_kernel(const int32_t* __restrict__ pos, int C, int n, const float* __r
     if (threadIdx.x == 0) mass[u] = (part[0] + part[1]) + (part[2] + part[3]);
 }
 
+// What reading a buffer and nothing else reaches on this chip: every thread fetches 16 bytes
+// at a time, eight loads in flight, workgroup b owns the b-th contiguous share of the buffer.
+// The reference point for the decode kernels' fraction of peak (they can at best stream their
+// bytes this fast).  The loaded words are folded into a value that is stored only if it equals
+// a constant it never equals in practice, so that the loads cannot be dropped.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+template <bool NT>
+__global__ void __launch_bounds__(256)
+read_stream_kernel(const u32x4_t* __restrict__ p, size_t pieces_per_wg, uint32_t* __restrict__ sink) {
+    constexpr int UNR = 8;
+    const u32x4_t* base = p + (size_t)blockIdx.x * pieces_per_wg;
+    uint32_t acc = 0;
+    for (size_t i = threadIdx.x; i + (UNR - 1) * 256 < pieces_per_wg; i += UNR * 256) {
+        u32x4_t r[UNR];
+#pragma unroll
+        for (int x = 0; x < UNR; ++x) r[x] = NT ? __builtin_nontemporal_load(base + i + x * 256) : base[i + x * 256];
+#pragma unroll
+        for (int x = 0; x < UNR; ++x) acc ^= r[x].x ^ r[x].y ^ r[x].z ^ r[x].w;
+    }
+    if (acc == 0x9E3779B9u) *sink = acc;
+}
+
 }  // namespace
+
+hipError_t launch_read_stream(const void* buf, size_t bytes, bool nontemporal, uint32_t* sink, hipStream_t stream) {
+    const size_t pieces_per_wg = bytes / 16 / 1024;  // bytes is a multiple of 1024 * 8 * 256 * 16
+    if (nontemporal)
+        read_stream_kernel<true><<<1024, 256, 0, stream>>>(static_cast<const u32x4_t*>(buf), pieces_per_wg, sink);
+    else
+        read_stream_kernel<false><<<1024, 256, 0, stream>>>(static_cast<const u32x4_t*>(buf), pieces_per_wg, sink);
+    return hipGetLastError();
+}
 
 hipError_t launch_persistence(const float* probs, int units, int length, long row_stride, long unit_stride,
                               int split, int32_t* counts, hipStream_t stream) {

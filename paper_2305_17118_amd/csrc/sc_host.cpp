@@ -826,6 +826,16 @@ sc_status sc_diag_trace(sc_cache* c, uint64_t* trace_out) {
     return SC_OK;
 }
 
+sc_status sc_diag_read_bandwidth(const void* buf, size_t bytes, int32_t nontemporal, uint32_t* sink,
+                                 void* stream) {
+    if (!buf || !sink || bytes == 0 || bytes % ((size_t)32 << 20) != 0) return SC_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(buf) % 16 != 0 || reinterpret_cast<uintptr_t>(sink) % 4 != 0)
+        return SC_ERR_INVALID_ARG;
+    if (sc::launch_read_stream(buf, bytes, nontemporal != 0, sink, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return SC_ERR_DEVICE;
+    return SC_OK;
+}
+
 sc_status sc_diag_persistence(const float* probs, int32_t units, int32_t length, int64_t row_stride,
                               int64_t unit_stride, int32_t split, int32_t* counts_out, void* stream) {
     if (!probs || !counts_out || units < 1 || length < 1 || split < 0 || split > length) return SC_ERR_INVALID_ARG;

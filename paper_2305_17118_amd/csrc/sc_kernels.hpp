@@ -211,6 +211,8 @@ hipError_t launch_recompute_record(const Layout& L, const ReplayArgs& a, hipStre
 // full-attention mass held by the resident rows.
 hipError_t launch_persistence(const float* probs, int units, int length, long row_stride, long unit_stride,
                               int split, int32_t* counts, hipStream_t stream);
+// Pure read of `bytes` (a multiple of 32 MiB) from buf with 16-byte loads, 1024 workgroups.
+hipError_t launch_read_stream(const void* buf, size_t bytes, bool nontemporal, uint32_t* sink, hipStream_t stream);
 hipError_t launch_kept_mass(const Layout& L, int n, const float* full, long unit_stride, float* mass,
                             hipStream_t stream);
 

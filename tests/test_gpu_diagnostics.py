@@ -78,3 +78,25 @@ def test_kept_mass_matches_reference_and_explains_the_budgeted_scores():
     with pytest.raises(B.ScError) as e:
         B.sc_diag_persistence(pf.data_ptr(), U, 10, 4, 100, 5, mass.data_ptr())
     assert e.value.status == B.SC_ERR_INVALID_ARG
+
+
+def test_read_bandwidth_probe_checks_its_arguments_and_leaves_memory_alone():
+    """The pure-read reference launch: sizes that are no multiple of 32 MiB, null and misaligned
+    pointers are rejected; a valid call changes neither the buffer nor the sink."""
+    import ctypes as C
+
+    n = 32 << 20
+    buf = torch.arange(n // 4, dtype=torch.int32, device="cuda")
+    sink = torch.full((1,), 77, dtype=torch.int32, device="cuda")
+    keep = buf.clone()
+    f = B.lib().sc_diag_read_bandwidth
+    s = int(torch.cuda.current_stream().cuda_stream)
+    assert f(buf.data_ptr(), n - 16, 1, sink.data_ptr(), s) == B.SC_ERR_INVALID_ARG
+    assert f(buf.data_ptr(), 0, 1, sink.data_ptr(), s) == B.SC_ERR_INVALID_ARG
+    assert f(None, n, 1, sink.data_ptr(), s) == B.SC_ERR_INVALID_ARG
+    assert f(buf.data_ptr(), n, 1, None, s) == B.SC_ERR_INVALID_ARG
+    assert f(buf.data_ptr() + 4, n, 1, sink.data_ptr(), s) == B.SC_ERR_INVALID_ARG
+    for nt in (1, 0):
+        B.sc_diag_read_bandwidth(buf.data_ptr(), n, bool(nt), sink.data_ptr(), s)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, keep) and int(sink[0]) == 77
