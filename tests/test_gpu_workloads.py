@@ -8,7 +8,7 @@ must agree bit for bit at every compression.
 import pytest
 
 from paper_2305_17118_amd import binding as B
-from paper_2305_17118_amd.workloads import CONFIGS, KV_F16, KV_F32, Workload, sample_units
+from paper_2305_17118_amd.workloads import CONFIGS, KV_F16, KV_F32, KV_I4G64, Workload, sample_units
 
 from .parity_util import ParityRun
 
@@ -40,11 +40,13 @@ def test_workload_matches_oracle(idx, extra):
     assert run.cache.n <= wl.budget + 1
 
 
-@pytest.mark.parametrize("kv,d", [(KV_F32, 64), (KV_F16, 128)], ids=["f32", "f16"])
+@pytest.mark.parametrize("kv,d", [(KV_F32, 64), (KV_F16, 128), (KV_I4G64, 128), (KV_I4G64, 64)],
+                         ids=["f32", "f16", "i4-d128", "i4-d64"])
 def test_many_small_units_drawn_by_ticket(kv, d):
-    """2048 units and more: the last sixteenth of the units is not tied to a workgroup index
-    (workgroups draw tickets for them, surplus workgroups return).  Small caches, every step
-    compared on the first sequence, on scattered units and on units of the ticketed tail."""
+    """2048 units and more.  fp32/fp16 rows: the last sixteenth of the units is not tied to a
+    workgroup index (workgroups draw tickets for them, surplus workgroups return).  4-bit rows:
+    one wave per unit, which writes its output without the merge through LDS.  Small caches,
+    every step compared on the first sequence, on scattered units and on units of the tail."""
     wl = Workload("tickets", 90, 96, 32, d, kv, 40, 50, 32, 4, 16, 8)
     assert wl.units >= 2048
     tail = list(range(wl.units - wl.units // 16, wl.units, 37)) + [wl.units - 1]
