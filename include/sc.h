@@ -470,7 +470,9 @@ sc_status sc_diag_read_bandwidth(const void *buf, size_t bytes, int32_t nontempo
  *                    the wave's raw hardware-id register (wave slot, SIMD, ...) }
  * with `clock` the GPU's constant-rate counter (100 MHz, shared by all workgroups).  Each launch
  * overwrites the previous one's readings; results of the step are not affected.
- *   trace_out : device uint64 [U][4], 8-byte aligned; NULL switches the recording off */
+ *   trace_out : device uint64 [U][4], 8-byte aligned; NULL switches the recording off
+ * SC_ERR_UNSUPPORTED for a cache whose decode step shares a unit among several workgroups (at most
+ * 64 units of fp32/fp16 rows with a capacity of 512 slots or more). */
 sc_status sc_diag_trace(sc_cache *c, uint64_t *trace_out);
 
 /* Static description of a status code. */

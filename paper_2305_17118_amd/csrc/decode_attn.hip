@@ -73,6 +73,14 @@ struct AttnArgs {
     // n_tail (the rest return at once); the last to draw sets the counter back to zero.
     int32_t* ticket;
     int n_static, n_tail, n_ticket_wgs;
+    // Very few units with long caches (fp32/fp16 kernel): `split` workgroups share a unit's rows.
+    // Each publishes its share (acc[D], m, l; `share_stride` floats apart) and the raw scores of
+    // its rows, then counts itself in arrive[u]; the last to arrive merges the shares and runs the
+    // epilogue.  0: one workgroup per unit.
+    int split, share_stride;
+    float* shares;     // [U][8][share_stride]
+    float* raw;        // [U][C] raw scores
+    int32_t* arrive;   // [U], zero between launches
 };
 
 // Diagnostics (a.trace set): every workgroup reports when it started, when its K/V stream ended
@@ -308,11 +316,20 @@ __device__ __forceinline__ void store_through16(void* p, const uint4& v) {
     asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(d) : "memory");
 }
 
-template <typename T, int D, int NW, int UNR>
+// Loads of what another workgroup of this launch, possibly on another XCD, has published with
+// store_through: device-scope loads, which are not served from this XCD's own copy of the line.
+__device__ __forceinline__ float load_published(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <typename T, int D, int NW, int UNR, bool SPLIT>
 __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
     TraceClock clk;
     clk.start(a);
-    if (a.seq.off && !seq_apply(a, blockIdx.x)) return;
+    // SPLIT: a.split consecutive workgroups share one unit, each taking a contiguous range of rows
+    const int wg = SPLIT ? (int)blockIdx.x / a.split : (int)blockIdx.x;
+    const int part = SPLIT ? (int)blockIdx.x - wg * a.split : 0;
+    if (a.seq.off && !seq_apply(a, wg)) return;
     constexpr int EPL = 16 / (int)sizeof(T);  // elements per lane
     constexpr int LPR = D / EPL;              // lanes per row
     constexpr int RPW = 64 / LPR;             // rows per wave load
@@ -331,8 +348,8 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
     // to a workgroup index: twice as many workgroups as there are such units draw tickets, an XCD
     // that gets to its ticket workgroups early takes more of the units, and workgroups that draw
     // when none is left return.
-    int u = blockIdx.x;
-    if (a.ticket && u >= a.n_static) {
+    int u = wg;
+    if (!SPLIT && a.ticket && u >= a.n_static) {
         __shared__ int drawn;
         if (threadIdx.x == 0) {
             const int k = __hip_atomic_fetch_add(a.ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -359,7 +376,17 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
     // waited for: q, the new row (its owner only), the counters.
     F qr;
     qr.raw = *reinterpret_cast<const uint4*>((const T*)a.q + in_off);
-    const bool owner = (wv == 0) && (g == 0);  // Alg. 1 model update: who holds the new row
+    // Rows [lo, hi) are this workgroup's (all resident rows unless the unit is split; ranges start
+    // at multiples of 32 rows so that no two workgroups write scores into one 128-byte line); the
+    // new row belongs to the workgroup that has the last range.
+    int lo = 0, hi = nc;
+    if constexpr (SPLIT) {
+        const int per = ((nc + a.split - 1) / a.split + 31) / 32 * 32;
+        lo = part * per < nc ? part * per : nc;
+        hi = lo + per < nc ? lo + per : nc;
+    }
+    const bool last_part = !SPLIT || part == a.split - 1;
+    const bool owner = (wv == 0) && (g == 0) && last_part;  // Alg. 1 model update: who holds the new row
     if (a.q_keep && owner)  // Alg. 2 as printed replays this query at the next compressions
         *reinterpret_cast<uint4*>((T*)a.q_keep + (size_t)u * a.q_keep_stride + c * EPL) = qr.raw;
     F k_own, v_own;
@@ -401,25 +428,25 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
 
 #pragma unroll
     for (int i = 0; i < EPL; ++i) qf[i] = (float)qr.e[i] * a.qk_log2;
-    int base = wv * CHUNK;
-    for (; base + CHUNK <= nc; base += STRIDE) {
+    int base = lo + wv * CHUNK;
+    for (; base + CHUNK <= hi; base += STRIDE) {
         F kr[UNR], vr[UNR];
         load_full(kr, vr, base);
         take_full(kr, vr, base);
     }
-    if (base < nc) {  // ragged tail of this wave
+    if (base < hi) {  // ragged tail of this wave
         F kr[UNR], vr[UNR];
 #pragma unroll
         for (int x = 0; x < UNR; ++x) {
             const int j = base + x * RPW + g;
-            const uint32_t off = (j < nc ? (uint32_t)j : 0u) * ROWB + (uint32_t)c * 16u;
+            const uint32_t off = (j < hi ? (uint32_t)j : 0u) * ROWB + (uint32_t)c * 16u;
             kr[x].raw = load_stream16(Kb, off);
             vr[x].raw = load_stream16(Vb, off);
         }
 #pragma unroll
         for (int x = 0; x < UNR; ++x) {
             const int j = base + x * RPW + g;
-            take_row(kr[x], vr[x], j, j < nc);
+            take_row(kr[x], vr[x], j, j < hi);
         }
     }
     if (owner) {
@@ -432,7 +459,7 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
         }
         if (c == 0) a.pos[(size_t)u * a.C + nc] = a.pos_value;
     }
-    if (wv == 0) take_row(k_own, v_own, nc, owner);
+    if (wv == 0 && last_part) take_row(k_own, v_own, nc, owner);
     clk.streamed(a);
 
 #pragma unroll
@@ -446,8 +473,63 @@ __global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
         }
     }
     __syncthreads();
-    finish_unit<T, D, NW * 64, NW>(a, u, s_lds, part_m, part_l, part_acc, cpre);
-    clk.finish(a, u);
+    if constexpr (SPLIT) {
+        static_assert(NW >= 8, "the shares of up to 8 workgroups are merged in the per-wave LDS arrays");
+        __shared__ int arrived;
+        const int tid = threadIdx.x;
+        // 1. Publish this workgroup's share (its waves merged) and the raw scores of its rows,
+        //    written through to where every XCD sees them.
+        float M = part_m[0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) M = fmaxf(M, part_m[w]);
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) L += part_m[w] == -INFINITY ? 0.f : part_l[w] * fast_exp2(part_m[w] - M);
+        float* share = a.shares + ((size_t)u * 8 + part) * a.share_stride;
+        for (int ch = tid; ch < D; ch += NW * 64) {
+            float o = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+                o += part_m[w] == -INFINITY ? 0.f : part_acc[w * D + ch] * fast_exp2(part_m[w] - M);
+            store_through(share + ch, o);
+        }
+        if (tid == 0) {
+            store_through(share + D, M);  // -inf when the range holds no row
+            store_through(share + D + 1, L);
+        }
+        float* raw = a.raw + (size_t)u * a.C;
+        for (int j = lo + tid; j < hi; j += NW * 64) store_through(raw + j, s_lds[j]);
+        if (last_part && tid == 0) store_through(raw + nc, s_lds[nc]);
+        // 2. Once all of it has arrived in memory, count this workgroup in; all but the last leave.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) {
+            const int k = __hip_atomic_fetch_add(a.arrive + u, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (k == a.split - 1)  // ready for the next launch
+                __hip_atomic_store(a.arrive + u, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            arrived = k;
+        }
+        __syncthreads();
+        if (__builtin_amdgcn_readfirstlane(arrived) != a.split - 1) return;
+        // 3. The last to arrive: fetch the others' scores and all shares, then finish the unit as
+        //    a workgroup that had streamed all of it would (shares take the place of waves).
+        for (int j = tid; j < a.n; j += NW * 64)
+            if (j < lo || (j >= hi && !(last_part && j == nc))) s_lds[j] = load_published(raw + j);
+        for (int i = tid; i < 8 * D; i += NW * 64) {
+            const int p = i / D, ch = i - p * D;
+            part_acc[i] = p < a.split ? load_published(a.shares + ((size_t)u * 8 + p) * a.share_stride + ch) : 0.f;
+        }
+        if (tid < 8) {
+            const float* sh = a.shares + ((size_t)u * 8 + tid) * a.share_stride;
+            part_m[tid] = tid < a.split ? load_published(sh + D) : -INFINITY;
+            part_l[tid] = tid < a.split ? load_published(sh + D + 1) : 0.f;
+        }
+        __syncthreads();
+        finish_unit<T, D, NW * 64, 8>(a, u, s_lds, part_m, part_l, part_acc, cpre);
+    } else {
+        finish_unit<T, D, NW * 64, NW>(a, u, s_lds, part_m, part_l, part_acc, cpre);
+        clk.finish(a, u);
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1071,12 +1153,16 @@ __global__ void clear_u32_kernel(uint32_t* p, size_t n) {
 }
 
 template <typename T, int D, int UNR>
-hipError_t launch_rows(const AttnArgs& a, int grid, int nw, hipStream_t stream) {
+hipError_t launch_rows(const AttnArgs& a, int U, int grid, int nw, hipStream_t stream) {
     const size_t lds = ((size_t)a.C + 2 * nw + (size_t)nw * D) * sizeof(float);
+    if (a.split) {
+        attn_rows_kernel<T, D, 16, UNR, true><<<U * a.split, 1024, lds, stream>>>(a);
+        return hipGetLastError();
+    }
     switch (nw) {
-        case 4: attn_rows_kernel<T, D, 4, UNR><<<grid, 256, lds, stream>>>(a); break;
-        case 8: attn_rows_kernel<T, D, 8, UNR><<<grid, 512, lds, stream>>>(a); break;
-        default: attn_rows_kernel<T, D, 16, UNR><<<grid, 1024, lds, stream>>>(a); break;
+        case 4: attn_rows_kernel<T, D, 4, UNR, false><<<grid, 256, lds, stream>>>(a); break;
+        case 8: attn_rows_kernel<T, D, 8, UNR, false><<<grid, 512, lds, stream>>>(a); break;
+        default: attn_rows_kernel<T, D, 16, UNR, false><<<grid, 1024, lds, stream>>>(a); break;
     }
     return hipGetLastError();
 }
@@ -1178,12 +1264,18 @@ hipError_t launch_decode_step(const Layout& L, const StepArgs& s, hipStream_t st
         a.n_ticket_wgs = 2 * a.n_tail;
     }
     const int grid = a.n_static + a.n_ticket_wgs;
+    a.split = L.kv_dtype != KV_I4G64 ? L.split : 0;
+    a.share_stride = L.d + 32;  // acc[d], m, l, padded to whole 128-byte lines
+    a.shares = L.shares;
+    a.raw = reinterpret_cast<float*>(L.srcmap);  // idle between compressions, same size [U][C]
+    a.arrive = L.arrive;
+    if (a.split) a.trace = nullptr;  // (the clocks are per workgroup-is-a-unit)
     if (L.kv_dtype == KV_F32)
-        return L.d == 64 ? launch_rows<float, 64, 2>(a, grid, nw, stream)
-                         : launch_rows<float, 128, 2>(a, grid, nw, stream);
+        return L.d == 64 ? launch_rows<float, 64, 2>(a, L.U, grid, nw, stream)
+                         : launch_rows<float, 128, 2>(a, L.U, grid, nw, stream);
     if (L.kv_dtype == KV_F16)
-        return L.d == 64 ? launch_rows<_Float16, 64, 2>(a, grid, nw, stream)
-                         : launch_rows<_Float16, 128, 2>(a, grid, nw, stream);
+        return L.d == 64 ? launch_rows<_Float16, 64, 2>(a, L.U, grid, nw, stream)
+                         : launch_rows<_Float16, 128, 2>(a, L.U, grid, nw, stream);
     const int nw4 = pick_waves_i4(L.U);
     return L.d == 64 ? launch_i4<64, 4>(a, L.U, nw4, stream) : launch_i4_mfma<4>(a, L.U, nw4, stream);
 }
@@ -1192,6 +1284,7 @@ hipError_t launch_clear_counters(const Layout& L, hipStream_t stream) {
     const size_t words = L.W32 ? (size_t)L.U * L.W32 * L.C : (size_t)L.U * L.E * L.C / 2;  // C is even
     clear_u32_kernel<<<1024, 256, 0, stream>>>(reinterpret_cast<uint32_t*>(L.cnt), words);
     if (L.ticket) clear_u32_kernel<<<1, 64, 0, stream>>>(reinterpret_cast<uint32_t*>(L.ticket), 1);
+    if (L.arrive) clear_u32_kernel<<<1, 64, 0, stream>>>(reinterpret_cast<uint32_t*>(L.arrive), (size_t)L.U);
     return hipGetLastError();
 }
 

@@ -51,7 +51,8 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct Sizes {
     int32_t n_trig, C, E, W32;
     size_t row_bytes, meta_bytes;  // per K (or V) row
-    size_t off_K, off_V, off_Km, off_Vm, off_pos, off_cnt, off_qh, off_map, off_first, off_seq, total;
+    size_t off_K, off_V, off_Km, off_Vm, off_pos, off_cnt, off_qh, off_map, off_first, off_seq, off_shares, off_arrive, total;
+    int32_t split;  // workgroups per unit of a decode step (very few units with long caches), else 0
     bool recompute;
 };
 
@@ -104,6 +105,15 @@ sc_status derive(const sc_config* cfg, Sizes* s) {
     s->off_map = off;   off = align_up(off + rows * 4);
     s->off_first = off; off = align_up(off + (size_t)cfg->batch * cfg->heads * 4);
     s->off_seq = off;   off = align_up(off + ((size_t)cfg->batch + 2) * 4);  // table, step count, ticket counter
+    // Very few units with long caches leave most CUs idle with one workgroup per unit: the decode
+    // step then splits a unit's rows over 8 workgroups (up to 32 units) or 4 (up to 64), fp32/fp16
+    // rows only.  Measured on 32 heads x 1050 rows of fp16: 13.4 -> 10.7 us per step at batch 1,
+    // 14.0 -> 12.8 at batch 2; from 128 units on (and with 8 workgroups at 64 units) the merge
+    // costs more than the extra workgroups gain.
+    const int64_t units = (int64_t)cfg->batch * cfg->heads;
+    s->split = (cfg->kv_dtype == SC_KV_I4G64 || s->C < 512) ? 0 : units <= 32 ? 8 : units <= 64 ? 4 : 0;
+    s->off_shares = off; off = align_up(off + (s->split ? (size_t)units * 8 * (d + 32) * 4 : 0));
+    s->off_arrive = off; off = align_up(off + (s->split ? (size_t)units * 4 : 0));
     s->total = off;
     return SC_OK;
 }
@@ -228,6 +238,10 @@ sc::Layout view_of(const sc_cache* c, const sc::Layout& whole, int b0, int b1) {
     if (whole.Qh) L.Qh = static_cast<char*>(whole.Qh) + u0 * (size_t)whole.w * whole.d * elem_bytes(c->cfg);
     L.srcmap = whole.srcmap + u0 * C;
     L.first = whole.first + u0;
+    if (whole.shares) {
+        L.shares = whole.shares + u0 * 8 * ((size_t)whole.d + 32);
+        L.arrive = whole.arrive + u0;
+    }
     return L;
 }
 
@@ -416,6 +430,9 @@ sc_status sc_cache_create(const sc_config* cfg, void* dev_workspace, size_t byte
     L.srcmap = reinterpret_cast<int32_t*>(base + s.off_map);
     L.first = reinterpret_cast<int32_t*>(base + s.off_first);
     L.ticket = reinterpret_cast<int32_t*>(base + s.off_seq) + cfg->batch + 1;
+    L.split = s.split;
+    L.shares = s.split ? reinterpret_cast<float*>(base + s.off_shares) : nullptr;
+    L.arrive = s.split ? reinterpret_cast<int32_t*>(base + s.off_arrive) : nullptr;
     c->ragged = false;
     c->table_known = false;
     c->step = 0;
@@ -822,6 +839,7 @@ sc_status sc_cache_view(const sc_cache* c, const void** K, const void** V, const
 sc_status sc_diag_trace(sc_cache* c, uint64_t* trace_out) {
     if (!c) return SC_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(trace_out) % 8 != 0) return SC_ERR_INVALID_ARG;
+    if (trace_out && c->L.split) return SC_ERR_UNSUPPORTED;  // several workgroups per unit
     c->trace = reinterpret_cast<unsigned long long*>(trace_out);
     return SC_OK;
 }

@@ -27,6 +27,9 @@ struct Layout {
     int32_t* srcmap;  // [U][C] scratch written by select, read by compact
     int32_t* first;   // [U] scratch: first slot whose row moves
     int32_t* ticket;  // one counter, zero between launches: units of a decode launch handed out by ticket
+    int split;        // fp32/fp16 decode: workgroups per unit when there are very few units with long caches, else 0
+    float* shares;    // [U][8][d + 32] shares of a split step (srcmap doubles as its [U][C] raw scores)
+    int32_t* arrive;  // [U] workgroups of a split step that have published, zero between launches
 };
 
 // ---- Ragged batches: every sequence runs Alg. 1 on its own clock ----------------------------

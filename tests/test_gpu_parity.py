@@ -629,6 +629,8 @@ def test_prefill_can_be_captured_in_a_graph_and_replayed(kv):
     (1, 5, KV_F32, 128, 255),
     (2, 40, KV_F32, 64, 600),
     (1, 3, KV_F16, 64, 513),      # head size 64, capacity just above 512 slots
+    (2, 24, KV_F16, 128, 540),    # 48 units: four workgroups per unit
+    (1, 4, KV_F32, 64, 600),      # fp32 rows, eight workgroups per unit
 ])
 def test_few_units_with_many_rows(batch, heads, kv, d, budget):
     """Small batches with long caches (the shape of low-latency serving): a streamed prompt, then

@@ -337,25 +337,30 @@ def test_random_serving_trace_matches_oracle(seed):
     assert requests >= batch and run.stats["seq_steps"] > 100
 
 
-@pytest.mark.parametrize("kv", [KV_F16, KV_I4G64], ids=["f16", "i4"])
-def test_decode_step_replayed_from_a_graph_with_the_device_clock(kv):
+@pytest.mark.parametrize("kv,budget,plens,start,T", [
+    (KV_F16, 40, [30, 0, 17], 40, 260),
+    (KV_I4G64, 40, [30, 0, 17], 40, 260),
+    # capacity above 512 slots and six units: every unit's rows are shared by 8 workgroups whose
+    # arrival counters must be back at zero for every replay
+    (KV_F16, 520, [500, 470, 510], 512, 700),
+], ids=["f16", "i4", "f16-long"])
+def test_decode_step_replayed_from_a_graph_with_the_device_clock(kv, budget, plens, start, T):
     """With the step count kept on the device one captured sc_decode_step_ragged call is replayed
     for every step between compressions, and again after each (eager) compression, with the
     inputs rewritten in place; outputs and the final cache must equal, bit for bit, those of a
     twin cache stepped eagerly with the step count passed as an argument."""
-    wl = _wl("rag-graph", 3, 2, 128, kv, 40, 4, 24, 12, 0.05)
-    T, U, d = 260, wl.units, wl.head_dim
+    wl = _wl("rag-graph", 3, 2, 128, kv, budget, 4, 24, 12, 0.05)
+    U, d = wl.units, wl.head_dim
     q, k, v = (torch.from_numpy(a).cuda() for a in streams(wl, steps=T))
     cfg = B.make_config(wl.batch, wl.heads, d, kv, wl.budget, wl.recent, wl.history, wl.drop)
     eager, graphed = B.BudgetCache(cfg), B.BudgetCache(cfg)
-    plens = [30, 0, 17]
     for c in (eager, graphed):
         c.prefill_ragged(q, k, v, plens, T * d, None)
     graphed.device_clock(True)
     qs, ks, vs = (torch.empty(U, d, dtype=torch.float16, device="cuda") for _ in range(3))  # static inputs
     out_e = torch.empty(U, d, dtype=torch.float16, device="cuda")
     out_g = torch.empty_like(out_e)
-    start = 40  # stream position of the first decode step (past every prompt)
+    # `start`: stream position of the first decode step (past every prompt)
 
     def load(s):
         qs.copy_(q[:, s]); ks.copy_(k[:, s]); vs.copy_(v[:, s])
