@@ -322,8 +322,11 @@ __device__ __forceinline__ float load_published(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// (At most 80 scalar registers: with the 90 the split variant would otherwise take, two workgroups
+// of 16 waves no longer fit on a CU -- measured: the second 256 workgroups of a launch then
+// start only as the first ones leave.)
 template <typename T, int D, int NW, int UNR, bool SPLIT>
-__global__ void __launch_bounds__(NW * 64) attn_rows_kernel(AttnArgs a) {
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_num_sgpr(80))) attn_rows_kernel(AttnArgs a) {
     TraceClock clk;
     clk.start(a);
     // SPLIT: a.split consecutive workgroups share one unit, each taking a contiguous range of rows
