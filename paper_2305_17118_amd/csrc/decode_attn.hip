@@ -1176,8 +1176,7 @@ hipError_t launch_i4(const AttnArgs& a, int U, int nw, hipStream_t stream) {
     switch (nw) {
         case 1: attn_i4_kernel<D, 1, UNR><<<U, 64, lds, stream>>>(a); break;
         case 2: attn_i4_kernel<D, 2, UNR><<<U, 128, lds, stream>>>(a); break;
-        case 4: attn_i4_kernel<D, 4, UNR><<<U, 256, lds, stream>>>(a); break;
-        default: attn_i4_kernel<D, 8, UNR><<<U, 512, lds, stream>>>(a); break;
+        default: attn_i4_kernel<D, 4, UNR><<<U, 256, lds, stream>>>(a); break;
     }
     return hipGetLastError();
 }
@@ -1188,8 +1187,7 @@ hipError_t launch_i4_mfma(const AttnArgs& a, int U, int nw, hipStream_t stream) 
     switch (nw) {
         case 1: attn_i4_mfma_kernel<1, UNR><<<U, 64, lds, stream>>>(a); break;
         case 2: attn_i4_mfma_kernel<2, UNR><<<U, 128, lds, stream>>>(a); break;
-        case 4: attn_i4_mfma_kernel<4, UNR><<<U, 256, lds, stream>>>(a); break;
-        default: attn_i4_mfma_kernel<8, UNR><<<U, 512, lds, stream>>>(a); break;
+        default: attn_i4_mfma_kernel<4, UNR><<<U, 256, lds, stream>>>(a); break;
     }
     return hipGetLastError();
 }
@@ -1199,14 +1197,15 @@ hipError_t launch_i4_mfma(const AttnArgs& a, int U, int nw, hipStream_t stream) 
 // workgroups share a CU) is the fastest or within noise of it everywhere.
 int pick_waves(int /*U*/) { return 16; }
 
-// The 4-bit kernel is bound by ALU work, and the per-wave fixed work (query set-up, merging 32
-// accumulators, the epilogue) is paid once per wave: use as few waves per workgroup as still
-// give the chip about 3000 waves (measured: 1 wave per unit is fastest at 3072 units).
+// The 4-bit kernel's per-wave fixed work (query set-up, merging 32 accumulators, the epilogue)
+// is paid once per wave, so a unit gets as few waves as still fill the chip.  Measured on
+// MI355X on 96*b units of 570 rows (us per launch with 1 / 2 / 4 / 8 waves per unit):
+// 96 units 17.0 / 11.7 / 9.2 / 10.3, 192: 17.4 / 12.0 / 9.9 / 10.3, 384: 18.4 / 14.5 / 12.5 / 18.4,
+// 768: 19.6 / 16.5 / 17.8 / 28.3, 1536: 27.4 / 27.4 / 33.1 / 53.9, 3072: one wave.
 int pick_waves_i4(int U) {
-    if (U >= 2048) return 1;
-    if (U >= 1024) return 2;
-    if (U >= 512) return 4;
-    return 8;
+    if (U > 1536) return 1;
+    if (U > 512) return 2;
+    return 4;
 }
 
 }  // namespace

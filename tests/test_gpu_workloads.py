@@ -40,15 +40,17 @@ def test_workload_matches_oracle(idx, extra):
     assert run.cache.n <= wl.budget + 1
 
 
-@pytest.mark.parametrize("kv,d", [(KV_F32, 64), (KV_F16, 128), (KV_I4G64, 128), (KV_I4G64, 64)],
-                         ids=["f32", "f16", "i4-d128", "i4-d64"])
-def test_many_small_units_drawn_by_ticket(kv, d):
+@pytest.mark.parametrize("kv,d,batch", [(KV_F32, 64, 96), (KV_F16, 128, 96), (KV_I4G64, 128, 96), (KV_I4G64, 64, 96),
+                                       (KV_I4G64, 128, 24), (KV_I4G64, 64, 24)],
+                         ids=["f32", "f16", "i4-d128", "i4-d64", "i4-d128-768-units", "i4-d64-768-units"])
+def test_many_small_units_drawn_by_ticket(kv, d, batch):
     """2048 units and more.  fp32/fp16 rows: the last sixteenth of the units is not tied to a
     workgroup index (workgroups draw tickets for them, surplus workgroups return).  4-bit rows:
-    one wave per unit, which writes its output without the merge through LDS.  Small caches,
-    every step compared on the first sequence, on scattered units and on units of the tail."""
-    wl = Workload("tickets", 90, 96, 32, d, kv, 40, 50, 32, 4, 16, 8)
-    assert wl.units >= 2048
+    one wave per unit, which writes its output without the merge through LDS (768 units: two
+    waves per unit).  Small caches, every step compared on the first sequence, on scattered units
+    and on units of the tail."""
+    wl = Workload("tickets", 90, batch, 32, d, kv, 40, 50, 32, 4, 16, 8)
+    assert wl.units >= 2048 or batch == 24
     tail = list(range(wl.units - wl.units // 16, wl.units, 37)) + [wl.units - 1]
     run = ParityRun(wl, sel=sorted(set(_sample(wl, 16)) | set(tail)))
     st = run.run(check_rows_every=1)
