@@ -21,7 +21,10 @@
  *              workspace (256-byte aligned, sc_workspace_bytes() long) that must outlive
  *              the handle.  The handle owns host metadata only.
  *   Streams.   `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *              Calls only enqueue kernels on it and never synchronise.
+ *              Calls only enqueue kernels on it and never synchronise.  The work of two calls
+ *              on one handle must not overlap on the device (the workspace holds scratch and
+ *              counters that a launch expects to find as the previous one left them): use one
+ *              stream per handle, or order the streams.
  *   Errors.    Functions return sc_status; nothing throws, aborts or prints.  Every argument
  *              and state check is made before anything is enqueued or changed: on
  *              SC_ERR_INVALID_ARG, _WORKSPACE, _FULL, _STATE, _UNSUPPORTED, _SCRATCH and
