@@ -640,3 +640,34 @@ def test_few_units_with_many_rows(batch, heads, kv, d, budget):
     run.prefill(budget - 40, mode=B.SC_PREFILL_STREAMED)
     st = run.run()
     assert st["steps"] == wl.total and st["compressions"] >= 4
+
+
+def test_shared_units_give_the_same_bits_whoever_arrives_last():
+    """32 units with long caches: 8 workgroups share a unit's rows and the last of them to arrive
+    merges the shares.  Which one that is changes from launch to launch; the result must not:
+    two caches fed the same stream, and a third one whose steps are interleaved with unrelated
+    work, agree bit for bit on every output and on the final state."""
+    wl = _wl("shared-units", 1, 32, 128, KV_F16, 0, 700, 540, 9, 64, 32, 0.05)
+    T, U, d = 640, wl.units, wl.head_dim
+    q, k, v = (torch.from_numpy(a).cuda() for a in streams(wl, steps=T))
+    cfg = B.make_config(wl.batch, wl.heads, d, wl.kv_dtype, wl.budget, wl.recent, wl.history, wl.drop)
+    caches = [B.BudgetCache(cfg) for _ in range(3)]
+    for c in caches:
+        c.prefill(q, k, v, 500, T * d, None)
+    outs = [torch.empty(U, d, dtype=torch.float16, device="cuda") for _ in caches]
+    noise = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    comps = 0
+    for s in range(500, T):
+        qs, ks, vs = q[:, s].contiguous(), k[:, s].contiguous(), v[:, s].contiguous()
+        due = [c.decode_step(qs, ks, vs, o) for c, o in zip(caches[:2], outs[:2])]
+        noise.random_(0, 255)  # other kernels in between shift the third cache's timing
+        due.append(caches[2].decode_step(qs, ks, vs, outs[2]))
+        assert due[0] == due[1] == due[2]
+        assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2]), "step %d" % s
+        if due[0]:
+            for c in caches:
+                c.compress()
+            comps += 1
+    assert comps >= 3
+    for c in caches[1:]:
+        assert torch.equal(caches[0].cnt(), c.cnt()) and torch.equal(caches[0].pos(), c.pos())
