@@ -41,11 +41,11 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 # current run timed the same launches, else `traffic` is null.  Sources: profiles/*hbm_traffic*.
 MEASURED_TRAFFIC = {
     # workload: (steps, warmup, resident_rows_avg, bytes per launch)
-    "cfg1-small-fp32": (200, 5, 225.94, 1532354),
-    "cfg2-opt6.7b-fp16": (200, 5, 959.23, 254326400),
-    "cfg3-opt13b-fp16": (200, 5, 346.75, 462222441),
-    "cfg4-opt66b-fp16": (20, 5, 561.25, 2684549523),
-    "cfg5-opt175b-int4": (200, 5, 574.29, 265968755),
+    "cfg1-small-fp32": (200, 5, 225.94, 1536454),
+    "cfg2-opt6.7b-fp16": (200, 5, 959.23, 254336938),
+    "cfg3-opt13b-fp16": (200, 5, 346.75, 462236504),
+    "cfg4-opt66b-fp16": (20, 5, 561.25, 2684583668),
+    "cfg5-opt175b-int4": (200, 5, 574.29, 265963506),
 }
 
 
