@@ -1156,17 +1156,17 @@ __global__ void clear_u32_kernel(uint32_t* p, size_t n) {
 }
 
 template <typename T, int D, int UNR>
-hipError_t launch_rows(const AttnArgs& a, int U, int grid, int nw, hipStream_t stream) {
-    const size_t lds = ((size_t)a.C + 2 * nw + (size_t)nw * D) * sizeof(float);
-    if (a.split) {
-        attn_rows_kernel<T, D, 16, UNR, true><<<U * a.split, 1024, lds, stream>>>(a);
-        return hipGetLastError();
-    }
-    switch (nw) {
-        case 4: attn_rows_kernel<T, D, 4, UNR, false><<<grid, 256, lds, stream>>>(a); break;
-        case 8: attn_rows_kernel<T, D, 8, UNR, false><<<grid, 512, lds, stream>>>(a); break;
-        default: attn_rows_kernel<T, D, 16, UNR, false><<<grid, 1024, lds, stream>>>(a); break;
-    }
+hipError_t launch_rows(const AttnArgs& a, int U, int grid, hipStream_t stream) {
+    // 16 waves per workgroup with two K and two V loads in flight per lane (<= 64 VGPRs, so two
+    // workgroups share a CU): measured on MI355X over unit counts from 128 to 9216 and 350 to 1000
+    // resident rows, the fastest or within 2% of it everywhere (4 or 8 waves: up to 65% slower on
+    // few units, 1 to 2% on many).
+    constexpr int NW = 16;
+    const size_t lds = ((size_t)a.C + 2 * NW + (size_t)NW * D) * sizeof(float);
+    if (a.split)
+        attn_rows_kernel<T, D, NW, UNR, true><<<U * a.split, NW * 64, lds, stream>>>(a);
+    else
+        attn_rows_kernel<T, D, NW, UNR, false><<<grid, NW * 64, lds, stream>>>(a);
     return hipGetLastError();
 }
 
@@ -1191,11 +1191,6 @@ hipError_t launch_i4_mfma(const AttnArgs& a, int U, int nw, hipStream_t stream) 
     }
     return hipGetLastError();
 }
-
-// Waves per workgroup.  Measured on MI355X over unit counts from 512 to 9216 and 350 to 1000
-// resident rows: 16 waves with two K and two V loads in flight per lane (<= 64 VGPRs, so two
-// workgroups share a CU) is the fastest or within noise of it everywhere.
-int pick_waves(int /*U*/) { return 16; }
 
 // The 4-bit kernel's per-wave fixed work (query set-up, merging 32 accumulators, the epilogue)
 // is paid once per wave, so a unit gets as few waves as still fill the chip.  Measured on
@@ -1253,7 +1248,6 @@ hipError_t launch_decode_step(const Layout& L, const StepArgs& s, hipStream_t st
         const size_t per_unit = rows * (L.W32 ? 4 : 2) + (size_t)L.d * elem + 2 * row;
         a.through = (size_t)L.U * per_unit >= ((size_t)8 << 20);
     }
-    const int nw = pick_waves(L.U);
     // Tickets for the last sixteenth of the units once a launch has several generations of
     // workgroups per XCD (512 workgroups are resident at a time).
     a.ticket = nullptr;
@@ -1273,11 +1267,11 @@ hipError_t launch_decode_step(const Layout& L, const StepArgs& s, hipStream_t st
     a.arrive = L.arrive;
     if (a.split) a.trace = nullptr;  // (the clocks are per workgroup-is-a-unit)
     if (L.kv_dtype == KV_F32)
-        return L.d == 64 ? launch_rows<float, 64, 2>(a, L.U, grid, nw, stream)
-                         : launch_rows<float, 128, 2>(a, L.U, grid, nw, stream);
+        return L.d == 64 ? launch_rows<float, 64, 2>(a, L.U, grid, stream)
+                         : launch_rows<float, 128, 2>(a, L.U, grid, stream);
     if (L.kv_dtype == KV_F16)
-        return L.d == 64 ? launch_rows<_Float16, 64, 2>(a, L.U, grid, nw, stream)
-                         : launch_rows<_Float16, 128, 2>(a, L.U, grid, nw, stream);
+        return L.d == 64 ? launch_rows<_Float16, 64, 2>(a, L.U, grid, stream)
+                         : launch_rows<_Float16, 128, 2>(a, L.U, grid, stream);
     const int nw4 = pick_waves_i4(L.U);
     return L.d == 64 ? launch_i4<64, 4>(a, L.U, nw4, stream) : launch_i4_mfma<4>(a, L.U, nw4, stream);
 }
