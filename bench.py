@@ -510,7 +510,10 @@ def run_decode(wl, args, K, W, dev, streams_dev=None):
     rows_avg = (sum(sum(x) / len(x) for x in n_log) if args.ragged else sum(n_log)) / len(n_log)
     lifetimes = None
     if args.lifetimes and cursor[0] < T:
-        lifetimes = workgroup_lifetimes(B, handles[0], U, dev, lambda: one_step(0), args.lifetimes_dump)
+        try:
+            lifetimes = workgroup_lifetimes(B, handles[0], U, dev, lambda: one_step(0), args.lifetimes_dump)
+        except B.ScError as e:  # caches whose units are shared among workgroups record no per-unit clocks
+            print("bench.py: --lifetimes skipped (%s)" % e, file=sys.stderr)
     for c in caches:
         c.close()
     return {
